@@ -1,0 +1,500 @@
+/*
+ * fp64 CPU oracle for Lightning Attention (arXiv 2307.14995).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow,
+ * readable evaluation of what the GPU library must compute.  Only the test
+ * suite, the smoke check and the benchmark's "cpu_baseline" leg may call it.
+ * It shares no code, header, table or constant with the HIP library.
+ *
+ * What is computed (per batch b and head h, independent chains):
+ *
+ *   Definition (Sec. 3.2.1, "O = (Q K^T (.) M) V"; mask from Eq. 1 without
+ *   the LRPE phase, as Sec. 3.3 drops it):
+ *       O[t,:] = sum_{s=0..t} lambda_h^(t-s) * (q_t . k_s) * v_s
+ *   No 1/sqrt(d) scale, no softmax, no normaliser (Sec. 3.1.3: the attention
+ *   "eliminates the softmax and scaling operation").
+ *
+ *   Recurrent form (Sec. 3.3, Algorithm 2, the robust inference recurrence):
+ *       kv_0 = kv_in (zero if absent);  kv_t = lambda*kv_{t-1} + k_t^T v_t;
+ *       o_t = q_t kv_t
+ *
+ *   Gradients: derivative of the definition.  With A = (Q K^T) (.) M:
+ *       dV = A^T dO,  dA = (dO V^T) (.) M,  dQ = dA K,  dK = dA^T Q
+ *   (App. B, Algorithm 4, read with its evident misprints corrected: dK is
+ *   the product of dA^T with Q, dQ accumulates into dQ).
+ *
+ * Tensor layout: contiguous row-major [Bt, H, N, D] doubles; decay[H]
+ * doubles in [0,1]; states [Bt, H, D, D] with kv[i][j] = sum k[i]*v[j]
+ * (row = key feature, column = value feature).
+ *
+ * Parity pins live in tests/test_oracle_pins.py (brute force, closed forms,
+ * cumulative-sum special case, finite differences, Algorithm 1 == Algorithm 2
+ * identity of App. C, block-form re-association).  Nothing is "parity unpinned".
+ *
+ * Parallelism: OpenMP over (b,h) only.  No blocking or reordering beyond what
+ * each formula states.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef long long i64;
+
+/* lambda^n for integer n >= 0 with the convention 0^0 = 1 (M[t,t] = 1 for every
+ * lambda, Eq. 1 at s = t). */
+static double decay_pow(double lam, i64 n) {
+    if (n == 0) return 1.0;
+    return pow(lam, (double)n);
+}
+
+int ltn_oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void ltn_oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* ------------------------------------------------------------------------ */
+/* Forward, quadratic masked-matrix form: the definition written out.        */
+/* Sec. 3.2.1: O = (Q K^T (.) M) V,  M[t,s] = lambda^(t-s) for t >= s.       */
+/* ------------------------------------------------------------------------ */
+void ltn_oracle_fwd_quadratic(const double* q, const double* k, const double* v,
+                              const double* decay, int Bt, int H, i64 N, int D,
+                              double* o) {
+    const i64 chains = (i64)Bt * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        const double* Q = q + c * N * D;
+        const double* K = k + c * N * D;
+        const double* V = v + c * N * D;
+        double* O = o + c * N * D;
+        for (i64 t = 0; t < N; ++t) {
+            for (int j = 0; j < D; ++j) O[t * D + j] = 0.0;
+            for (i64 s = 0; s <= t; ++s) {
+                double dot = 0.0;
+                for (int i = 0; i < D; ++i) dot += Q[t * D + i] * K[s * D + i];
+                const double a = dot * decay_pow(lam, t - s); /* A[t,s] */
+                for (int j = 0; j < D; ++j) O[t * D + j] += a * V[s * D + j];
+            }
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Forward, recurrent form: Algorithm 2 (Sec. 3.3), token by token.          */
+/* kv_in / kv_out may be NULL (zero initial state / state not returned).     */
+/* ------------------------------------------------------------------------ */
+void ltn_oracle_fwd_recurrent(const double* q, const double* k, const double* v,
+                              const double* decay, const double* kv_in,
+                              int Bt, int H, i64 N, int D,
+                              double* o, double* kv_out) {
+    const i64 chains = (i64)Bt * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        const double* Q = q + c * N * D;
+        const double* K = k + c * N * D;
+        const double* V = v + c * N * D;
+        double* O = o + c * N * D;
+        double* kv = (double*)malloc(sizeof(double) * D * D);
+        if (kv_in) memcpy(kv, kv_in + c * D * D, sizeof(double) * D * D);
+        else memset(kv, 0, sizeof(double) * D * D);
+        for (i64 t = 0; t < N; ++t) {
+            /* kv_t = lambda kv_{t-1} + k_t^T v_t */
+            for (int i = 0; i < D; ++i)
+                for (int j = 0; j < D; ++j)
+                    kv[i * D + j] = lam * kv[i * D + j] + K[t * D + i] * V[t * D + j];
+            /* o_t = q_t kv_t */
+            for (int j = 0; j < D; ++j) {
+                double acc = 0.0;
+                for (int i = 0; i < D; ++i) acc += Q[t * D + i] * kv[i * D + j];
+                O[t * D + j] = acc;
+            }
+        }
+        if (kv_out) memcpy(kv_out + c * D * D, kv, sizeof(double) * D * D);
+        free(kv);
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Algorithm 1 (Sec. 3.3), the "origin" recurrence that factors the mask as   */
+/* (q lambda^t)(k lambda^-t).  Kept only to test the identity of App. C,      */
+/* kv_t = lambda^-t kvbar_t, and to show why no kernel may use this form.     */
+/* Tokens are numbered t = 1..N as in the paper.  Returns the final state.    */
+/* ------------------------------------------------------------------------ */
+void ltn_oracle_fwd_origin(const double* q, const double* k, const double* v,
+                           const double* decay, int Bt, int H, i64 N, int D,
+                           double* o, double* kv_out) {
+    const i64 chains = (i64)Bt * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        const double* Q = q + c * N * D;
+        const double* K = k + c * N * D;
+        const double* V = v + c * N * D;
+        double* O = o + c * N * D;
+        double* kv = (double*)calloc((size_t)D * D, sizeof(double));
+        for (i64 t = 1; t <= N; ++t) {
+            const double up = pow(lam, -(double)t);
+            const double dn = pow(lam, (double)t);
+            const i64 r = t - 1;
+            for (int i = 0; i < D; ++i)
+                for (int j = 0; j < D; ++j)
+                    kv[i * D + j] += K[r * D + i] * up * V[r * D + j];
+            for (int j = 0; j < D; ++j) {
+                double acc = 0.0;
+                for (int i = 0; i < D; ++i) acc += Q[r * D + i] * dn * kv[i * D + j];
+                O[r * D + j] = acc;
+            }
+        }
+        if (kv_out) memcpy(kv_out + c * D * D, kv, sizeof(double) * D * D);
+        free(kv);
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Forward, paper's tiling (App. B, Algorithm 3): for each query block i,     */
+/* loop over every key/value block j, A_ij = (Q_i K_j^T) (.) M_ij,            */
+/* O_i += A_ij V_j.  Br and Bc may differ and need not divide N (the paper    */
+/* assumes they do; a short last block is simply shorter).                    */
+/* ------------------------------------------------------------------------ */
+void ltn_oracle_fwd_tiled(const double* q, const double* k, const double* v,
+                          const double* decay, int Bt, int H, i64 N, int D,
+                          int Br, int Bc, double* o) {
+    const i64 chains = (i64)Bt * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        const double* Q = q + c * N * D;
+        const double* K = k + c * N * D;
+        const double* V = v + c * N * D;
+        double* O = o + c * N * D;
+        double* A = (double*)malloc(sizeof(double) * Br * Bc);
+        for (i64 i0 = 0; i0 < N; i0 += Br) {
+            const i64 nr = (N - i0 < Br) ? (N - i0) : Br;
+            for (i64 r = 0; r < nr; ++r)
+                for (int j = 0; j < D; ++j) O[(i0 + r) * D + j] = 0.0;
+            for (i64 j0 = 0; j0 < N; j0 += Bc) {
+                const i64 nc = (N - j0 < Bc) ? (N - j0) : Bc;
+                for (i64 r = 0; r < nr; ++r)
+                    for (i64 cc = 0; cc < nc; ++cc) {
+                        const i64 t = i0 + r, s = j0 + cc;
+                        double m = (t >= s) ? decay_pow(lam, t - s) : 0.0; /* M_ij */
+                        double dot = 0.0;
+                        for (int i = 0; i < D; ++i) dot += Q[t * D + i] * K[s * D + i];
+                        A[r * Bc + cc] = dot * m;
+                    }
+                for (i64 r = 0; r < nr; ++r)
+                    for (i64 cc = 0; cc < nc; ++cc)
+                        for (int j = 0; j < D; ++j)
+                            O[(i0 + r) * D + j] += A[r * Bc + cc] * V[(j0 + cc) * D + j];
+            }
+        }
+        free(A);
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Forward, block form: the intra-block masked tile plus the lambda-scaled    */
+/* product with a running D x D state.  This is the re-association that a     */
+/* blockwise kernel performs, evaluated literally in fp64:                     */
+/*   S = Q_i K_i^T; A = S (.) M_B; O_i = A V_i + diag(lambda^(r+1)) Q_i KV_i   */
+/*   KV_{i+1} = lambda^len KV_i + sum_c lambda^(len-1-c) k_c^T v_c             */
+/* with len the number of tokens in block i.  Only non-negative exponents.    */
+/* It validates the decay exponents before any kernel exists.                  */
+/* ------------------------------------------------------------------------ */
+void ltn_oracle_fwd_block(const double* q, const double* k, const double* v,
+                          const double* decay, const double* kv_in,
+                          int Bt, int H, i64 N, int D, int block,
+                          double* o, double* kv_out) {
+    const i64 chains = (i64)Bt * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        const double* Q = q + c * N * D;
+        const double* K = k + c * N * D;
+        const double* V = v + c * N * D;
+        double* O = o + c * N * D;
+        double* kv = (double*)malloc(sizeof(double) * D * D);
+        double* nk = (double*)malloc(sizeof(double) * D * D);
+        double* A = (double*)malloc(sizeof(double) * block * block);
+        if (kv_in) memcpy(kv, kv_in + c * D * D, sizeof(double) * D * D);
+        else memset(kv, 0, sizeof(double) * D * D);
+        for (i64 b0 = 0; b0 < N; b0 += block) {
+            const i64 len = (N - b0 < block) ? (N - b0) : block;
+            /* intra scores and mask */
+            for (i64 r = 0; r < len; ++r)
+                for (i64 cc = 0; cc < len; ++cc) {
+                    double dot = 0.0;
+                    for (int i = 0; i < D; ++i) dot += Q[(b0 + r) * D + i] * K[(b0 + cc) * D + i];
+                    A[r * block + cc] = (r >= cc) ? dot * decay_pow(lam, r - cc) : 0.0;
+                }
+            /* intra output + inter output */
+            for (i64 r = 0; r < len; ++r) {
+                const double lq = decay_pow(lam, r + 1);
+                for (int j = 0; j < D; ++j) {
+                    double intra = 0.0;
+                    for (i64 cc = 0; cc < len; ++cc) intra += A[r * block + cc] * V[(b0 + cc) * D + j];
+                    double inter = 0.0;
+                    for (int i = 0; i < D; ++i) inter += Q[(b0 + r) * D + i] * kv[i * D + j];
+                    O[(b0 + r) * D + j] = intra + lq * inter;
+                }
+            }
+            /* state update */
+            const double lb = decay_pow(lam, len);
+            for (int i = 0; i < D; ++i)
+                for (int j = 0; j < D; ++j) {
+                    double acc = 0.0;
+                    for (i64 cc = 0; cc < len; ++cc)
+                        acc += decay_pow(lam, len - 1 - cc) * K[(b0 + cc) * D + i] * V[(b0 + cc) * D + j];
+                    nk[i * D + j] = lb * kv[i * D + j] + acc;
+                }
+            memcpy(kv, nk, sizeof(double) * D * D);
+        }
+        if (kv_out) memcpy(kv_out + c * D * D, kv, sizeof(double) * D * D);
+        free(A); free(nk); free(kv);
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Backward, quadratic form: materialise A and dA per chain.                  */
+/*   dV = A^T dO;  dA = (dO V^T) (.) M;  dQ = dA K;  dK = dA^T Q              */
+/* ------------------------------------------------------------------------ */
+void ltn_oracle_bwd_quadratic(const double* q, const double* k, const double* v,
+                              const double* d_o, const double* decay,
+                              int Bt, int H, i64 N, int D,
+                              double* dq, double* dk, double* dv) {
+    const i64 chains = (i64)Bt * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        const double* Q = q + c * N * D;
+        const double* K = k + c * N * D;
+        const double* V = v + c * N * D;
+        const double* G = d_o + c * N * D;
+        double* DQ = dq + c * N * D;
+        double* DK = dk + c * N * D;
+        double* DV = dv + c * N * D;
+        memset(DQ, 0, sizeof(double) * N * D);
+        memset(DK, 0, sizeof(double) * N * D);
+        memset(DV, 0, sizeof(double) * N * D);
+        for (i64 t = 0; t < N; ++t)
+            for (i64 s = 0; s <= t; ++s) {
+                const double m = decay_pow(lam, t - s); /* M[t,s] */
+                double qk = 0.0, gv = 0.0;
+                for (int i = 0; i < D; ++i) {
+                    qk += Q[t * D + i] * K[s * D + i];
+                    gv += G[t * D + i] * V[s * D + i];
+                }
+                const double a = qk * m;  /* A[t,s]  */
+                const double da = gv * m; /* dA[t,s] */
+                for (int j = 0; j < D; ++j) {
+                    DV[s * D + j] += a * G[t * D + j];
+                    DQ[t * D + j] += da * K[s * D + j];
+                    DK[s * D + j] += da * Q[t * D + j];
+                }
+            }
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Backward, recurrent form.                                                   */
+/* Forward sweep re-runs Algorithm 2's state and emits dq_t = dO_t kv_t^T.    */
+/* Reverse sweep carries dkv (same shape as kv): for t = N-1..0               */
+/*   dkv = lambda dkv + q_t^T dO_t;  dk_t = v_t dkv^T;  dv_t = k_t dkv         */
+/* (state updated before use, so the diagonal term s = t is included).         */
+/* ------------------------------------------------------------------------ */
+void ltn_oracle_bwd_recurrent(const double* q, const double* k, const double* v,
+                              const double* d_o, const double* decay,
+                              int Bt, int H, i64 N, int D,
+                              double* dq, double* dk, double* dv) {
+    const i64 chains = (i64)Bt * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        const double* Q = q + c * N * D;
+        const double* K = k + c * N * D;
+        const double* V = v + c * N * D;
+        const double* G = d_o + c * N * D;
+        double* DQ = dq + c * N * D;
+        double* DK = dk + c * N * D;
+        double* DV = dv + c * N * D;
+        double* kv = (double*)calloc((size_t)D * D, sizeof(double));
+        for (i64 t = 0; t < N; ++t) {
+            for (int i = 0; i < D; ++i)
+                for (int j = 0; j < D; ++j)
+                    kv[i * D + j] = lam * kv[i * D + j] + K[t * D + i] * V[t * D + j];
+            for (int i = 0; i < D; ++i) {
+                double acc = 0.0;
+                for (int j = 0; j < D; ++j) acc += G[t * D + j] * kv[i * D + j];
+                DQ[t * D + i] = acc;
+            }
+        }
+        memset(kv, 0, sizeof(double) * D * D); /* now the suffix state dkv */
+        for (i64 t = N - 1; t >= 0; --t) {
+            for (int i = 0; i < D; ++i)
+                for (int j = 0; j < D; ++j)
+                    kv[i * D + j] = lam * kv[i * D + j] + Q[t * D + i] * G[t * D + j];
+            for (int i = 0; i < D; ++i) {
+                double acc = 0.0;
+                for (int j = 0; j < D; ++j) acc += V[t * D + j] * kv[i * D + j];
+                DK[t * D + i] = acc;
+            }
+            for (int j = 0; j < D; ++j) {
+                double acc = 0.0;
+                for (int i = 0; i < D; ++i) acc += K[t * D + i] * kv[i * D + j];
+                DV[t * D + j] = acc;
+            }
+        }
+        free(kv);
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Backward, block form (forward-order sweep for dQ with the prefix state,    */
+/* reverse-order sweep for dK, dV with the suffix state), evaluated literally */
+/* in fp64 with non-negative decay exponents only:                             */
+/*   forward sweep, block i with KV_i:                                         */
+/*     dA = (dO_i V_i^T) (.) M_B;  dQ_i = dA K_i + diag(lambda^(r+1)) dO_i KV_i^T */
+/*     KV_{i+1} as in the forward block form                                   */
+/*   reverse sweep, block i with dKV_i (suffix state as seen from the block's  */
+/*   end: sum over later tokens t of lambda^(t - end) q_t^T dO_t, end = first  */
+/*   token after the block):                                                    */
+/*     A = (Q_i K_i^T) (.) M_B                                                  */
+/*     dV_i = A^T dO_i + diag(lambda^(len-c)) K_i dKV_i                         */
+/*     dK_i = dA^T Q_i + diag(lambda^(len-c)) V_i dKV_i^T                       */
+/*     dKV_{i-1} = lambda^len dKV_i + sum_r lambda^r q_r^T dO_r                 */
+/* ------------------------------------------------------------------------ */
+void ltn_oracle_bwd_block(const double* q, const double* k, const double* v,
+                          const double* d_o, const double* decay,
+                          int Bt, int H, i64 N, int D, int block,
+                          double* dq, double* dk, double* dv) {
+    const i64 chains = (i64)Bt * H;
+    const i64 T = (N + block - 1) / block;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        const double* Q = q + c * N * D;
+        const double* K = k + c * N * D;
+        const double* V = v + c * N * D;
+        const double* G = d_o + c * N * D;
+        double* DQ = dq + c * N * D;
+        double* DK = dk + c * N * D;
+        double* DV = dv + c * N * D;
+        double* st = (double*)calloc((size_t)D * D, sizeof(double));
+        double* nx = (double*)malloc(sizeof(double) * D * D);
+        double* A = (double*)malloc(sizeof(double) * block * block);
+        double* dA = (double*)malloc(sizeof(double) * block * block);
+        /* forward-order sweep: dQ */
+        for (i64 ib = 0; ib < T; ++ib) {
+            const i64 b0 = ib * block;
+            const i64 len = (N - b0 < block) ? (N - b0) : block;
+            for (i64 r = 0; r < len; ++r)
+                for (i64 cc = 0; cc < len; ++cc) {
+                    double gv = 0.0;
+                    for (int j = 0; j < D; ++j) gv += G[(b0 + r) * D + j] * V[(b0 + cc) * D + j];
+                    dA[r * block + cc] = (r >= cc) ? gv * decay_pow(lam, r - cc) : 0.0;
+                }
+            for (i64 r = 0; r < len; ++r) {
+                const double lq = decay_pow(lam, r + 1);
+                for (int i = 0; i < D; ++i) {
+                    double intra = 0.0;
+                    for (i64 cc = 0; cc < len; ++cc) intra += dA[r * block + cc] * K[(b0 + cc) * D + i];
+                    double inter = 0.0;
+                    for (int j = 0; j < D; ++j) inter += G[(b0 + r) * D + j] * st[i * D + j];
+                    DQ[(b0 + r) * D + i] = intra + lq * inter;
+                }
+            }
+            const double lb = decay_pow(lam, len);
+            for (int i = 0; i < D; ++i)
+                for (int j = 0; j < D; ++j) {
+                    double acc = 0.0;
+                    for (i64 cc = 0; cc < len; ++cc)
+                        acc += decay_pow(lam, len - 1 - cc) * K[(b0 + cc) * D + i] * V[(b0 + cc) * D + j];
+                    nx[i * D + j] = lb * st[i * D + j] + acc;
+                }
+            memcpy(st, nx, sizeof(double) * D * D);
+        }
+        /* reverse-order sweep: dK, dV */
+        memset(st, 0, sizeof(double) * D * D);
+        for (i64 ib = T - 1; ib >= 0; --ib) {
+            const i64 b0 = ib * block;
+            const i64 len = (N - b0 < block) ? (N - b0) : block;
+            for (i64 r = 0; r < len; ++r)
+                for (i64 cc = 0; cc < len; ++cc) {
+                    double qk = 0.0, gv = 0.0;
+                    for (int i = 0; i < D; ++i) {
+                        qk += Q[(b0 + r) * D + i] * K[(b0 + cc) * D + i];
+                        gv += G[(b0 + r) * D + i] * V[(b0 + cc) * D + i];
+                    }
+                    const double m = (r >= cc) ? decay_pow(lam, r - cc) : 0.0;
+                    A[r * block + cc] = qk * m;
+                    dA[r * block + cc] = gv * m;
+                }
+            for (i64 cc = 0; cc < len; ++cc) {
+                const double lk = decay_pow(lam, len - cc);
+                for (int j = 0; j < D; ++j) {
+                    double intra = 0.0;
+                    for (i64 r = 0; r < len; ++r) intra += A[r * block + cc] * G[(b0 + r) * D + j];
+                    double inter = 0.0;
+                    for (int i = 0; i < D; ++i) inter += K[(b0 + cc) * D + i] * st[i * D + j];
+                    DV[(b0 + cc) * D + j] = intra + lk * inter;
+                }
+                for (int i = 0; i < D; ++i) {
+                    double intra = 0.0;
+                    for (i64 r = 0; r < len; ++r) intra += dA[r * block + cc] * Q[(b0 + r) * D + i];
+                    double inter = 0.0;
+                    for (int j = 0; j < D; ++j) inter += V[(b0 + cc) * D + j] * st[i * D + j];
+                    DK[(b0 + cc) * D + i] = intra + lk * inter;
+                }
+            }
+            const double lb = decay_pow(lam, len);
+            for (int i = 0; i < D; ++i)
+                for (int j = 0; j < D; ++j) {
+                    double acc = 0.0;
+                    for (i64 r = 0; r < len; ++r)
+                        acc += decay_pow(lam, r) * Q[(b0 + r) * D + i] * G[(b0 + r) * D + j];
+                    nx[i * D + j] = lb * st[i * D + j] + acc;
+                }
+            memcpy(st, nx, sizeof(double) * D * D);
+        }
+        free(dA); free(A); free(nx); free(st);
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* One decode step: a single iteration of Algorithm 2 on a caller-held state. */
+/* q,k,v,o: [Bt,H,D]; kv: [Bt,H,D,D], updated in place, then read:            */
+/*   kv = lambda kv + k^T v;  o = q kv                                         */
+/* ------------------------------------------------------------------------ */
+void ltn_oracle_decode_step(const double* q, const double* k, const double* v,
+                            const double* decay, int Bt, int H, int D,
+                            double* kv, double* o) {
+    const i64 chains = (i64)Bt * H;
+#pragma omp parallel for schedule(static)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        double* S = kv + c * D * D;
+        for (int i = 0; i < D; ++i)
+            for (int j = 0; j < D; ++j)
+                S[i * D + j] = lam * S[i * D + j] + k[c * D + i] * v[c * D + j];
+        for (int j = 0; j < D; ++j) {
+            double acc = 0.0;
+            for (int i = 0; i < D; ++i) acc += q[c * D + i] * S[i * D + j];
+            o[c * D + j] = acc;
+        }
+    }
+}

@@ -1,0 +1,199 @@
+"""ctypes loader for the fp64 CPU oracle of Lightning Attention (arXiv 2307.14995).
+
+TEST INFRASTRUCTURE ONLY: the test suite, the smoke check and the benchmark's
+``cpu_baseline`` leg may import this module; the GPU library never does, and
+this module never imports the GPU package.
+
+Every function takes array-likes (numpy arrays, or torch CPU tensors of any
+float dtype, bf16 included), widens them exactly to float64 and returns float64
+numpy arrays.  Tensor layout is ``[Bt, H, N, D]``; ``decay`` is ``[H]``; states
+are ``[Bt, H, D, D]`` with rows indexed by the key feature.
+
+The formulas are in ``ltn_oracle.c``; each entry below names the passage of the
+paper it follows.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ltn_oracle.c")
+_LIB = os.path.join(_HERE, "libltn_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (seconds).  Returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+               "-fno-fast-math", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ci, cl = ctypes.c_int, ctypes.c_longlong
+        lib.ltn_oracle_num_threads.restype = ci
+        lib.ltn_oracle_set_num_threads.argtypes = [ci]
+        lib.ltn_oracle_fwd_quadratic.argtypes = [dp, dp, dp, dp, ci, ci, cl, ci, dp]
+        lib.ltn_oracle_fwd_recurrent.argtypes = [dp, dp, dp, dp, dp, ci, ci, cl, ci, dp, dp]
+        lib.ltn_oracle_fwd_origin.argtypes = [dp, dp, dp, dp, ci, ci, cl, ci, dp, dp]
+        lib.ltn_oracle_fwd_tiled.argtypes = [dp, dp, dp, dp, ci, ci, cl, ci, ci, ci, dp]
+        lib.ltn_oracle_fwd_block.argtypes = [dp, dp, dp, dp, dp, ci, ci, cl, ci, ci, dp, dp]
+        lib.ltn_oracle_bwd_quadratic.argtypes = [dp, dp, dp, dp, dp, ci, ci, cl, ci, dp, dp, dp]
+        lib.ltn_oracle_bwd_recurrent.argtypes = [dp, dp, dp, dp, dp, ci, ci, cl, ci, dp, dp, dp]
+        lib.ltn_oracle_bwd_block.argtypes = [dp, dp, dp, dp, dp, ci, ci, cl, ci, ci, dp, dp, dp]
+        lib.ltn_oracle_decode_step.argtypes = [dp, dp, dp, dp, ci, ci, ci, dp, dp]
+        for name in ("fwd_quadratic", "fwd_recurrent", "fwd_origin", "fwd_tiled", "fwd_block",
+                     "bwd_quadratic", "bwd_recurrent", "bwd_block", "decode_step",
+                     "set_num_threads"):
+            getattr(lib, "ltn_oracle_" + name).restype = None
+        _lib = lib
+    return _lib
+
+
+def _f64(x) -> np.ndarray:
+    """Exact widening to a contiguous float64 numpy array."""
+    if hasattr(x, "detach"):  # torch tensor (numpy cannot hold bf16)
+        x = x.detach().cpu().double().numpy()
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _shape4(q, k, v):
+    assert q.ndim == 4 and q.shape == k.shape == v.shape, "expect [Bt,H,N,D] tensors of one shape"
+    return q.shape
+
+
+def num_threads() -> int:
+    return int(_load().ltn_oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().ltn_oracle_set_num_threads(int(n))
+
+
+def fwd_quadratic(q, k, v, decay):
+    """Sec. 3.2.1 definition O = (Q K^T (.) M) V, M[t,s] = lambda^(t-s), t >= s."""
+    q, k, v, decay = _f64(q), _f64(k), _f64(v), _f64(decay)
+    Bt, H, N, D = _shape4(q, k, v)
+    assert decay.shape == (H,)
+    o = np.empty_like(q)
+    _load().ltn_oracle_fwd_quadratic(_p(q), _p(k), _p(v), _p(decay), Bt, H, N, D, _p(o))
+    return o
+
+
+def fwd_recurrent(q, k, v, decay, kv_in=None, return_state=False):
+    """Sec. 3.3 Algorithm 2: kv = lambda kv + k^T v; o = q kv, token by token."""
+    q, k, v, decay = _f64(q), _f64(k), _f64(v), _f64(decay)
+    Bt, H, N, D = _shape4(q, k, v)
+    assert decay.shape == (H,)
+    kvi = None if kv_in is None else _f64(kv_in)
+    if kvi is not None:
+        assert kvi.shape == (Bt, H, D, D)
+    o = np.empty_like(q)
+    kvo = np.empty((Bt, H, D, D), dtype=np.float64)
+    _load().ltn_oracle_fwd_recurrent(_p(q), _p(k), _p(v), _p(decay), _p(kvi), Bt, H, N, D,
+                                     _p(o), _p(kvo))
+    return (o, kvo) if return_state else o
+
+
+def fwd_origin(q, k, v, decay):
+    """Sec. 3.3 Algorithm 1 (the overflow-prone factorisation); returns (o, kv_N)."""
+    q, k, v, decay = _f64(q), _f64(k), _f64(v), _f64(decay)
+    Bt, H, N, D = _shape4(q, k, v)
+    o = np.empty_like(q)
+    kvo = np.empty((Bt, H, D, D), dtype=np.float64)
+    with np.errstate(all="ignore"):
+        _load().ltn_oracle_fwd_origin(_p(q), _p(k), _p(v), _p(decay), Bt, H, N, D, _p(o), _p(kvo))
+    return o, kvo
+
+
+def fwd_tiled(q, k, v, decay, Br, Bc):
+    """App. B Algorithm 3: quadratic (i, j) tile loops with block sizes Br, Bc."""
+    q, k, v, decay = _f64(q), _f64(k), _f64(v), _f64(decay)
+    Bt, H, N, D = _shape4(q, k, v)
+    o = np.empty_like(q)
+    _load().ltn_oracle_fwd_tiled(_p(q), _p(k), _p(v), _p(decay), Bt, H, N, D, int(Br), int(Bc), _p(o))
+    return o
+
+
+def fwd_block(q, k, v, decay, block, kv_in=None, return_state=False):
+    """Blockwise re-association: masked intra tile + decayed running-state term."""
+    q, k, v, decay = _f64(q), _f64(k), _f64(v), _f64(decay)
+    Bt, H, N, D = _shape4(q, k, v)
+    kvi = None if kv_in is None else _f64(kv_in)
+    o = np.empty_like(q)
+    kvo = np.empty((Bt, H, D, D), dtype=np.float64)
+    _load().ltn_oracle_fwd_block(_p(q), _p(k), _p(v), _p(decay), _p(kvi), Bt, H, N, D, int(block),
+                                 _p(o), _p(kvo))
+    return (o, kvo) if return_state else o
+
+
+def _bwd(fn, q, k, v, d_o, decay, *extra):
+    q, k, v, d_o, decay = _f64(q), _f64(k), _f64(v), _f64(d_o), _f64(decay)
+    Bt, H, N, D = _shape4(q, k, v)
+    assert d_o.shape == q.shape and decay.shape == (H,)
+    dq, dk, dv = np.empty_like(q), np.empty_like(q), np.empty_like(q)
+    fn(_p(q), _p(k), _p(v), _p(d_o), _p(decay), Bt, H, N, D, *extra, _p(dq), _p(dk), _p(dv))
+    return dq, dk, dv
+
+
+def bwd_quadratic(q, k, v, d_o, decay):
+    """Derivative of the definition: dV = A^T dO, dA = (dO V^T)(.)M, dQ = dA K, dK = dA^T Q."""
+    return _bwd(_load().ltn_oracle_bwd_quadratic, q, k, v, d_o, decay)
+
+
+def bwd_recurrent(q, k, v, d_o, decay):
+    """Prefix-state sweep for dQ, reverse suffix-state sweep for dK and dV."""
+    return _bwd(_load().ltn_oracle_bwd_recurrent, q, k, v, d_o, decay)
+
+
+def bwd_block(q, k, v, d_o, decay, block):
+    """Blockwise backward (forward-order sweep for dQ, reverse-order sweep for dK, dV)."""
+    return _bwd(_load().ltn_oracle_bwd_block, q, k, v, d_o, decay, int(block))
+
+
+def decode_step(q, k, v, kv, decay):
+    """One iteration of Algorithm 2 on a given state; returns (o, new_kv)."""
+    q, k, v, decay = _f64(q), _f64(k), _f64(v), _f64(decay)
+    kv = _f64(kv).copy()
+    Bt, H, D = q.shape
+    assert kv.shape == (Bt, H, D, D) and decay.shape == (H,)
+    o = np.empty_like(q)
+    _load().ltn_oracle_decode_step(_p(q), _p(k), _p(v), _p(decay), Bt, H, D, _p(kv), _p(o))
+    return o, kv
+
+
+def rel_l2(x, ref) -> float:
+    """||x - ref||_2 / ||ref||_2 in fp64 over the whole tensor (0 if both are zero)."""
+    x, ref = _f64(x), _f64(ref)
+    den = float(np.linalg.norm(ref.ravel()))
+    num = float(np.linalg.norm((x - ref).ravel()))
+    if den == 0.0:
+        return 0.0 if num == 0.0 else float("inf")
+    return num / den
+
+
+def max_rel_l2(x, ref) -> float:
+    """Maximum of rel_l2 over the whole tensor and over every (b, h) slice."""
+    x, ref = _f64(x), _f64(ref)
+    worst = rel_l2(x, ref)
+    if x.ndim >= 3:
+        for b in range(x.shape[0]):
+            for h in range(x.shape[1]):
+                worst = max(worst, rel_l2(x[b, h], ref[b, h]))
+    return worst
