@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the Lightning Attention hot path on one MI355X.
+
+One "step" = one forward + one backward call of the library on the headline workload
+(7B-shaped layer: Bt=4, H=32, N=8192, D=128, bf16 tensors, fp32 accumulation), with
+all tensors resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3_7b|cfg2_385m|cfg_1b]
+                  [--no-cpu-baseline] [--report]   (--report adds the other workloads to stderr)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
+
+
+def flops_per_token_head(D: int, B: int):
+    """FLOP conventions per token-head (one multiply or one add = 1 FLOP), fwd+bwd."""
+    return {
+        "F_min": 14 * D * D,                               # recurrent form, block independent
+        "F_alg": 14 * D * D + 7 * (B + 1) * D,             # blockwise method, causal half of each tile
+        # what the kernels issue: four passes (fwd + three gradient passes), each 4 D^2 for the
+        # state products plus, per 64-token block at a two-way value-column split, 10 of 16
+        # score tiles twice and 12 of 16 score-times-value tiles once
+        "F_exec": 16 * D * D + 16 * B * D,
+    }
+
+
+def algorithmic_bytes_per_token_head(D: int, esize: int):
+    """Ideal HBM traffic: fwd reads Q,K,V writes O; bwd reads Q,K,V,dO writes dQ,dK,dV."""
+    return {"fwd": 4 * D * esize, "bwd": 7 * D * esize}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3_7b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--report", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the attention path has no collective "
+              "inside it and no multi-GPU code is part of it); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2307_14995_amd as ltn
+    from paper_2307_14995_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    ltn.load_library()
+
+    w = synth.CONFIGS[args.workload]
+    esize = 2 if w.dtype == torch.bfloat16 else 4
+    block = w.block or ltn.ltn_attn_pick_block(w.D, w.dtype)
+    q, k, v = synth.make_qkv(w.Bt, w.H, w.N, w.D, w.dtype, w.seed)
+    d_o = synth.make_do(w.Bt, w.H, w.N, w.D, w.dtype, w.seed)
+    decay = synth.decay_bench_rule(w.H)
+    qd, kd, vd, gd, dd = (t.to(dev) for t in (q, k, v, d_o, decay))
+    o = torch.empty_like(qd)
+    grads = tuple(torch.empty_like(qd) for _ in range(3))
+
+    def step():
+        ltn.ltn_attn_fwd(qd, kd, vd, dd, block=w.block, out=o)
+        ltn.ltn_attn_bwd(qd, kd, vd, gd, dd, block=w.block, out=grads)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # Timed region: exactly K steps; HIP events on the stream the kernels run on
+    # (torch's current stream is the one handed to the library).
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_wall0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        ltn.ltn_attn_fwd(qd, kd, vd, dd, block=w.block, out=o)
+        ev[i][1].record()
+        ltn.ltn_attn_bwd(qd, kd, vd, gd, dd, block=w.block, out=grads)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_wall0) * 1e3
+    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    ms_per_step = wall_ms / args.steps
+
+    token_heads = w.Bt * w.H * w.N
+    tokens = w.Bt * w.N
+    tokens_per_s = tokens / (ms_per_step * 1e-3)
+    fl = flops_per_token_head(w.D, block)
+    ab = algorithmic_bytes_per_token_head(w.D, esize)
+    tflops = {n: f * token_heads / (ms_per_step * 1e-3) / 1e12 for n, f in fl.items()}
+
+    # Dominant kernel: the backward launch (three gradient passes in one kernel).
+    bwd_bytes = ab["bwd"] * token_heads
+    achieved = bwd_bytes / (bwd_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": "pass_bf16_kernel (backward launch: dQ, dK, dV passes)",
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "kernel_ms": round(bwd_ms, 4),
+        "fwd_kernel_ms": round(fwd_ms, 4),
+        "fwd_achieved_GBs": round(ab["fwd"] * token_heads / (fwd_ms * 1e-3) / 1e9, 1),
+    }
+
+    out = {
+        "metric": "Lightning Attention fwd+bwd tokens/s (7B-shaped layer: Bt=4, H=32, N=8192, D=128)"
+                  if args.workload == "cfg3_7b" else f"Lightning Attention fwd+bwd tokens/s ({w.name})",
+        "value": round(tokens_per_s, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == torch.bfloat16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "Bt": w.Bt, "H": w.H, "N": w.N, "D": w.D, "block": block,
+                   "pass": "fwd+bwd", "decay": "lambda_h=exp(-2^(-8(h+1)/H))"},
+        "tflops": {n: round(x, 1) for n, x in tflops.items()},
+        "mfma_peak_frac": {n: round(x / MFMA_BF16_PEAK_TFLOPS, 4) for n, x in tflops.items()},
+        "token_heads_per_s": round(token_heads / (ms_per_step * 1e-3), 1),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, q, k, v, d_o, decay)
+    if args.report:
+        extended_report(ltn, synth, torch, dev)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def cpu_baseline(w, q, k, v, d_o, decay):
+    """The fp64 oracle (recurrent form, as it stands) timed on the host cores on a bounded
+    sample of the same workload: whole (b,h) chains at full N, one per OpenMP thread."""
+    from oracle import ltn_oracle as orc
+    cores = orc.num_threads()
+    n_chains = min(w.Bt * w.H, cores)
+    # sample: the first n_chains heads of batch 0 (heads differ only in decay)
+    hs = min(w.H, n_chains)
+    bs = max(1, n_chains // hs)
+    sl = (slice(0, bs), slice(0, hs))
+    qs, ks, vs, gs, ds = q[sl], k[sl], v[sl], d_o[sl], decay[:hs]
+    t0 = time.perf_counter()
+    orc.fwd_recurrent(qs, ks, vs, ds)
+    orc.bwd_recurrent(qs, ks, vs, gs, ds)
+    dt = time.perf_counter() - t0
+    token_heads = bs * hs * w.N
+    return {
+        "value": round(token_heads / dt / w.H, 1),
+        "unit": "tokens/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"{bs * hs} of {w.Bt * w.H} (batch,head) chains at full N={w.N}, fwd+bwd recurrent fp64, "
+                  f"{dt:.1f} s; scaled by token-heads to the {w.H}-head layer",
+        "seconds": round(dt, 2),
+    }
+
+
+def extended_report(ltn, synth, torch, dev):
+    """Other workloads (not the bench line): printed to stderr as JSON lines."""
+    def time_call(fn, n=10, warm=3):
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    shapes = [("cfg2_385m", 8, 8, 2048), ("cfg_1b", 8, 16, 2048), ("cfg3_7b", 4, 32, 8192)]
+    shapes += [(f"long_N{n}", 1, 32, n) for n in synth.LONG_CONTEXT_N]
+    D = 128
+    for name, Bt, H, N in shapes:
+        q, k, v = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
+                   for _ in range(3))
+        g = torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        dd = synth.decay_bench_rule(H).to(dev)
+        o = torch.empty_like(q)
+        gr = tuple(torch.empty_like(q) for _ in range(3))
+        f = time_call(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o))
+        b = time_call(lambda: ltn.ltn_attn_bwd(q, k, v, g, dd, out=gr))
+        th = Bt * H * N
+        print(json.dumps({"workload": name, "Bt": Bt, "H": H, "N": N, "fwd_ms": round(f, 4), "bwd_ms": round(b, 4),
+                          "tokens_per_s": round(Bt * N / ((f + b) * 1e-3), 1),
+                          "fwd_GBs": round(4 * D * 2 * th / (f * 1e-3) / 1e9, 1),
+                          "bwd_GBs": round(7 * D * 2 * th / (b * 1e-3) / 1e9, 1),
+                          "F_alg_TFLOPs": round((14 * D * D + 7 * 65 * D) * th / ((f + b) * 1e-3) / 1e12, 1)}),
+              file=sys.stderr, flush=True)
+        del q, k, v, g, o, gr
+    c = synth.DECODE
+    Bt, H = c["Bt"], c["H"]
+    kv = torch.zeros(Bt, H, D, D, device=dev)
+    q1, k1, v1 = (torch.randn(Bt, H, D, device=dev).to(torch.bfloat16) for _ in range(3))
+    dd = synth.decay_bench_rule(H).to(dev)
+    o1 = torch.empty_like(q1)
+    t = time_call(lambda: ltn.ltn_attn_decode_step(q1, k1, v1, kv, dd, out=o1), n=512, warm=20)
+    print(json.dumps({"workload": "decode_cfg5", "Bt": Bt, "H": H, "us_per_step": round(t * 1e3, 2),
+                      "state_GBs": round(2 * Bt * H * D * D * 4 / (t * 1e-3) / 1e9, 1),
+                      "batch_tokens_per_s": round(Bt / (t * 1e-3), 1)}), file=sys.stderr, flush=True)
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,133 @@
+/*
+ * ltn_attn.h -- C ABI of the MI355X (gfx950) Lightning Attention library.
+ *
+ * Lightning Attention is causal linear attention with a per-head exponential
+ * decay (arXiv 2307.14995, Sec. 3.2.1; decay mask from Eq. 1 without the LRPE
+ * phase, as Sec. 3.3 drops it):
+ *
+ *     O = ((Q K^T) (.) M_h) V,   M_h[t,s] = lambda_h^(t-s) for t >= s, else 0,
+ *
+ * with no 1/sqrt(d) scale, no softmax and no normaliser (Sec. 3.1.3).  The
+ * library evaluates it blockwise: a masked intra-block tile product plus a
+ * decay-scaled product with a running D x D state, the block form of the
+ * recurrence  kv_t = lambda kv_{t-1} + k_t^T v_t,  o_t = q_t kv_t
+ * (Sec. 3.3, Algorithm 2).
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers into caller-owned memory.  The
+ *     library never allocates, frees or keeps a pointer after the call returns.
+ *   - Tensors are contiguous row-major [Bt, H, N, D] (batch, head, token,
+ *     feature) in `dtype` (fp32, or bf16 stored as 16-bit words).  `decay` is a
+ *     device array of H fp32 values lambda_h in [0, 1]; values are not read on
+ *     the host (use ltn_attn_check_decay on a host copy to validate them).
+ *   - States are fp32 [Bt, H, D, D] with kv[b,h,i,j] = sum_s w_s k_s[i] v_s[j]
+ *     (row = key feature, column = value feature).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  Calls return without synchronising.
+ *   - Outputs are fully overwritten; inputs are never written.  An output that
+ *     aliases an input is rejected (LTN_ERR_UNSUPPORTED).
+ *   - Errors are return codes only.  Argument errors are detected on the host
+ *     before anything is launched.  Bt == 0 or H == 0 is a successful no-op; when
+ *     Bt * H * N == 0 the token tensors are not touched and may be NULL.
+ *   - Arithmetic: bf16 tensors use bf16 MFMA with fp32 accumulation and an fp32
+ *     running state; fp32 tensors use fp32 arithmetic throughout.  Only
+ *     non-negative powers of lambda are ever formed, so lambda = 0 and
+ *     lambda = 1 are exact and strong decays cannot overflow (the failure mode
+ *     Sec. 3.3 describes for the factorised form of Algorithm 1).
+ *   - Supported shapes: D in {64, 128}; N >= 0 arbitrary (a short last block
+ *     is handled on chip; the paper's listings assume block | N).
+ *     `block` is the intra-block tile length: 0 lets the library choose
+ *     (ltn_attn_pick_block); bf16 supports 64; fp32 supports 16, 32 and 64
+ *     with D * block <= 4096.
+ *   - Results are bitwise reproducible run to run for fixed arguments (no
+ *     floating-point atomics).
+ */
+#ifndef LTN_ATTN_H
+#define LTN_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LTN_OK = 0,
+    LTN_ERR_NULL = 1,        /* a required pointer is NULL                          */
+    LTN_ERR_SHAPE = 2,       /* negative size, or workspace too small               */
+    LTN_ERR_UNSUPPORTED = 3, /* D / block / dtype combination not built, aliasing   */
+    LTN_ERR_ALIGN = 4,       /* a tensor pointer is not 16-byte aligned             */
+    LTN_ERR_DECAY = 5,       /* ltn_attn_check_decay: a value outside [0, 1] or NaN */
+    LTN_ERR_LAUNCH = 6       /* the HIP runtime refused the launch                  */
+} ltn_status;
+
+typedef enum { LTN_F32 = 0, LTN_BF16 = 1 } ltn_dtype;
+
+/*
+ * Forward pass (Sec. 3.2.1; App. B Algorithm 3 computes the same O with a
+ * quadratic tile loop -- this library uses the linear-cost block recurrence).
+ *
+ *   o[b,h,t,:] = sum_{s<=t} lambda_h^(t-s) (q_t . k_s) v_s  +  lambda_h^(t+1) q_t kv_in[b,h]
+ *
+ *   q, k, v  in : device, [Bt,H,N,D] dtype
+ *   o        out: device, [Bt,H,N,D] dtype
+ *   decay    in : device, [H] fp32
+ *   kv_in    in : device, [Bt,H,D,D] fp32, or NULL for a zero initial state
+ *   kv_out   out: device, [Bt,H,D,D] fp32, or NULL; receives the state after the
+ *                 last token (kv_{N-1} of Algorithm 2); may alias kv_in
+ *   workspace   : device scratch of at least ltn_attn_workspace_bytes(...) bytes
+ *                 (may be NULL when that is 0)
+ * N == 0 copies kv_in (or zeros) to kv_out and does nothing else.
+ */
+ltn_status ltn_attn_fwd(const void* q, const void* k, const void* v, void* o,
+                        const float* decay, const float* kv_in, float* kv_out,
+                        int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward pass: gradients of the definition above (App. B Algorithm 4 read
+ * with its misprints corrected: dK = dA^T Q, dQ accumulates dA K).  With
+ * A = (Q K^T)(.)M and dA = (dO V^T)(.)M:  dQ = dA K, dK = dA^T Q, dV = A^T dO.
+ * Nothing saved by the forward is needed (the paper trains with activation
+ * recomputation, Sec. 3.2): inputs are q, k, v and d_o only, zero initial state.
+ *
+ *   q, k, v, d_o in : device, [Bt,H,N,D] dtype
+ *   dq, dk, dv   out: device, [Bt,H,N,D] dtype
+ */
+ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void* d_o,
+                        void* dq, void* dk, void* dv, const float* decay,
+                        int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One recurrent decode step (Sec. 3.3, Algorithm 2, one loop iteration):
+ *     kv <- lambda_h kv + k^T v   (in place),   o = q kv   (the updated state)
+ *
+ *   q, k, v in : device, [Bt,H,D] dtype       o out: device, [Bt,H,D] dtype
+ *   kv  in/out : device, [Bt,H,D,D] fp32
+ */
+ltn_status ltn_attn_decode_step(const void* q, const void* k, const void* v, void* o,
+                                float* kv, const float* decay,
+                                int Bt, int H, int D, ltn_dtype dtype, void* stream);
+
+/* Block length the library uses for (D, dtype) when `block` is 0; 0 if unsupported. */
+int ltn_attn_pick_block(int D, ltn_dtype dtype);
+
+/* Scratch bytes ltn_attn_fwd (is_bwd = 0) or ltn_attn_bwd (is_bwd = 1) needs for
+ * these arguments.  A smaller workspace makes the call fail with LTN_ERR_SHAPE.
+ * The present kernels keep every intermediate on chip, so this returns 0. */
+size_t ltn_attn_workspace_bytes(int Bt, int H, long long N, int D, int block,
+                                ltn_dtype dtype, int is_bwd);
+
+/* Host-side validation of a HOST copy of the decay array: LTN_OK if every value
+ * is in [0, 1], LTN_ERR_DECAY otherwise (Eq. 2 gives values in (0, 1]; the last
+ * layer uses exactly 1). */
+ltn_status ltn_attn_check_decay(const float* decay_host, int H);
+
+/* Static, human-readable name of a status code. */
+const char* ltn_status_str(ltn_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LTN_ATTN_H */

@@ -1,0 +1,22 @@
+"""MI355X-native Lightning Attention (arXiv 2307.14995): a C-ABI library of gfx950 HIP
+kernels plus this thin binding.  Importing the package loads nothing; the shared
+library is opened on first use and its absence is an error (there is no fallback).
+"""
+from .binding import (  # noqa: F401
+    LtnError,
+    library_path,
+    load_library,
+    ltn_attn_bwd,
+    ltn_attn_check_decay,
+    ltn_attn_decode_step,
+    ltn_attn_fwd,
+    ltn_attn_pick_block,
+    ltn_attn_workspace_bytes,
+    ltn_status_str,
+)
+
+__all__ = [
+    "LtnError", "library_path", "load_library", "ltn_attn_fwd", "ltn_attn_bwd",
+    "ltn_attn_decode_step", "ltn_attn_pick_block", "ltn_attn_workspace_bytes",
+    "ltn_attn_check_decay", "ltn_status_str",
+]

@@ -1,0 +1,185 @@
+"""ctypes binding of libltn_attn.so: argument marshalling only.
+
+Every function has the name and meaning of the C entry point in include/ltn_attn.h.
+PyTorch is used for device memory and the current HIP stream; all arithmetic of the
+attention path runs inside the library's kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libltn_attn.so")
+_lib = None
+
+LTN_F32, LTN_BF16 = 0, 1
+SYMBOLS = (
+    "ltn_attn_fwd", "ltn_attn_bwd", "ltn_attn_decode_step", "ltn_attn_pick_block",
+    "ltn_attn_workspace_bytes", "ltn_attn_check_decay", "ltn_status_str",
+)
+
+
+class LtnError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = int(code)
+        super().__init__(f"{where}: {ltn_status_str(code)}")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Open the built library; build it first only if nothing is built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from .build import build_library
+        build_library(force=True)
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with __graft_entry__.build()")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, fp, ci, cl, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_size_t
+    lib.ltn_attn_fwd.argtypes = [vp, vp, vp, vp, fp, fp, fp, ci, ci, cl, ci, ci, ci, vp, sz, vp]
+    lib.ltn_attn_fwd.restype = ci
+    lib.ltn_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, fp, ci, ci, cl, ci, ci, ci, vp, sz, vp]
+    lib.ltn_attn_bwd.restype = ci
+    lib.ltn_attn_decode_step.argtypes = [vp, vp, vp, vp, fp, fp, ci, ci, ci, ci, vp]
+    lib.ltn_attn_decode_step.restype = ci
+    lib.ltn_attn_pick_block.argtypes = [ci, ci]
+    lib.ltn_attn_pick_block.restype = ci
+    lib.ltn_attn_workspace_bytes.argtypes = [ci, ci, cl, ci, ci, ci, ci]
+    lib.ltn_attn_workspace_bytes.restype = sz
+    lib.ltn_attn_check_decay.argtypes = [ctypes.POINTER(ctypes.c_float), ci]
+    lib.ltn_attn_check_decay.restype = ci
+    lib.ltn_status_str.argtypes = [ci]
+    lib.ltn_status_str.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def ltn_status_str(code: int) -> str:
+    return load_library().ltn_status_str(int(code)).decode()
+
+
+def ltn_attn_pick_block(D: int, dtype: torch.dtype) -> int:
+    return int(load_library().ltn_attn_pick_block(int(D), _dtype_code(dtype)))
+
+
+def ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, is_bwd) -> int:
+    return int(load_library().ltn_attn_workspace_bytes(Bt, H, N, D, block, _dtype_code(dtype), int(is_bwd)))
+
+
+def ltn_attn_check_decay(decay) -> int:
+    """Validate a decay array (copied to the host); returns the status code."""
+    d = torch.as_tensor(decay).detach().to("cpu", torch.float32).contiguous()
+    buf = (ctypes.c_float * d.numel())(*d.tolist())
+    return int(load_library().ltn_attn_check_decay(buf, d.numel()))
+
+
+def _dtype_code(dtype: torch.dtype) -> int:
+    if dtype == torch.float32:
+        return LTN_F32
+    if dtype == torch.bfloat16:
+        return LTN_BF16
+    raise TypeError(f"unsupported dtype {dtype}: the library computes in fp32 or bf16")
+
+
+def _dev(t: torch.Tensor, what: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{what} must live on the GPU (the library has no CPU path)")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return t
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(device) -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def _workspace(nbytes: int, device):
+    return None if nbytes == 0 else torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def ltn_attn_fwd(q, k, v, decay, kv_in=None, return_state=False, block=0, out=None, kv_out=None):
+    """O[Bt,H,N,D] = ((Q K^T) (.) M) V, optionally continuing from / returning the fp32 state."""
+    lib = load_library()
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (decay, "decay")):
+        _dev(t, n)
+    if q.shape != k.shape or q.shape != v.shape or q.dim() != 4 or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must be [Bt,H,N,D] tensors of one shape and dtype")
+    Bt, H, N, D = q.shape
+    if decay.dtype != torch.float32 or decay.numel() != H:
+        raise ValueError("decay must be fp32 [H]")
+    o = torch.empty_like(q) if out is None else _dev(out, "out")
+    if kv_in is not None:
+        _dev(kv_in, "kv_in")
+        if kv_in.dtype != torch.float32 or tuple(kv_in.shape) != (Bt, H, D, D):
+            raise ValueError("kv_in must be fp32 [Bt,H,D,D]")
+    if kv_out is None and return_state:
+        kv_out = torch.empty((Bt, H, D, D), dtype=torch.float32, device=q.device)
+    code = _dtype_code(q.dtype)
+    ws_bytes = int(lib.ltn_attn_workspace_bytes(Bt, H, N, D, block, code, 0))
+    ws = _workspace(ws_bytes, q.device)
+    with torch.cuda.device(q.device):
+        rc = lib.ltn_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(decay), _ptr(kv_in), _ptr(kv_out),
+                              Bt, H, N, D, int(block), code, _ptr(ws), ws_bytes, _stream(q.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_fwd")
+    return (o, kv_out) if (return_state or kv_out is not None) else o
+
+
+def ltn_attn_bwd(q, k, v, d_o, decay, block=0, out=None):
+    """(dQ, dK, dV) of the forward definition; needs q, k, v, dO only."""
+    lib = load_library()
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (d_o, "d_o"), (decay, "decay")):
+        _dev(t, n)
+    if not (q.shape == k.shape == v.shape == d_o.shape) or q.dim() != 4:
+        raise ValueError("q, k, v, d_o must be [Bt,H,N,D] tensors of one shape")
+    if not (q.dtype == k.dtype == v.dtype == d_o.dtype):
+        raise ValueError("q, k, v, d_o must share a dtype")
+    Bt, H, N, D = q.shape
+    if decay.dtype != torch.float32 or decay.numel() != H:
+        raise ValueError("decay must be fp32 [H]")
+    if out is None:
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    else:
+        dq, dk, dv = (_dev(t, "out") for t in out)
+    code = _dtype_code(q.dtype)
+    ws_bytes = int(lib.ltn_attn_workspace_bytes(Bt, H, N, D, block, code, 1))
+    ws = _workspace(ws_bytes, q.device)
+    with torch.cuda.device(q.device):
+        rc = lib.ltn_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(decay),
+                              Bt, H, N, D, int(block), code, _ptr(ws), ws_bytes, _stream(q.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_bwd")
+    return dq, dk, dv
+
+
+def ltn_attn_decode_step(q, k, v, kv, decay, out=None):
+    """kv <- lambda kv + k^T v (in place); returns o = q kv.  q, k, v: [Bt,H,D]; kv: fp32 [Bt,H,D,D]."""
+    lib = load_library()
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (kv, "kv"), (decay, "decay")):
+        _dev(t, n)
+    if not (q.shape == k.shape == v.shape) or q.dim() != 3 or not (q.dtype == k.dtype == v.dtype):
+        raise ValueError("q, k, v must be [Bt,H,D] tensors of one shape and dtype")
+    Bt, H, D = q.shape
+    if kv.dtype != torch.float32 or tuple(kv.shape) != (Bt, H, D, D):
+        raise ValueError("kv must be fp32 [Bt,H,D,D]")
+    if decay.dtype != torch.float32 or decay.numel() != H:
+        raise ValueError("decay must be fp32 [H]")
+    o = torch.empty_like(q) if out is None else _dev(out, "out")
+    with torch.cuda.device(q.device):
+        rc = lib.ltn_attn_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(kv), _ptr(decay),
+                                      Bt, H, D, _dtype_code(q.dtype), _stream(q.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_decode_step")
+    return o

@@ -1,0 +1,184 @@
+// C-ABI layer of the Lightning Attention library: argument validation (host only,
+// before any launch), choice of block length and value-column split, and dispatch
+// to the gfx950 kernels.  See include/ltn_attn.h for the contract.
+#include "../../include/ltn_attn.h"
+#include "ltn_kernels.h"
+
+#include <cstdint>
+#include <cstdlib>
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Value columns handled per workgroup.  Every value-column slice of a chain
+// recomputes that chain's score tiles and re-reads its first two operands, so the
+// split is only as deep as needed to put a workgroup on each of the 256 compute
+// units.  LTN_ATTN_DV (debug only) overrides the choice.
+int pick_dv(long long chain_passes, int D, ltn_dtype dtype) {
+    if (const char* e = std::getenv("LTN_ATTN_DV")) {
+        const int v = std::atoi(e);
+        const int lo = (dtype == LTN_BF16) ? 32 : D / 2;
+        if ((v == D || v == D / 2 || v == D / 4) && v >= lo) return v;
+    }
+    if (chain_passes >= 512) return D;
+    if (dtype == LTN_F32) return D / 2;
+    if (chain_passes >= 128 || D == 64) return D / 2;
+    return D / 4;
+}
+
+ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype dtype, int* blk_out) {
+    if (Bt < 0 || H < 0 || N < 0 || D <= 0 || block < 0) return LTN_ERR_SHAPE;
+    if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
+    if (D != 64 && D != 128) return LTN_ERR_UNSUPPORTED;
+    const int blk = block ? block : ltn_attn_pick_block(D, dtype);
+    if (dtype == LTN_BF16) {
+        if (blk != 64) return LTN_ERR_UNSUPPORTED;
+    } else {
+        if (blk != 16 && blk != 32 && blk != 64) return LTN_ERR_UNSUPPORTED;
+        if ((long long)D * blk > 4096) return LTN_ERR_UNSUPPORTED;
+    }
+    if ((long long)Bt * H > 0x3fffffffLL) return LTN_ERR_SHAPE;
+    *blk_out = blk;
+    return LTN_OK;
+}
+
+ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, hipStream_t stream) {
+    const int dv = pick_dv((long long)pb.chains * pb.count, D, dtype);
+    const hipError_t e = (dtype == LTN_BF16) ? ltn::launch_pass_bf16(pb, D, dv, stream)
+                                             : ltn::launch_pass_f32(pb, D, dv, blk, stream);
+    return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ltn_attn_pick_block(int D, ltn_dtype dtype) {
+    if (D != 64 && D != 128) return 0;
+    if (dtype == LTN_BF16) return 64;
+    if (dtype == LTN_F32) return D == 64 ? 64 : 32;
+    return 0;
+}
+
+size_t ltn_attn_workspace_bytes(int, int, long long, int, int, ltn_dtype, int) { return 0; }
+
+ltn_status ltn_attn_check_decay(const float* decay_host, int H) {
+    if (!decay_host) return LTN_ERR_NULL;
+    if (H < 0) return LTN_ERR_SHAPE;
+    for (int h = 0; h < H; ++h)
+        if (!(decay_host[h] >= 0.0f && decay_host[h] <= 1.0f)) return LTN_ERR_DECAY;
+    return LTN_OK;
+}
+
+const char* ltn_status_str(ltn_status s) {
+    switch (s) {
+        case LTN_OK: return "LTN_OK";
+        case LTN_ERR_NULL: return "LTN_ERR_NULL: a required pointer is NULL";
+        case LTN_ERR_SHAPE: return "LTN_ERR_SHAPE: bad size or workspace too small";
+        case LTN_ERR_UNSUPPORTED: return "LTN_ERR_UNSUPPORTED: shape/dtype/block not supported, or output aliases an input";
+        case LTN_ERR_ALIGN: return "LTN_ERR_ALIGN: tensor pointer not 16-byte aligned";
+        case LTN_ERR_DECAY: return "LTN_ERR_DECAY: decay value outside [0, 1]";
+        case LTN_ERR_LAUNCH: return "LTN_ERR_LAUNCH: HIP launch failed";
+    }
+    return "LTN_ERR_?: unknown status";
+}
+
+ltn_status ltn_attn_fwd(const void* q, const void* k, const void* v, void* o,
+                        const float* decay, const float* kv_in, float* kv_out,
+                        int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace;
+    const bool empty = (Bt == 0 || H == 0 || N == 0);   // no token is read or written
+    if (!decay || (!empty && (!q || !k || !v || !o))) return LTN_ERR_NULL;
+    int blk = 0;
+    const ltn_status cs = check_common(Bt, H, N, D, block, dtype, &blk);
+    if (cs != LTN_OK) return cs;
+    if (workspace_bytes < ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, 0)) return LTN_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) ||
+        !aligned16(kv_in) || !aligned16(kv_out) || (reinterpret_cast<uintptr_t>(decay) & 3u))
+        return LTN_ERR_ALIGN;
+    if (!empty && (o == q || o == k || o == v || (const void*)kv_out == q || (const void*)kv_out == k ||
+                   (const void*)kv_out == v || (const void*)kv_out == o))
+        return LTN_ERR_UNSUPPORTED;
+    const long long chains = (long long)Bt * H;
+    if (chains == 0) return LTN_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (N == 0) {
+        if (!kv_out) return LTN_OK;
+        return ltn::launch_state_copy(kv_in, kv_out, (size_t)chains * D * D, st) == hipSuccess
+                   ? LTN_OK : LTN_ERR_LAUNCH;
+    }
+    ltn::PassBatch pb = {};
+    pb.count = 1;
+    pb.decay = decay;
+    pb.chains = (int)chains;
+    pb.H = H;
+    pb.N = N;
+    pb.p[0] = ltn::PassArgs{q, k, v, o, kv_in, kv_out, 0};
+    return run_passes(pb, D, blk, dtype, st);
+}
+
+ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void* d_o,
+                        void* dq, void* dk, void* dv, const float* decay,
+                        int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace;
+    const bool empty = (Bt == 0 || H == 0 || N == 0);
+    if (!decay || (!empty && (!q || !k || !v || !d_o || !dq || !dk || !dv))) return LTN_ERR_NULL;
+    int blk = 0;
+    const ltn_status cs = check_common(Bt, H, N, D, block, dtype, &blk);
+    if (cs != LTN_OK) return cs;
+    if (workspace_bytes < ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, 1)) return LTN_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) ||
+        !aligned16(dk) || !aligned16(dv) || (reinterpret_cast<uintptr_t>(decay) & 3u))
+        return LTN_ERR_ALIGN;
+    const void* ins[4] = {q, k, v, d_o};
+    const void* outs[3] = {dq, dk, dv};
+    for (int a = 0; a < 3 && !empty; ++a) {
+        for (int b = 0; b < 4; ++b)
+            if (outs[a] == ins[b]) return LTN_ERR_UNSUPPORTED;
+        for (int b = a + 1; b < 3; ++b)
+            if (outs[a] == outs[b]) return LTN_ERR_UNSUPPORTED;
+    }
+    const long long chains = (long long)Bt * H;
+    if (chains == 0 || N == 0) return LTN_OK;
+    // The three gradients are three decayed linear-attention passes with permuted
+    // operands (derivative of O = ((Q K^T)(.)M) V; App. B Algorithm 4 corrected):
+    //   dQ = ((dO V^T)(.)M)   K   -> pass(dO, V, K), first token -> last
+    //   dV = ((Q K^T)(.)M)^T  dO  -> pass(K, Q, dO), last token -> first
+    //   dK = ((dO V^T)(.)M)^T Q   -> pass(V, dO, Q), last token -> first
+    ltn::PassBatch pb = {};
+    pb.count = 3;
+    pb.decay = decay;
+    pb.chains = (int)chains;
+    pb.H = H;
+    pb.N = N;
+    pb.p[0] = ltn::PassArgs{k, q, d_o, dv, nullptr, nullptr, 1};
+    pb.p[1] = ltn::PassArgs{v, d_o, q, dk, nullptr, nullptr, 1};
+    pb.p[2] = ltn::PassArgs{d_o, v, k, dq, nullptr, nullptr, 0};
+    return run_passes(pb, D, blk, dtype, static_cast<hipStream_t>(stream));
+}
+
+ltn_status ltn_attn_decode_step(const void* q, const void* k, const void* v, void* o,
+                                float* kv, const float* decay,
+                                int Bt, int H, int D, ltn_dtype dtype, void* stream) {
+    if (!q || !k || !v || !o || !kv || !decay) return LTN_ERR_NULL;
+    if (Bt < 0 || H < 0 || D <= 0) return LTN_ERR_SHAPE;
+    if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
+    if (D != 64 && D != 128) return LTN_ERR_UNSUPPORTED;
+    if ((long long)Bt * H > 0x3fffffffLL) return LTN_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(kv) ||
+        (reinterpret_cast<uintptr_t>(decay) & 3u))
+        return LTN_ERR_ALIGN;
+    if (o == q || o == k || o == v || (const void*)kv == q || (const void*)kv == k ||
+        (const void*)kv == v || (const void*)kv == o)
+        return LTN_ERR_UNSUPPORTED;
+    const int chains = Bt * H;
+    if (chains == 0) return LTN_OK;
+    const hipError_t e = ltn::launch_decode(q, k, v, o, kv, decay, chains, H, D, dtype == LTN_BF16,
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,75 @@
+// Internal launcher interface between the C-ABI layer and the gfx950 kernels.
+// Not installed; the public boundary is include/ltn_attn.h.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace ltn {
+
+// One "decayed linear-attention pass":
+//   out[t,:] = sum_{s<=t} lambda^(t-s) (a_t . b_s) c_s  (+ lambda^(t+1) a_t state_in)
+// evaluated blockwise with a running state  S <- lambda^len S + (decayed b)^T c.
+// With rev = 1 the token axis is traversed from the last token to the first, which
+// turns the sum into  sum_{s>=t} lambda^(s-t) (a_t . b_s) c_s  (the anti-causal pass
+// the gradients dK and dV need).  The forward pass and the three gradients of
+// Lightning Attention (arXiv 2307.14995, Sec. 3.2.1 / App. B) are four such passes:
+//   O  = pass(Q,  K,  V)        dQ = pass(dO, V,  K)
+//   dV = pass(K,  Q,  dO, rev)  dK = pass(V,  dO, Q, rev)
+struct PassArgs {
+    const void* a;        // [chains, N, D]  "query-like" operand
+    const void* b;        // [chains, N, D]  "key-like" operand
+    const void* c;        // [chains, N, D]  "value-like" operand
+    void* out;            // [chains, N, D]
+    const float* state_in;  // [chains, D, D] fp32 or nullptr (zero)
+    float* state_out;       // [chains, D, D] fp32 or nullptr
+    int rev;              // 0: first token -> last; 1: last -> first
+};
+
+struct PassBatch {
+    PassArgs p[3];
+    int count;            // 1..3 passes run concurrently in one launch
+    const float* decay;   // [H]
+    int chains;           // Bt * H
+    int H;
+    long long N;
+};
+
+// bf16 MFMA kernel, block length 64.  D in {64,128}; dv = value columns per workgroup.
+hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream);
+// fp32 kernel.  D in {64,128}, block in {16,32,64}, D*block <= 4096.
+hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStream_t stream);
+// kv[c] (or zeros if null) -> kv_out[c], n floats.
+hipError_t launch_state_copy(const float* kv_in, float* kv_out, size_t n, hipStream_t stream);
+// One decode step, see ltn_attn_decode_step.
+hipError_t launch_decode(const void* q, const void* k, const void* v, void* o, float* kv,
+                         const float* decay, int chains, int H, int D, int is_bf16,
+                         hipStream_t stream);
+
+// lambda^n, n >= 0, by binary powering in fp64 (only multiplications: exact up to
+// rounding, lambda = 0 gives 0^0 = 1, no transcendental).  Never called with n < 0.
+__device__ __forceinline__ float decay_pow(float lam, int n) {
+    double base = (double)lam, r = 1.0;
+    while (n > 0) {
+        if (n & 1) r *= base;
+        base *= base;
+        n >>= 1;
+    }
+    return (float)r;
+}
+
+// Workgroup index -> (pass, chain, split).  Consecutive workgroup ids are dealt
+// round-robin to the 8 XCDs, each with a private L2; all workgroups that read the
+// same chain's tokens (its passes and value-column splits) are therefore given
+// ids that are congruent mod 8, so re-reads of a chain's tiles hit one L2.
+__device__ __forceinline__ void map_workgroup(int wg, int per_chain, int chains,
+                                              int& chain, int& within) {
+    if ((chains & 7) == 0) {
+        const int xcd = wg & 7, slot = wg >> 3;
+        chain = (slot / per_chain) * 8 + xcd;
+        within = slot % per_chain;
+    } else {
+        chain = wg / per_chain;
+        within = wg % per_chain;
+    }
+}
+
+}  // namespace ltn

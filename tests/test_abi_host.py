@@ -1,0 +1,146 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the public header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2307_14995_amd as ltn
+from paper_2307_14995_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ltn_attn.h")
+
+OK, E_NULL, E_SHAPE, E_UNSUP, E_ALIGN, E_DECAY, E_LAUNCH = range(7)
+P = 0x10000  # fake, 16-byte aligned, never dereferenced: validation fails before any launch
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return ltn.load_library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ltn_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.SYMBOLS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(7):
+        s = ltn.ltn_status_str(code)
+        assert s.startswith("LTN_") and s not in seen
+        seen.add(s)
+    assert "unknown" in ltn.ltn_status_str(99)
+
+
+def test_pick_block_and_workspace(lib):
+    import torch
+    assert ltn.ltn_attn_pick_block(128, torch.bfloat16) == 64
+    assert ltn.ltn_attn_pick_block(64, torch.bfloat16) == 64
+    assert ltn.ltn_attn_pick_block(64, torch.float32) == 64
+    assert ltn.ltn_attn_pick_block(128, torch.float32) == 32
+    assert ltn.ltn_attn_pick_block(96, torch.bfloat16) == 0
+    assert ltn.ltn_attn_workspace_bytes(4, 32, 8192, 128, 0, torch.bfloat16, 1) == 0
+
+
+def test_check_decay(lib):
+    assert ltn.ltn_attn_check_decay([0.0, 0.5, 1.0]) == OK
+    assert ltn.ltn_attn_check_decay([0.5, 1.0001]) == E_DECAY
+    assert ltn.ltn_attn_check_decay([-1e-9]) == E_DECAY
+    assert ltn.ltn_attn_check_decay([float("nan")]) == E_DECAY
+    assert lib.ltn_attn_check_decay(None, 3) == E_NULL
+
+
+def fwd(lib, q=P, k=P + 0x1000, v=P + 0x2000, o=P + 0x3000, decay=P + 0x4000, kv_in=None, kv_out=None,
+        Bt=1, H=2, N=256, D=64, block=0, dtype=1, ws=None, ws_bytes=0):
+    return lib.ltn_attn_fwd(q, k, v, o, decay, kv_in, kv_out, Bt, H, N, D, block, dtype, ws, ws_bytes, None)
+
+
+def bwd(lib, q=P, k=P + 0x1000, v=P + 0x2000, g=P + 0x3000, dq=P + 0x5000, dk=P + 0x6000, dv=P + 0x7000,
+        decay=P + 0x4000, Bt=1, H=2, N=256, D=64, block=0, dtype=1):
+    return lib.ltn_attn_bwd(q, k, v, g, dq, dk, dv, decay, Bt, H, N, D, block, dtype, None, 0, None)
+
+
+def test_fwd_argument_errors(lib):
+    assert fwd(lib, q=None) == E_NULL
+    assert fwd(lib, o=None) == E_NULL
+    assert fwd(lib, decay=None) == E_NULL
+    assert fwd(lib, N=-1) == E_SHAPE
+    assert fwd(lib, Bt=-1) == E_SHAPE
+    assert fwd(lib, D=96) == E_UNSUP
+    assert fwd(lib, D=256) == E_UNSUP
+    assert fwd(lib, dtype=7) == E_UNSUP
+    assert fwd(lib, block=48) == E_UNSUP
+    assert fwd(lib, block=32, dtype=1) == E_UNSUP          # bf16 supports block 64 only
+    assert fwd(lib, D=128, block=64, dtype=0) == E_UNSUP   # fp32: D * block <= 4096
+    assert fwd(lib, q=P + 8) == E_ALIGN
+    assert fwd(lib, kv_out=P + 0x8004) == E_ALIGN
+    assert fwd(lib, decay=P + 0x4002) == E_ALIGN
+    assert fwd(lib, o=P) == E_UNSUP                        # output aliases q
+    assert fwd(lib, kv_out=P + 0x2000) == E_UNSUP          # state aliases v
+    # empty problems succeed without touching the GPU
+    assert fwd(lib, Bt=0) == OK
+    assert fwd(lib, H=0) == OK
+    assert fwd(lib, N=0) == OK                             # no state requested -> nothing to do
+
+
+def test_bwd_argument_errors(lib):
+    assert bwd(lib, g=None) == E_NULL
+    assert bwd(lib, dv=None) == E_NULL
+    assert bwd(lib, N=-5) == E_SHAPE
+    assert bwd(lib, D=32) == E_UNSUP
+    assert bwd(lib, block=128) == E_UNSUP
+    assert bwd(lib, dk=P + 4) == E_ALIGN
+    assert bwd(lib, dq=P) == E_UNSUP                       # dq aliases q
+    assert bwd(lib, dk=P + 0x5000) == E_UNSUP              # dk aliases dq
+    assert bwd(lib, Bt=0) == OK
+    assert bwd(lib, N=0) == OK
+
+
+def test_decode_argument_errors(lib):
+    f = lib.ltn_attn_decode_step
+    args = dict(q=P, k=P + 0x100, v=P + 0x200, o=P + 0x300, kv=P + 0x1000, decay=P + 0x4000)
+
+    def call(Bt=2, H=2, D=128, dtype=1, **over):
+        a = dict(args, **over)
+        return f(a["q"], a["k"], a["v"], a["o"], a["kv"], a["decay"], Bt, H, D, dtype, None)
+
+    assert call(kv=None) == E_NULL
+    assert call(q=None) == E_NULL
+    assert call(Bt=-2) == E_SHAPE
+    assert call(D=100) == E_UNSUP
+    assert call(dtype=3) == E_UNSUP
+    assert call(v=P + 0x202) == E_ALIGN
+    assert call(o=P + 0x100) == E_UNSUP
+    assert call(Bt=0) == OK
+
+
+def test_binding_rejects_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 1, 4, 64)
+    with pytest.raises(ValueError):
+        ltn.ltn_attn_fwd(x, x, x, torch.ones(1))
+
+
+def test_product_path_does_not_import_the_oracle():
+    """The library's Python side must never reach into oracle/ (and vice versa)."""
+    pkg_dir = os.path.join(ROOT, "paper_2307_14995_amd")
+    for dirpath, _, files in os.walk(pkg_dir):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower().replace("the cpu oracle's tests", ""), f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2307_14995_amd" not in text and "libltn_attn" not in text, f

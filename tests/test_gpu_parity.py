@@ -1,0 +1,371 @@
+"""GPU parity: the HIP library (through its C ABI, via the ctypes binding) against the
+fp64 CPU oracle, element by element on the same seeded inputs.
+
+Error metric: ||x - ref||_2 / ||ref||_2 in fp64, maximum over the whole tensor and
+every (batch, head) slice.  Bounds: 1e-4 for fp32 tensors, 1e-2 for bf16 tensors
+(bf16 inputs are widened exactly for the oracle, so the bound covers the kernel's own
+arithmetic: bf16 rounding of the masked scores, of the published state and of the
+outputs, with fp32 accumulation).
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2307_14995_amd as ltn
+from paper_2307_14995_amd import synth
+from oracle import ltn_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float32: 1e-4, torch.bfloat16: 1e-2}
+
+
+def dev():
+    return torch.device("cuda:0")
+
+
+def gpu(*ts):
+    return tuple(t.to(dev()) for t in ts)
+
+
+class force_dv:
+    """Debug override of the value-column split, so every kernel variant gets parity-tested."""
+
+    def __init__(self, dv):
+        self.dv = dv
+
+    def __enter__(self):
+        self.old = os.environ.get("LTN_ATTN_DV")
+        if self.dv:
+            os.environ["LTN_ATTN_DV"] = str(self.dv)
+
+    def __exit__(self, *a):
+        os.environ.pop("LTN_ATTN_DV", None)
+        if self.old is not None:
+            os.environ["LTN_ATTN_DV"] = self.old
+
+
+def decays(H):
+    """Per-head decay sets exercised everywhere: benchmark rule, Eq. 2 (down to exp(-8)), 1 and 0."""
+    out = {"bench": synth.decay_bench_rule(H), "eq2": synth.decay_paper_rule(H),
+           "one": torch.ones(H), "zero": torch.zeros(H)}
+    mix = synth.decay_bench_rule(H).clone()
+    mix[0] = 1.0
+    if H > 1:
+        mix[1] = 0.0
+    if H > 2:
+        mix[2] = float(np.exp(-8.0))
+    out["mix"] = mix
+    return out
+
+
+def check(name, got, ref, tol, per_slice=True):
+    """per_slice=False is for single-token outputs [Bt,H,D]: a (b,h) slice is then one
+    D-vector scaled by a single dot product q.k (exactly so for lambda = 0), whose relative
+    error is unbounded under cancellation in any finite precision; the bound is taken over
+    the whole tensor there."""
+    assert torch.isfinite(got.float()).all(), f"{name}: non-finite values"
+    err = orc.max_rel_l2(got, ref) if per_slice else orc.rel_l2(got, ref)
+    assert err <= tol, f"{name}: rel-L2 {err:.3e} > {tol:g}"
+    return err
+
+
+# --------------------------------------------------------------------------- config 1 (fp32)
+
+
+def test_cfg1_fp32_forward():
+    w = synth.CONFIGS["cfg1_fp32_small"]
+    q, k, v = synth.make_qkv(w.Bt, w.H, w.N, w.D, w.dtype, w.seed)
+    decay = synth.decay_bench_rule(w.H)
+    o = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), block=w.block)
+    ref = orc.fwd_quadratic(q, k, v, decay)
+    check("O", o, ref, 1e-4)
+
+
+@pytest.mark.parametrize("D,block", [(64, 16), (64, 32), (64, 64), (128, 16), (128, 32)])
+@pytest.mark.parametrize("N", [1, 37, 130])
+def test_fp32_fwd_bwd_blocks(D, block, N):
+    Bt, H = 2, 3
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.float32, 100 + N)
+    g = synth.make_do(Bt, H, N, D, torch.float32, 100 + N)
+    decay = decays(H)["mix"]
+    for dv in (D, D // 2):
+        with force_dv(dv):
+            o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), block=block, return_state=True)
+            dq, dk, dvv = ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay), block=block)
+        o_ref, kv_ref = orc.fwd_recurrent(q, k, v, decay, return_state=True)
+        check("O", o, orc.fwd_quadratic(q, k, v, decay), 1e-4)
+        check("kv", kv, kv_ref, 1e-4)
+        for n, x, r in zip(("dQ", "dK", "dV"), (dq, dk, dvv), orc.bwd_quadratic(q, k, v, g, decay)):
+            check(n, x, r, 1e-4)
+
+
+# --------------------------------------------------------------------------- bf16 forward
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("N", [1, 15, 63, 64, 65, 128, 200, 517])
+def test_bf16_forward_ragged(D, N):
+    Bt, H = 1, 3                           # 3 chains: the non-XCD-grouped workgroup map
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 200 + N)
+    for name, decay in decays(H).items():
+        ref, kv_ref = orc.fwd_recurrent(q, k, v, decay, return_state=True)
+        for dv in (D, D // 2) + ((D // 4,) if D == 128 else ()):
+            with force_dv(dv):
+                o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), return_state=True)
+            check(f"O[{name},dv={dv}]", o, ref, 1e-2)
+            check(f"kv[{name},dv={dv}]", kv, kv_ref, 1e-2)
+
+
+def test_bf16_forward_many_chains_xcd_map():
+    Bt, H, N, D = 4, 8, 300, 128           # 32 chains: the XCD-grouped workgroup map
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 31)
+    decay = synth.decay_bench_rule(H)
+    ref = orc.fwd_recurrent(q, k, v, decay)
+    for dv in (128, 64, 32):
+        with force_dv(dv):
+            o = ltn.ltn_attn_fwd(*gpu(q, k, v, decay))
+        check(f"O[dv={dv}]", o, ref, 1e-2)
+
+
+def test_bf16_chunked_prefill_matches_one_call():
+    Bt, H, N, D = 2, 4, 448, 128
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 41)
+    decay = decays(H)["mix"]
+    qd, kd, vd, dd = gpu(q, k, v, decay)
+    ref, kv_ref = orc.fwd_recurrent(q, k, v, decay, return_state=True)
+    cut = 203                               # not a block multiple
+    o1, kv1 = ltn.ltn_attn_fwd(qd[:, :, :cut].contiguous(), kd[:, :, :cut].contiguous(),
+                               vd[:, :, :cut].contiguous(), dd, return_state=True)
+    o2, kv2 = ltn.ltn_attn_fwd(qd[:, :, cut:].contiguous(), kd[:, :, cut:].contiguous(),
+                               vd[:, :, cut:].contiguous(), dd, kv_in=kv1, return_state=True)
+    check("O", torch.cat([o1, o2], 2), ref, 1e-2)
+    check("kv", kv2, kv_ref, 1e-2)
+    # N = 0 with a state: the state is passed through untouched
+    empty = qd[:, :, :0].contiguous()
+    _, kv3 = ltn.ltn_attn_fwd(empty, empty, empty, dd, kv_in=kv2, return_state=True)
+    assert torch.equal(kv3, kv2)
+    _, kv4 = ltn.ltn_attn_fwd(empty, empty, empty, dd, return_state=True)
+    assert torch.count_nonzero(kv4) == 0
+
+
+# --------------------------------------------------------------------------- bf16 backward
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("N", [1, 64, 97, 333])
+def test_bf16_backward_ragged(D, N):
+    Bt, H = 2, 3
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 300 + N)
+    g = synth.make_do(Bt, H, N, D, torch.bfloat16, 300 + N)
+    for name, decay in decays(H).items():
+        refs = orc.bwd_recurrent(q, k, v, g, decay)
+        for dv in (D, D // 2):
+            with force_dv(dv):
+                outs = ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay))
+            for n, x, r in zip(("dQ", "dK", "dV"), outs, refs):
+                check(f"{n}[{name},dv={dv}]", x, r, 1e-2)
+
+
+def test_bf16_backward_probe_reads_back_scores():
+    """dO = e_t e_j^T: column j of dV must be row t of the masked score matrix A."""
+    Bt, H, N, D = 1, 1, 150, 128
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 51)
+    decay = torch.tensor([0.97], dtype=torch.float32)
+    t, j = 140, 77
+    g = torch.zeros(Bt, H, N, D, dtype=torch.bfloat16)
+    g[0, 0, t, j] = 1.0
+    _, _, dv = ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay))
+    lam = float(decay[0])                   # the fp32 value the kernel sees
+    a_row = (q[0, 0, t].double() @ k[0, 0].double().T) * torch.tensor(
+        [lam ** (t - s) if s <= t else 0.0 for s in range(N)], dtype=torch.float64)
+    assert orc.rel_l2(dv[0, 0, :, j], a_row.numpy()) <= 1e-2
+    other = dv[0, 0].clone()
+    other[:, j] = 0
+    assert torch.count_nonzero(other) == 0
+
+
+# --------------------------------------------------------------------------- decode
+
+
+@pytest.mark.parametrize("dtype,D", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 128), (torch.float32, 64)])
+def test_decode_steps_continue_prefix(dtype, D):
+    Bt, H, N0, steps = 3, 4, 100, 24
+    q, k, v = synth.make_qkv(Bt, H, N0, D, dtype, 61)
+    decay = decays(H)["mix"]
+    qd, kd, vd, dd = gpu(q, k, v, decay)
+    _, kv = ltn.ltn_attn_fwd(qd, kd, vd, dd, return_state=True)
+    _, kv_ref = orc.fwd_recurrent(q, k, v, decay, return_state=True)
+    tol = TOL[dtype]
+    for s in range(steps):
+        q1, k1, v1 = synth.make_step_qkv(Bt, H, D, dtype, 61, s)
+        o1 = ltn.ltn_attn_decode_step(*gpu(q1, k1, v1), kv, dd)
+        o_ref, kv_ref = orc.decode_step(q1, k1, v1, kv_ref, decay)
+        check(f"o[{s}]", o1, o_ref, tol, per_slice=False)
+    check("kv", kv, kv_ref, tol)
+
+
+def test_decode_time_does_not_depend_on_position():
+    """Sec. 4 / Fig. 4: per-token cost of the recurrent form is constant in sequence position."""
+    Bt, H, D = 16, 32, 128
+    decay = synth.decay_bench_rule(H).to(dev())
+    kv = torch.zeros(Bt, H, D, D, device=dev())
+    q, k, v = gpu(*synth.make_step_qkv(Bt, H, D, torch.bfloat16, 5, 0))
+
+    def timed(n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            ltn.ltn_attn_decode_step(q, k, v, kv, decay)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    timed(50)
+    early = timed(200)
+    for _ in range(2000):
+        ltn.ltn_attn_decode_step(q, k, v, kv, decay)
+    late = timed(200)
+    assert 0.5 < late / early < 2.0, (early, late)
+
+
+# --------------------------------------------------------------------------- determinism / robustness
+
+
+def test_bitwise_reproducible():
+    Bt, H, N, D = 2, 4, 260, 128
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 71)
+    g = synth.make_do(Bt, H, N, D, torch.bfloat16, 71)
+    args = gpu(q, k, v, g, synth.decay_bench_rule(H))
+    a = ltn.ltn_attn_fwd(*args[:3], args[4])
+    b = ltn.ltn_attn_fwd(*args[:3], args[4])
+    assert torch.equal(a, b)
+    ga = ltn.ltn_attn_bwd(*args)
+    gb = ltn.ltn_attn_bwd(*args)
+    for x, y in zip(ga, gb):
+        assert torch.equal(x, y)
+
+
+def test_outputs_fully_overwritten_and_inputs_untouched():
+    Bt, H, N, D = 1, 2, 100, 128
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 81)
+    decay = synth.decay_bench_rule(H)
+    qd, kd, vd, dd = gpu(q, k, v, decay)
+    poison = torch.full_like(qd, float("nan"))
+    o = ltn.ltn_attn_fwd(qd, kd, vd, dd, out=poison)
+    assert torch.isfinite(o.float()).all()
+    assert torch.equal(qd.cpu(), q) and torch.equal(kd.cpu(), k) and torch.equal(vd.cpu(), v)
+
+
+def test_strong_decay_stays_finite_on_long_sequence():
+    """exp(-8) per token: the factorised form of Algorithm 1 would overflow; ours must not."""
+    Bt, H, N, D = 1, 2, 2048, 128
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 91)
+    decay = torch.tensor([float(np.exp(-8.0)), 1.0], dtype=torch.float32)
+    o = ltn.ltn_attn_fwd(*gpu(q, k, v, decay))
+    check("O", o, orc.fwd_recurrent(q, k, v, decay), 1e-2)
+
+
+# --------------------------------------------------------------------------- full-size configurations
+
+
+def sampled_chain_check(w, chains, backward=True):
+    """Run the full-size workload on the GPU in the benchmark's launch configuration and
+    compare whole (b,h) chains, chosen across the batch/head range, against the oracle."""
+    q, k, v = synth.make_qkv(w.Bt, w.H, w.N, w.D, w.dtype, w.seed)
+    g = synth.make_do(w.Bt, w.H, w.N, w.D, w.dtype, w.seed)
+    decay = synth.decay_bench_rule(w.H)
+    qd, kd, vd, gd, dd = gpu(q, k, v, g, decay)
+    o = ltn.ltn_attn_fwd(qd, kd, vd, dd, block=w.block)
+    grads = ltn.ltn_attn_bwd(qd, kd, vd, gd, dd, block=w.block) if backward else ()
+    torch.cuda.synchronize()
+    tol = TOL[w.dtype]
+    for (b, h) in chains:
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        dh = decay[h:h + 1]
+        ref = orc.fwd_recurrent(q[sl], k[sl], v[sl], dh)
+        check(f"O[{b},{h}]", o[sl], ref, tol)
+        if backward:
+            refs = orc.bwd_recurrent(q[sl], k[sl], v[sl], g[sl], dh)
+            for n, x, r in zip(("dQ", "dK", "dV"), grads, refs):
+                check(f"{n}[{b},{h}]", x[sl], r, tol)
+    if backward:
+        # property that holds at any size, checked over every chain:
+        # <dQ,Q> = <dK,K> = <dV,V> = <dO,O> per (b,h), since O is linear in each input
+        ref = (gd.double() * o.double()).sum(dim=(2, 3))
+        scale = (gd.double().norm(dim=(2, 3)) * o.double().norm(dim=(2, 3)))
+        for n, x, y in zip(("dQ", "dK", "dV"), grads, (qd, kd, vd)):
+            got = (x.double() * y.double()).sum(dim=(2, 3))
+            assert ((got - ref).abs() / scale).max().item() < 2e-2, n
+
+
+def test_cfg2_385m_shape_sampled():
+    w = synth.CONFIGS["cfg2_385m"]
+    sampled_chain_check(w, [(0, 0), (3, 5), (7, 7)])
+
+
+def test_cfg3_7b_shape_sampled():
+    w = synth.CONFIGS["cfg3_7b"]
+    sampled_chain_check(w, [(0, 0), (1, 13), (3, 31)])
+
+
+def test_long_context_linear_time_and_parity():
+    """Bt=1, H=32, D=128, N doubling: sampled-chain parity at N=65536 and time ~ linear in N."""
+    H, D = 32, 128
+    decay = synth.decay_bench_rule(H)
+    times = {}
+    for N in (16384, 32768, 65536):
+        q, k, v = synth.make_qkv(1, H, N, D, torch.bfloat16, synth.LONG_CONTEXT_SEED)
+        g = synth.make_do(1, H, N, D, torch.bfloat16, synth.LONG_CONTEXT_SEED)
+        qd, kd, vd, gd, dd = gpu(q, k, v, g, decay)
+        for _ in range(2):
+            o = ltn.ltn_attn_fwd(qd, kd, vd, dd)
+            grads = ltn.ltn_attn_bwd(qd, kd, vd, gd, dd)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            o = ltn.ltn_attn_fwd(qd, kd, vd, dd)
+            grads = ltn.ltn_attn_bwd(qd, kd, vd, gd, dd)
+        e1.record()
+        torch.cuda.synchronize()
+        times[N] = e0.elapsed_time(e1) / 3
+        if N == 65536:
+            for h in (0, 31):
+                sl = (slice(0, 1), slice(h, h + 1))
+                check(f"O[{h}]", o[sl], orc.fwd_recurrent(q[sl], k[sl], v[sl], decay[h:h + 1]), 1e-2)
+                refs = orc.bwd_recurrent(q[sl], k[sl], v[sl], g[sl], decay[h:h + 1])
+                for n, x, r in zip(("dQ", "dK", "dV"), grads, refs):
+                    check(f"{n}[{h}]", x[sl], r, 1e-2)
+    for N in (32768, 65536):
+        ratio = times[N] / times[N // 2]
+        assert 1.7 < ratio < 2.3, (times, ratio)
+
+
+def test_decode_config5_sampled():
+    """Bt=64, H=32, D=128: state from a 1024-token prefix, then decode steps; chains sampled."""
+    c = synth.DECODE
+    Bt, H, D, N0 = c["Bt"], c["H"], c["D"], c["prefix"]
+    q, k, v = synth.make_qkv(Bt, H, N0, D, torch.bfloat16, c["seed"])
+    decay = synth.decay_bench_rule(H)
+    qd, kd, vd, dd = gpu(q, k, v, decay)
+    _, kv = ltn.ltn_attn_fwd(qd, kd, vd, dd, return_state=True)
+    picks = [(0, 0), (17, 9), (63, 31)]
+    ref_state = {}
+    for (b, h) in picks:
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        _, s = orc.fwd_recurrent(q[sl], k[sl], v[sl], decay[h:h + 1], return_state=True)
+        check(f"kv0[{b},{h}]", kv[sl], s, 1e-2)
+        ref_state[(b, h)] = s
+    steps = 64
+    for s in range(steps):
+        q1, k1, v1 = synth.make_step_qkv(Bt, H, D, torch.bfloat16, c["seed"], s)
+        o1 = ltn.ltn_attn_decode_step(*gpu(q1, k1, v1), kv, dd)
+        for (b, h) in picks:
+            sl = (slice(b, b + 1), slice(h, h + 1))
+            o_ref, ref_state[(b, h)] = orc.decode_step(q1[sl], k1[sl], v1[sl], ref_state[(b, h)], decay[h:h + 1])
+            check(f"o[{s}][{b},{h}]", o1[sl], o_ref, 1e-2)
+    for (b, h) in picks:
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        check(f"kv[{b},{h}]", kv[sl], ref_state[(b, h)], 1e-2)
