@@ -12,21 +12,26 @@
 // (A,B,C) = (Q,K,V) gives the forward output; the gradient passes reuse the same
 // kernel with permuted operands and, for dK/dV, a reversed token axis.
 //
-// Work split inside a 256-thread workgroup (4 wavefronts of 64 lanes):
-//   * wave w owns the 16 query rows 16w..16w+15 of the block.  It forms the
-//     transposed score tiles P^T[key tile][its rows] with 16x16x32 bf16 MFMA, so
-//     the fp32 accumulators already sit in the lane layout the next MFMA wants as
-//     its B operand: the masked scores never leave registers.
-//   * the output is produced transposed (O^T = C^T P^T + S^T A^T) so every lane
-//     holds four consecutive output features of one token -> 8-byte stores.
-//   * wave w owns state rows [w*D/4, (w+1)*D/4) in fp32 accumulators for the whole
-//     sequence; after each update it publishes a bf16 copy to LDS (double
-//     buffered), which all waves read as the A operand of S^T A^T.
-//   * B and C tiles are staged global -> registers -> LDS one block ahead (double
-//     buffered, padded rows: conflict-free 16-byte reads); operands that must be
-//     read "down the token axis" (C for P C, B^T and C for the state update) use
-//     the LDS transpose read ds_read_b64_tr_b16.
-//   * one workgroup barrier per block.
+// A workgroup is 512 threads = 8 wavefronts with two roles, two waves per SIMD, so
+// that one role's LDS and VALU latencies hide under the other's MFMAs:
+//   * output waves 0..3: wave w owns query rows 16w..16w+15 of the block.  It forms
+//     the transposed score tiles P^T[key tile][its rows] with 16x16x32 bf16 MFMA; the
+//     fp32 accumulators already sit in the lane layout the next MFMA wants as its B
+//     operand (the contraction index is permuted identically on both operands), so
+//     the masked scores never leave registers.  The output is produced transposed
+//     (O^T = C^T P^T + S^T A^T): every lane holds four consecutive output features of
+//     one token -> 8-byte stores.  A fragments come straight from global memory.
+//   * state waves 4..7: wave u owns state rows [u*D/4, (u+1)*D/4) x DV in fp32
+//     accumulators for the whole sequence, applies S <- lambda^len S + (decayed B)^T C
+//     and publishes a bf16 copy [dv][dk] to LDS, which the output waves read as the A
+//     operand of S^T A^T.  These waves also stage the next block's B and C tiles
+//     global -> registers -> LDS.
+//   * LDS tiles and the state copy are double buffered: one barrier per block.  Row
+//     pitches are 32 bytes over a multiple of 256 (measured best for the 16-byte
+//     row reads and for the transpose reads).  Operands read "down the token axis"
+//     (C for P C, B^T and C for the state update) use ds_read_b64_tr_b16.
+//   * wave role and strip are compile-time constants of the code each wave runs, so
+//     causal tile skipping costs no branches inside a block.
 // Only non-negative powers of lambda are formed.
 #include "ltn_kernels.h"
 
@@ -61,66 +66,202 @@ __device__ __forceinline__ bf16x4 to_bf16(const f32x4& x) {
     return __builtin_convertvector(x, bf16x4);
 }
 
+// All VMEM loads issued so far have landed (keeps the compiler's wait-count
+// bookkeeping from carrying "pending" prologue loads into the block loop, where
+// it would otherwise wait for every prefetch right after issuing it).
+__device__ __forceinline__ void retire_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 constexpr int kBlock = 64;
-constexpr int kThreads = 256;
+constexpr int kThreads = 512;
+constexpr int kStageThreads = 256;     // the four state waves
 
 template <int D, int DV>
 struct Cfg {
     static constexpr int KS = D / 32;          // k-steps of a D-long contraction
-    static constexpr int MT = D / 64;          // 16-row state tiles owned per wave
+    static constexpr int MT = D / 64;          // 16-row state tiles owned per state wave
     static constexpr int NT = DV / 16;         // 16-column tiles of the value slice
-    static constexpr int KP = D * 2 + 16;      // LDS row pitch of the B tile / state copy (bytes)
-    static constexpr int VP = DV * 2 + 16;     // LDS row pitch of the C tile (bytes)
-    static constexpr int KC = D / 32;          // 16-byte chunks of B staged per thread
-    static constexpr int VC = (DV >= 32) ? DV / 32 : 1;
-    static constexpr int KB = 0;                       // B tile, 2 buffers
-    static constexpr int VB = 2 * kBlock * KP;         // C tile, 2 buffers
-    static constexpr int SB = VB + 2 * kBlock * VP;    // bf16 state copy [DV][D], 2 buffers
-    static constexpr int TOTAL = SB + 2 * DV * KP;
+    static constexpr int KP = D * 2 + 32;      // LDS row pitch of the B tile / state copy (bytes)
+    static constexpr int VP = DV * 2 + 32;     // LDS row pitch of the C tile (bytes)
+    static constexpr int KC = D / 32;          // 16-byte chunks of B staged per staging thread
+    static constexpr int VC = DV / 32;         // 16-byte chunks of C staged per staging thread
+    static constexpr int KBYTES = kBlock * KP;
+    static constexpr int VBYTES = kBlock * VP;
+    static constexpr int SBYTES = DV * KP;
+    static constexpr int KB = 0;
+    static constexpr int VB = 2 * KBYTES;
+    static constexpr int SB = VB + 2 * VBYTES;
+    static constexpr int TOTAL = SB + 2 * SBYTES;
 };
 
-template <int D, int DV>
-__global__ __launch_bounds__(kThreads, 1)
-void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
+struct Chain {            // what every wave of the workgroup knows about its problem
+    const char* a;        // operands offset to this chain (and value-column slice for c/out)
+    const char* b;
+    const char* c;
+    char* out;
+    const float* state_in;   // offset to this chain and column slice, or nullptr
+    float* state_out;
+    long long N;
+    int T;                // number of 64-token blocks
+    int last_valid;       // tokens in the last block (1..64)
+    int rev;
+    float lam;
+};
+
+// ------------------------------------------------------------------ output waves
+
+template <int D, int DV, int W>
+__device__ __forceinline__ void run_output_wave(const Chain& ch, char* smem, int lane) {
     using C = Cfg<D, DV>;
-    constexpr int KS = C::KS, MT = C::MT, NT = C::NT, KP = C::KP, VP = C::VP;
-    __shared__ __attribute__((aligned(16))) char smem[C::TOTAL];
+    constexpr int KS = C::KS, NT = C::NT, KP = C::KP, VP = C::VP;
+    constexpr long long ROW = D * 2;
+    const int g = lane >> 4, i16 = lane & 15;
+    const float lam = ch.lam;
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int w = tid >> 6;          // wave = query-row strip
-    const int g = lane >> 4;         // 16-lane group
-    const int i16 = lane & 15;
-
-    int chain, within;
-    map_workgroup(blockIdx.x, pb.count * nsplit, pb.chains, chain, within);
-    const int pi = within / nsplit;
-    const int split = within - pi * nsplit;
-    const PassArgs P = pb.p[pi];
-    const int rev = P.rev;
-    const long long N = pb.N;
-    const int T = (int)((N + kBlock - 1) / kBlock);
-    const float lam = pb.decay[chain % pb.H];
-
-    const size_t chain_off = (size_t)chain * (size_t)N * D * 2;
-    const char* Ap = (const char*)P.a + chain_off;
-    const char* Bp = (const char*)P.b + chain_off;
-    const char* Cp = (const char*)P.c + chain_off + (size_t)split * DV * 2;
-    char* Op = (char*)P.out + chain_off + (size_t)split * DV * 2;
-    constexpr size_t ROW = (size_t)D * 2;
-
-    // ---- per-lane decay constants (non-negative exponents only)
-    const float qscale = decay_pow(lam, 16 * w + i16 + 1);     // lambda^(r+1), r = row in block
-    const int d0 = i16 - 4 * g;                                 // (row - key) inside a diagonal tile, j = 0
+    // decay constants (non-negative exponents only)
+    const float qscale = decay_pow(lam, 16 * W + i16 + 1);      // lambda^(r+1), r = row in block
+    const int d0 = i16 - 4 * g;                                  // (row - key) in a diagonal tile at j = 0
     float mdiag[4], moff[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         mdiag[j] = (d0 - j >= 0) ? decay_pow(lam, d0 - j) : 0.0f;
-        moff[j] = decay_pow(lam, 16 + d0 - j);                  // 16 + d0 - j >= 1
+        moff[j] = decay_pow(lam, 16 + d0 - j);                   // 16 + d0 - j >= 1
     }
     const float lam16 = decay_pow(lam, 16), lam32 = decay_pow(lam, 32);
-    float ksc[2][8];                                            // lambda^(len-1-token), token per MFMA k-slot
-    float lamB;
+
+    // cursors for this lane's token row (16W + i16) of block 0
+    const long long r0 = ch.rev ? (ch.N - 1 - (16 * W + i16)) : (long long)(16 * W + i16);
+    const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
+    const char* pq = ch.a + r0 * ROW + (8 * g) * 2;
+    char* po = ch.out + r0 * ROW + (4 * g) * 2;
+
+    Frag Qf[KS], Qn[KS];
+    auto load_q = [&](int valid) {
+        const bool ok = (16 * W + i16) < valid;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) Qn[ks].u = ok ? *(const uint4*)(pq + ks * 64) : uint4{0, 0, 0, 0};
+    };
+    load_q(ch.T == 1 ? ch.last_valid : kBlock);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) Qf[ks] = Qn[ks];
+    retire_loads();
+    __syncthreads();                       // block 0 tiles and the initial state copy are in LDS
+
+    for (int blk = 0; blk < ch.T; ++blk) {
+        const int cur = blk & 1;
+        const bool more = blk + 1 < ch.T;
+        const int valid = more ? kBlock : ch.last_valid;
+        const char* kb = smem + C::KB + cur * C::KBYTES;
+        const char* vb = smem + C::VB + cur * C::VBYTES;
+        const char* sb = smem + C::SB + cur * C::SBYTES;
+
+        if (more) {                        // next block's A fragments, in flight during the math
+            pq += step;
+            load_q((blk + 2 == ch.T) ? ch.last_valid : kBlock);
+        }
+
+        // -- transposed scores P^T[key tile kt <= W][own 16 rows]
+        f32x4 sacc[W + 1];
+#pragma unroll
+        for (int kt = 0; kt <= W; ++kt) sacc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const char* ka = kb + i16 * KP + (8 * g) * 2;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int kt = 0; kt <= W; ++kt) {
+                Frag a;
+                a.u = *(const uint4*)(ka + (16 * kt) * KP + (32 * ks) * 2);
+                sacc[kt] = mfma16(a.v, Qf[ks].v, sacc[kt]);
+            }
+
+        // -- inter-block output (independent of the scores): S^T A^T with the published state
+        f32x4 oi[NT], oe[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            oi[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            oe[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        const char* sa = sb + i16 * KP + (8 * g) * 2;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                Frag a;
+                a.u = *(const uint4*)(sa + (16 * nt) * KP + (32 * ks) * 2);
+                oe[nt] = mfma16(a.v, Qf[ks].v, oe[nt]);
+            }
+
+        // -- mask the scores, round to bf16: they are B operands as they stand
+        bf16x4 Pt[4];
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+            if (kt < W) {
+                const float sc = (W - kt == 1) ? 1.0f : ((W - kt == 2) ? lam16 : lam32);
+                f32x4 m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) m[j] = sacc[kt < W ? kt : 0][j] * (moff[j] * sc);
+                Pt[kt] = to_bf16(m);
+            } else if (kt == W) {
+                f32x4 m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) m[j] = sacc[W][j] * mdiag[j];
+                Pt[kt] = to_bf16(m);
+            } else {
+                Pt[kt] = bf16x4{0, 0, 0, 0};
+            }
+        }
+
+        // -- intra-block output (transposed): O^T += C^T P^T, C read down the token axis
+        const char* va = vb + (4 * g + (i16 >> 2)) * VP + (4 * (i16 & 3)) * 2;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            if (2 * p <= W) {
+                Frag b;
+                b.b[0] = Pt[2 * p];
+                b.b[1] = Pt[2 * p + 1];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    Frag vf;
+                    vf.h[0] = lds_tr16(va + (32 * p) * VP + (16 * nt) * 2);
+                    vf.h[1] = lds_tr16(va + (32 * p + 16) * VP + (16 * nt) * 2);
+                    oi[nt] = mfma16(vf.v, b.v, oi[nt]);
+                }
+            }
+        }
+
+        // -- combine and store: lane holds token (16W + i16), features 16nt + 4g .. +3
+        if ((16 * W + i16) < valid) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                f32x4 r;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) r[j] = oi[nt][j] + qscale * oe[nt][j];
+                *(bf16x4*)(po + 32 * nt) = to_bf16(r);
+            }
+        }
+        po += step;
+
+        if (more) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) Qf[ks] = Qn[ks];
+            __syncthreads();
+        }
+    }
+}
+
+// ------------------------------------------------------------------ state waves
+
+template <int D, int DV>
+__device__ __forceinline__ void run_state_wave(const Chain& ch, char* smem, int lane, int u) {
+    using C = Cfg<D, DV>;
+    constexpr int MT = C::MT, NT = C::NT, KP = C::KP, VP = C::VP;
+    constexpr long long ROW = D * 2;
+    const int g = lane >> 4, i16 = lane & 15;
+    const int stid = u * 64 + lane;                 // 0..255 among the staging threads
+    const int dk0 = u * (D / 4);
+    const float lam = ch.lam;
+
+    // lambda^(len-1-token) per MFMA k-slot, and lambda^len
+    float ksc[2][8], lamB;
     auto set_block_len = [&](int len) {
         lamB = decay_pow(lam, len);
 #pragma unroll
@@ -133,24 +274,22 @@ void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
     };
     set_block_len(kBlock);
 
-    // ---- state: wave w owns rows [dk0, dk0 + D/4) x all DV columns, fp32
-    const int dk0 = w * (D / 4);
+    // running state, fp32
     f32x4 st[MT][NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            if (P.state_in) {
-                const float* s = P.state_in + (size_t)chain * D * D + (size_t)split * DV;
+            if (ch.state_in) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    st[mt][nt][j] = s[(size_t)(dk0 + 16 * mt + 4 * g + j) * D + 16 * nt + i16];
+                    st[mt][nt][j] = ch.state_in[(size_t)(dk0 + 16 * mt + 4 * g + j) * D + 16 * nt + i16];
             } else {
                 st[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
         }
     auto publish_state = [&](int buf) {
-        char* sb = smem + C::SB + buf * (DV * KP);
+        char* sb = smem + C::SB + buf * C::SBYTES;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -158,164 +297,80 @@ void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
                 *(bf16x4*)(sb + (16 * nt + i16) * KP + (dk0 + 16 * mt + 4 * g) * 2) = to_bf16(st[mt][nt]);
     };
 
-    // ---- staging of the next block: global -> registers
+    // staging cursors: this thread's first chunk of the B tile and of the C tile, block 0
+    constexpr int KRPC = kStageThreads / (D / 8);    // tile rows covered per chunk index
+    constexpr int VRPC = kStageThreads / (DV / 8);
+    const int krow = stid / (D / 8), kch = stid % (D / 8);
+    const int vrow = stid / (DV / 8), vch = stid % (DV / 8);
+    const long long rs = ch.rev ? -ROW : ROW;        // byte stride between consecutive block rows
+    const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
+    const char* pk = ch.b + (ch.rev ? (ch.N - 1 - krow) : (long long)krow) * ROW + kch * 16;
+    const char* pv = ch.c + (ch.rev ? (ch.N - 1 - vrow) : (long long)vrow) * ROW + vch * 16;
     uint4 kst[C::KC], vst[C::VC];
-    Frag Qf[KS], Qn[KS];
-    auto grow = [&](long long t) -> size_t { return (size_t)(rev ? (N - 1 - t) : t); };
-    auto load_block = [&](int blk) {
-        const long long t0 = (long long)blk * kBlock;
+    auto load_tiles = [&](int valid) {
 #pragma unroll
-        for (int c = 0; c < C::KC; ++c) {
-            const int id = c * kThreads + tid;
-            const int r = id / (D / 8), ch = id % (D / 8);
-            const long long t = t0 + r;
-            kst[c] = (t < N) ? *(const uint4*)(Bp + grow(t) * ROW + ch * 16) : uint4{0, 0, 0, 0};
-        }
+        for (int c = 0; c < C::KC; ++c)
+            kst[c] = (c * KRPC + krow < valid) ? *(const uint4*)(pk + (long long)(c * KRPC) * rs) : uint4{0, 0, 0, 0};
 #pragma unroll
-        for (int c = 0; c < C::VC; ++c) {
-            const int id = c * kThreads + tid;
-            const int r = id / (DV / 8), ch = id % (DV / 8);
-            const long long t = t0 + r;
-            const bool ok = (t < N) && (r < kBlock);
-            vst[c] = ok ? *(const uint4*)(Cp + grow(t) * ROW + ch * 16) : uint4{0, 0, 0, 0};
-        }
-        const long long tq = t0 + 16 * w + i16;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            Qn[ks].u = (tq < N) ? *(const uint4*)(Ap + grow(tq) * ROW + (32 * ks + 8 * g) * 2)
-                                : uint4{0, 0, 0, 0};
+        for (int c = 0; c < C::VC; ++c)
+            vst[c] = (c * VRPC + vrow < valid) ? *(const uint4*)(pv + (long long)(c * VRPC) * rs) : uint4{0, 0, 0, 0};
     };
     auto stage_to_lds = [&](int buf) {
-        char* kb = smem + C::KB + buf * (kBlock * KP);
-        char* vb = smem + C::VB + buf * (kBlock * VP);
+        char* kb = smem + C::KB + buf * C::KBYTES;
+        char* vb = smem + C::VB + buf * C::VBYTES;
 #pragma unroll
-        for (int c = 0; c < C::KC; ++c) {
-            const int id = c * kThreads + tid;
-            *(uint4*)(kb + (id / (D / 8)) * KP + (id % (D / 8)) * 16) = kst[c];
-        }
+        for (int c = 0; c < C::KC; ++c) *(uint4*)(kb + (c * KRPC + krow) * KP + kch * 16) = kst[c];
 #pragma unroll
-        for (int c = 0; c < C::VC; ++c) {
-            const int id = c * kThreads + tid;
-            const int r = id / (DV / 8);
-            if (r < kBlock) *(uint4*)(vb + r * VP + (id % (DV / 8)) * 16) = vst[c];
-        }
+        for (int c = 0; c < C::VC; ++c) *(uint4*)(vb + (c * VRPC + vrow) * VP + vch * 16) = vst[c];
     };
 
-    // ---- prologue
-    load_block(0);
+    // prologue: block 0 tiles and the initial state copy into buffer 0
+    load_tiles(ch.T == 1 ? ch.last_valid : kBlock);
     publish_state(0);
     stage_to_lds(0);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) Qf[ks] = Qn[ks];
+    retire_loads();
     __syncthreads();
 
-    for (int blk = 0; blk < T; ++blk) {
+    for (int blk = 0; blk < ch.T; ++blk) {
         const int cur = blk & 1;
-        const long long t0 = (long long)blk * kBlock;
-        const char* kb = smem + C::KB + cur * (kBlock * KP);
-        const char* vb = smem + C::VB + cur * (kBlock * VP);
-        const char* sb = smem + C::SB + cur * (DV * KP);
+        const bool more = blk + 1 < ch.T;
+        const char* kb = smem + C::KB + cur * C::KBYTES;
+        const char* vb = smem + C::VB + cur * C::VBYTES;
 
-        if (blk + 1 < T) load_block(blk + 1);          // in flight during this block's math
-        const long long rem = N - t0;
-        if (rem < kBlock) set_block_len((int)rem);      // short last block only
-
-        // -- transposed masked scores P^T[key tile kt][own 16 rows], kept in registers
-        bf16x4 Pt[4];
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt) {
-            if (kt <= w) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    Frag a;
-                    a.u = *(const uint4*)(kb + (16 * kt + i16) * KP + (32 * ks + 8 * g) * 2);
-                    acc = mfma16(a.v, Qf[ks].v, acc);
-                }
-                if (kt == w) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[j] *= mdiag[j];
-                } else {
-                    const int dlt = w - kt;             // 1..3, wave-uniform
-                    const float s = (dlt == 1) ? 1.0f : ((dlt == 2) ? lam16 : lam32);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[j] *= moff[j] * s;
-                }
-                Pt[kt] = to_bf16(acc);
-            } else {
-                Pt[kt] = bf16x4{0, 0, 0, 0};
-            }
+        if (more) {                        // next block's tiles: global -> registers
+            pk += step; pv += step;
+            load_tiles((blk + 2 == ch.T) ? ch.last_valid : kBlock);
+        } else {
+            if (!ch.state_out) break;      // the last update only feeds the returned state
+            if (ch.last_valid != kBlock) set_block_len(ch.last_valid);
         }
 
-        // -- C-tile operands read down the token axis (used by P C and by the state update)
+        // -- C operand down the token axis, all four key tiles
         Frag Vf[2][NT];
+        const char* va = vb + (4 * g + (i16 >> 2)) * VP + (4 * (i16 & 3)) * 2;
 #pragma unroll
         for (int p = 0; p < 2; ++p)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const char* a0 = vb + (32 * p + 4 * g + (i16 >> 2)) * VP + (16 * nt + 4 * (i16 & 3)) * 2;
-                Vf[p][nt].h[0] = lds_tr16(a0);
-                Vf[p][nt].h[1] = lds_tr16(a0 + 16 * VP);
+                Vf[p][nt].h[0] = lds_tr16(va + (32 * p) * VP + (16 * nt) * 2);
+                Vf[p][nt].h[1] = lds_tr16(va + (32 * p + 16) * VP + (16 * nt) * 2);
             }
 
-        // -- intra-block output (transposed): O^T += C^T P^T
-        f32x4 oi[NT], oe[NT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            oi[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            oe[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            if (2 * p <= w) {
-                Frag b;
-                b.b[0] = Pt[2 * p];
-                b.b[1] = Pt[2 * p + 1];
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) oi[nt] = mfma16(Vf[p][nt].v, b.v, oi[nt]);
-            }
-        }
-
-        // -- inter-block output: S^T A^T with the published bf16 state
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                Frag a;
-                a.u = *(const uint4*)(sb + (16 * nt + i16) * KP + (32 * ks + 8 * g) * 2);
-                oe[nt] = mfma16(a.v, Qf[ks].v, oe[nt]);
-            }
-
-        // -- combine and store: lane holds token (16w + i16), features 16nt + 4g .. +3
-        {
-            const long long t = t0 + 16 * w + i16;
-            if (t < N) {
-                char* orow = Op + grow(t) * ROW + (4 * g) * 2;
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    f32x4 r;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) r[j] = oi[nt][j] + qscale * oe[nt][j];
-                    *(bf16x4*)(orow + 32 * nt) = to_bf16(r);
-                }
-            }
-        }
-
-        // -- state update: S <- lambda^len S + (decayed B)^T C
+        // -- S <- lambda^len S + (decayed B)^T C
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) st[mt][nt][j] *= lamB;
+        const char* kt0 = kb + (4 * g + (i16 >> 2)) * KP + (dk0 + 4 * (i16 & 3)) * 2;
 #pragma unroll
         for (int p = 0; p < 2; ++p)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const char* a0 = kb + (32 * p + 4 * g + (i16 >> 2)) * KP + (dk0 + 16 * mt + 4 * (i16 & 3)) * 2;
                 Frag a;
-                a.h[0] = lds_tr16(a0);
-                a.h[1] = lds_tr16(a0 + 16 * KP);
+                a.h[0] = lds_tr16(kt0 + (32 * p) * KP + (16 * mt) * 2);
+                a.h[1] = lds_tr16(kt0 + (32 * p + 16) * KP + (16 * mt) * 2);
                 f32x8 af = __builtin_convertvector(a.v, f32x8);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) af[j] *= ksc[p][j];
@@ -324,25 +379,60 @@ void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
                 for (int nt = 0; nt < NT; ++nt) st[mt][nt] = mfma16(a.v, Vf[p][nt].v, st[mt][nt]);
             }
 
-        // -- publish for the next block, then hand over the staged tiles
-        if (blk + 1 < T) {
+        if (more) {
             publish_state(cur ^ 1);
             stage_to_lds(cur ^ 1);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) Qf[ks] = Qn[ks];
+            __syncthreads();
         }
-        __syncthreads();
     }
 
-    if (P.state_out) {
-        float* s = P.state_out + (size_t)chain * D * D + (size_t)split * DV;
+    if (ch.state_out) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    s[(size_t)(dk0 + 16 * mt + 4 * g + j) * D + 16 * nt + i16] = st[mt][nt][j];
+                    ch.state_out[(size_t)(dk0 + 16 * mt + 4 * g + j) * D + 16 * nt + i16] = st[mt][nt][j];
+    }
+}
+
+template <int D, int DV>
+__global__ __launch_bounds__(kThreads)
+void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
+    using C = Cfg<D, DV>;
+    __shared__ __attribute__((aligned(16))) char smem[C::TOTAL];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: role dispatch is a uniform branch
+
+    int chain, within;
+    map_workgroup(blockIdx.x, pb.count * nsplit, pb.chains, chain, within);
+    const int pi = within / nsplit;
+    const int split = within - pi * nsplit;
+    const PassArgs P = pb.p[pi];
+
+    Chain ch;
+    const size_t chain_off = (size_t)chain * (size_t)pb.N * D * 2;
+    const size_t col_off = (size_t)split * DV * 2;
+    ch.a = (const char*)P.a + chain_off;
+    ch.b = (const char*)P.b + chain_off;
+    ch.c = (const char*)P.c + chain_off + col_off;
+    ch.out = (char*)P.out + chain_off + col_off;
+    ch.state_in = P.state_in ? P.state_in + (size_t)chain * D * D + (size_t)split * DV : nullptr;
+    ch.state_out = P.state_out ? P.state_out + (size_t)chain * D * D + (size_t)split * DV : nullptr;
+    ch.N = pb.N;
+    ch.T = (int)((pb.N + kBlock - 1) / kBlock);
+    ch.last_valid = (int)(pb.N - (long long)(ch.T - 1) * kBlock);
+    ch.rev = P.rev;
+    ch.lam = pb.decay[chain % pb.H];
+
+    switch (wave) {
+        case 0: run_output_wave<D, DV, 0>(ch, smem, lane); break;
+        case 1: run_output_wave<D, DV, 1>(ch, smem, lane); break;
+        case 2: run_output_wave<D, DV, 2>(ch, smem, lane); break;
+        case 3: run_output_wave<D, DV, 3>(ch, smem, lane); break;
+        default: run_state_wave<D, DV>(ch, smem, lane, wave - 4); break;
     }
 }
 
