@@ -44,12 +44,41 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(8 * sizeof(float)))) float f32x8;
 
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
 union Frag {          // one 16x16x32 MFMA operand: 8 bf16 per lane
     bf16x8 v;
-    uint4 u;
+    u32x4 u;
     s16x4 h[2];
     bf16x4 b[2];
 };
+
+// Global prefetch loads are issued from inline assembly and waited for with explicit
+// vmcnt counts.  Left to the compiler, the loads that rotate through register sets two
+// blocks ahead make its wait-count bookkeeping give up at the loop header and wait for
+// every load right after issuing it (measured: the kernel then runs at memory latency,
+// not bandwidth).  VMEM operations retire in issue order, so "vmcnt(n)" with n = the
+// number of VMEM operations issued after the wanted loads is exact; a smaller n is safe.
+// The destination is an in/out operand and every prefetch load is unconditional, so a
+// register set is one variable updated in place: the compiler has no reason to copy it
+// (a copy made between issue and wait would read stale data).
+__device__ __forceinline__ void gload16(u32x4& r, const char* p) {
+    asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(r) : "v"(p) : "memory");
+}
+// wait until at most N VMEM operations are outstanding; the operands tie the wait to the
+// registers it protects so that no use of them can be scheduled above it
+template <int N>
+__device__ __forceinline__ void wait_vm(u32x4& a) { asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N) : "memory"); }
+template <int N>
+__device__ __forceinline__ void wait_vm(u32x4& a, u32x4& b) { asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory"); }
+template <int N, int CNT>
+__device__ __forceinline__ void wait_vm_all(u32x4 (&r)[CNT]) {
+    static_assert(CNT >= 1 && CNT <= 4, "register sets of 1..4 fragments");
+    if constexpr (CNT == 1) wait_vm<N>(r[0]);
+    else if constexpr (CNT == 2) wait_vm<N>(r[0], r[1]);
+    else if constexpr (CNT == 3) { wait_vm<N>(r[0], r[1]); wait_vm<N>(r[2]); }
+    else { wait_vm<N>(r[0], r[1]); wait_vm<N>(r[2], r[3]); }
+}
 
 __device__ __forceinline__ s16x4 lds_tr16(const char* p) {
     // 16 lanes give the addresses of a 4 x 16 tile of 16-bit elements (lane s: row
@@ -65,11 +94,6 @@ __device__ __forceinline__ f32x4 mfma16(const bf16x8& a, const bf16x8& b, const 
 __device__ __forceinline__ bf16x4 to_bf16(const f32x4& x) {
     return __builtin_convertvector(x, bf16x4);
 }
-
-// All VMEM loads issued so far have landed (keeps the compiler's wait-count
-// bookkeeping from carrying "pending" prologue loads into the block loop, where
-// it would otherwise wait for every prefetch right after issuing it).
-__device__ __forceinline__ void retire_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 constexpr int kBlock = 64;
 constexpr int kThreads = 512;
@@ -134,30 +158,37 @@ __device__ __forceinline__ void run_output_wave(const Chain& ch, char* smem, int
     const char* pq = ch.a + r0 * ROW + (8 * g) * 2;
     char* po = ch.out + r0 * ROW + (4 * g) * 2;
 
-    Frag Qf[KS], Qn[KS];
-    auto load_q = [&](int valid) {
-        const bool ok = (16 * W + i16) < valid;
+    // A fragments: three rotating register sets, loaded two blocks ahead (one block of
+    // loads in flight per wave does not cover HBM latency under load).  Loads are
+    // unconditional: a row past the end of the last block reads the chain's last valid row
+    // instead and is zeroed after it lands.
+    auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
+    auto load_q = [&](u32x4 (&Q)[KS], int b) {
+        b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block (ignored)
+        const int row = 16 * W + i16, valid = valid_of(b);
+        const char* p = pq + (long long)b * step;
+        if (row >= valid) p -= (long long)(row - (valid - 1)) * (ch.rev ? -ROW : ROW);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) Qn[ks].u = ok ? *(const uint4*)(pq + ks * 64) : uint4{0, 0, 0, 0};
+        for (int ks = 0; ks < KS; ++ks) gload16(Q[ks], p + ks * 64);
     };
-    load_q(ch.T == 1 ? ch.last_valid : kBlock);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) Qf[ks] = Qn[ks];
-    retire_loads();
-    __syncthreads();                       // block 0 tiles and the initial state copy are in LDS
 
-    for (int blk = 0; blk < ch.T; ++blk) {
+    auto do_block = [&](int blk, u32x4 (&Qr)[KS], u32x4 (&Qin)[KS]) {
         const int cur = blk & 1;
         const bool more = blk + 1 < ch.T;
-        const int valid = more ? kBlock : ch.last_valid;
+        const int valid = valid_of(blk);
         const char* kb = smem + C::KB + cur * C::KBYTES;
         const char* vb = smem + C::VB + cur * C::VBYTES;
         const char* sb = smem + C::SB + cur * C::SBYTES;
 
-        if (more) {                        // next block's A fragments, in flight during the math
-            pq += step;
-            load_q((blk + 2 == ch.T) ? ch.last_valid : kBlock);
-        }
+        // Q(blk) was issued two blocks ago; since then this wave issued the NT stores of
+        // each of two blocks and the KS loads of Q(blk+1) (blocks 0 and 1 were retired in
+        // the prologue, where any count is safe).
+        wait_vm_all<2 * NT + KS>(Qr);
+        Frag Qf[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) Qf[ks].u = ((16 * W + i16) < valid) ? Qr[ks] : u32x4{0, 0, 0, 0};
+
+        load_q(Qin, blk + 2);              // in flight during this block and the next
 
         // -- transposed scores P^T[key tile kt <= W][own 16 rows]
         f32x4 sacc[W + 1];
@@ -169,7 +200,7 @@ __device__ __forceinline__ void run_output_wave(const Chain& ch, char* smem, int
 #pragma unroll
             for (int kt = 0; kt <= W; ++kt) {
                 Frag a;
-                a.u = *(const uint4*)(ka + (16 * kt) * KP + (32 * ks) * 2);
+                a.u = *(const u32x4*)(ka + (16 * kt) * KP + (32 * ks) * 2);
                 sacc[kt] = mfma16(a.v, Qf[ks].v, sacc[kt]);
             }
 
@@ -186,7 +217,7 @@ __device__ __forceinline__ void run_output_wave(const Chain& ch, char* smem, int
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 Frag a;
-                a.u = *(const uint4*)(sa + (16 * nt) * KP + (32 * ks) * 2);
+                a.u = *(const u32x4*)(sa + (16 * nt) * KP + (32 * ks) * 2);
                 oe[nt] = mfma16(a.v, Qf[ks].v, oe[nt]);
             }
 
@@ -229,23 +260,37 @@ __device__ __forceinline__ void run_output_wave(const Chain& ch, char* smem, int
         }
 
         // -- combine and store: lane holds token (16W + i16), features 16nt + 4g .. +3
-        if ((16 * W + i16) < valid) {
+        if (more || (16 * W + i16) < valid) {     // every lane stores in a full block
+            char* p = po + (long long)blk * step;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 f32x4 r;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) r[j] = oi[nt][j] + qscale * oe[nt][j];
-                *(bf16x4*)(po + 32 * nt) = to_bf16(r);
+                *(bf16x4*)(p + 32 * nt) = to_bf16(r);
             }
         }
-        po += step;
+        if (more) __syncthreads();
+    };
 
-        if (more) {
+    u32x4 Q0[KS], Q1[KS], Q2[KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) Qf[ks] = Qn[ks];
-            __syncthreads();
-        }
+    for (int ks = 0; ks < KS; ++ks) Q0[ks] = Q1[ks] = Q2[ks] = u32x4{0, 0, 0, 0};
+    load_q(Q0, 0);
+    load_q(Q1, 1);
+    wait_vm_all<0>(Q0);
+    wait_vm_all<0>(Q1);
+    __syncthreads();                       // block 0 tiles and the initial state copy are in LDS
+
+    for (int blk = 0; blk < ch.T; blk += 3) {
+        do_block(blk, Q0, Q2);
+        if (blk + 1 < ch.T) do_block(blk + 1, Q1, Q0);
+        if (blk + 2 < ch.T) do_block(blk + 2, Q2, Q1);
     }
+    // the last two prefetches were never consumed: retire them before the registers die
+    wait_vm_all<0>(Q0);
+    wait_vm_all<0>(Q1);
+    wait_vm_all<0>(Q2);
 }
 
 // ------------------------------------------------------------------ state waves
@@ -306,42 +351,55 @@ __device__ __forceinline__ void run_state_wave(const Chain& ch, char* smem, int 
     const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
     const char* pk = ch.b + (ch.rev ? (ch.N - 1 - krow) : (long long)krow) * ROW + kch * 16;
     const char* pv = ch.c + (ch.rev ? (ch.N - 1 - vrow) : (long long)vrow) * ROW + vch * 16;
-    uint4 kst[C::KC], vst[C::VC];
-    auto load_tiles = [&](int valid) {
+    // Two staging register sets: block b+1 is "ready" (landed or landing) while block b+2
+    // is being fetched, so two blocks of loads are in flight per workgroup.  Loads are
+    // unconditional; rows past the end of the last block read its last valid row and are
+    // zeroed when staged.
+    struct Stage { u32x4 k[C::KC]; u32x4 v[C::VC]; };
+    auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
+    auto load_tiles = [&](Stage& t, int b) {
+        b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block (ignored)
+        const int valid = valid_of(b);
+        const char* k0 = pk + (long long)b * step;
+        const char* v0 = pv + (long long)b * step;
 #pragma unroll
-        for (int c = 0; c < C::KC; ++c)
-            kst[c] = (c * KRPC + krow < valid) ? *(const uint4*)(pk + (long long)(c * KRPC) * rs) : uint4{0, 0, 0, 0};
+        for (int c = 0; c < C::KC; ++c) {
+            int r = c * KRPC + krow;
+            r = (r < valid ? r : valid - 1) - krow;
+            gload16(t.k[c], k0 + (long long)r * rs);
+        }
 #pragma unroll
-        for (int c = 0; c < C::VC; ++c)
-            vst[c] = (c * VRPC + vrow < valid) ? *(const uint4*)(pv + (long long)(c * VRPC) * rs) : uint4{0, 0, 0, 0};
+        for (int c = 0; c < C::VC; ++c) {
+            int r = c * VRPC + vrow;
+            r = (r < valid ? r : valid - 1) - vrow;
+            gload16(t.v[c], v0 + (long long)r * rs);
+        }
     };
-    auto stage_to_lds = [&](int buf) {
+    auto wait_tiles = [&](Stage& t, bool newer_in_flight) {
+        // the KC + VC loads of the following block are always issued after these
+        if (newer_in_flight) { wait_vm_all<C::KC + C::VC>(t.k); wait_vm_all<C::KC + C::VC>(t.v); }
+        else { wait_vm_all<0>(t.k); wait_vm_all<0>(t.v); }
+    };
+    auto stage_to_lds = [&](const Stage& t, int buf, int valid) {
         char* kb = smem + C::KB + buf * C::KBYTES;
         char* vb = smem + C::VB + buf * C::VBYTES;
 #pragma unroll
-        for (int c = 0; c < C::KC; ++c) *(uint4*)(kb + (c * KRPC + krow) * KP + kch * 16) = kst[c];
+        for (int c = 0; c < C::KC; ++c)
+            *(u32x4*)(kb + (c * KRPC + krow) * KP + kch * 16) = (c * KRPC + krow < valid) ? t.k[c] : u32x4{0, 0, 0, 0};
 #pragma unroll
-        for (int c = 0; c < C::VC; ++c) *(uint4*)(vb + (c * VRPC + vrow) * VP + vch * 16) = vst[c];
+        for (int c = 0; c < C::VC; ++c)
+            *(u32x4*)(vb + (c * VRPC + vrow) * VP + vch * 16) = (c * VRPC + vrow < valid) ? t.v[c] : u32x4{0, 0, 0, 0};
     };
 
-    // prologue: block 0 tiles and the initial state copy into buffer 0
-    load_tiles(ch.T == 1 ? ch.last_valid : kBlock);
-    publish_state(0);
-    stage_to_lds(0);
-    retire_loads();
-    __syncthreads();
-
-    for (int blk = 0; blk < ch.T; ++blk) {
+    auto do_block = [&](int blk, Stage& ready, Stage& incoming) -> bool {
         const int cur = blk & 1;
         const bool more = blk + 1 < ch.T;
         const char* kb = smem + C::KB + cur * C::KBYTES;
         const char* vb = smem + C::VB + cur * C::VBYTES;
 
-        if (more) {                        // next block's tiles: global -> registers
-            pk += step; pv += step;
-            load_tiles((blk + 2 == ch.T) ? ch.last_valid : kBlock);
-        } else {
-            if (!ch.state_out) break;      // the last update only feeds the returned state
+        load_tiles(incoming, blk + 2);     // global -> registers, two blocks ahead
+        if (!more) {
+            if (!ch.state_out) return false;   // the last update only feeds the returned state
             if (ch.last_valid != kBlock) set_block_len(ch.last_valid);
         }
 
@@ -381,10 +439,33 @@ __device__ __forceinline__ void run_state_wave(const Chain& ch, char* smem, int 
 
         if (more) {
             publish_state(cur ^ 1);
-            stage_to_lds(cur ^ 1);
+            wait_tiles(ready, true);
+            stage_to_lds(ready, cur ^ 1, valid_of(blk + 1));
             __syncthreads();
         }
+        return more;
+    };
+
+    // prologue: block 0 tiles and the initial state copy into buffer 0; block 1 in flight
+    Stage sa_, sb_;
+#pragma unroll
+    for (int c = 0; c < C::KC; ++c) sa_.k[c] = sb_.k[c] = u32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int c = 0; c < C::VC; ++c) sa_.v[c] = sb_.v[c] = u32x4{0, 0, 0, 0};
+    load_tiles(sa_, 0);
+    publish_state(0);
+    wait_tiles(sa_, false);
+    stage_to_lds(sa_, 0, valid_of(0));
+    load_tiles(sa_, 1);
+    __syncthreads();
+
+    for (int blk = 0; blk < ch.T; blk += 2) {
+        if (!do_block(blk, sa_, sb_)) break;
+        if (!do_block(blk + 1, sb_, sa_)) break;
     }
+    // prefetches past the last block were never consumed: retire them before the registers die
+    wait_tiles(sa_, false);
+    wait_tiles(sb_, false);
 
     if (ch.state_out) {
 #pragma unroll
