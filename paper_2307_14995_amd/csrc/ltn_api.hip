@@ -16,15 +16,16 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // split is only as deep as needed to put a workgroup on each of the 256 compute
 // units.  LTN_ATTN_DV (debug only) overrides the choice.
 int pick_dv(long long chain_passes, int D, ltn_dtype dtype) {
+    // bf16 kernel: slices of 64 or 32 columns (D = 128), 64 or 32 (D = 64); fp32: D or D/2
+    const int hi = (dtype == LTN_BF16) ? 64 : D;
+    const int lo = (dtype == LTN_BF16) ? 32 : D / 2;
     if (const char* e = std::getenv("LTN_ATTN_DV")) {
         const int v = std::atoi(e);
-        const int lo = (dtype == LTN_BF16) ? 32 : D / 2;
-        if ((v == D || v == D / 2 || v == D / 4) && v >= lo) return v;
+        if ((v == D || v == D / 2 || v == D / 4) && v >= lo && v <= hi) return v;
     }
-    if (chain_passes >= 512) return D;
-    if (dtype == LTN_F32) return D / 2;
-    if (chain_passes >= 128 || D == 64) return D / 2;
-    return D / 4;
+    if (dtype == LTN_F32) return chain_passes >= 512 ? D : D / 2;
+    if (chain_passes * (D / hi) >= 256) return hi;
+    return lo;
 }
 
 ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype dtype, int* blk_out) {

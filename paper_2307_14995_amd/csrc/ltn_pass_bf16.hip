@@ -111,9 +111,10 @@ struct Cfg {
     static constexpr int KBYTES = kBlock * KP;
     static constexpr int VBYTES = kBlock * VP;
     static constexpr int SBYTES = DV * KP;
-    static constexpr int KB = 0;
-    static constexpr int VB = 2 * KBYTES;
-    static constexpr int SB = VB + 2 * VBYTES;
+    static constexpr int KB = 0;                       // B tile, 2 buffers
+    static constexpr int AB = 2 * KBYTES;              // A tile, 2 buffers
+    static constexpr int VB = 4 * KBYTES;              // C tile, 2 buffers
+    static constexpr int SB = VB + 2 * VBYTES;         // bf16 state copy [DV][D], 2 buffers
     static constexpr int TOTAL = SB + 2 * SBYTES;
 };
 
@@ -152,43 +153,31 @@ __device__ __forceinline__ void run_output_wave(const Chain& ch, char* smem, int
     }
     const float lam16 = decay_pow(lam, 16), lam32 = decay_pow(lam, 32);
 
-    // cursors for this lane's token row (16W + i16) of block 0
+    // output cursor for this lane's token row (16W + i16) of block 0
     const long long r0 = ch.rev ? (ch.N - 1 - (16 * W + i16)) : (long long)(16 * W + i16);
     const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
-    const char* pq = ch.a + r0 * ROW + (8 * g) * 2;
     char* po = ch.out + r0 * ROW + (4 * g) * 2;
-
-    // A fragments: three rotating register sets, loaded two blocks ahead (one block of
-    // loads in flight per wave does not cover HBM latency under load).  Loads are
-    // unconditional: a row past the end of the last block reads the chain's last valid row
-    // instead and is zeroed after it lands.
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
-    auto load_q = [&](u32x4 (&Q)[KS], int b) {
-        b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block (ignored)
-        const int row = 16 * W + i16, valid = valid_of(b);
-        const char* p = pq + (long long)b * step;
-        if (row >= valid) p -= (long long)(row - (valid - 1)) * (ch.rev ? -ROW : ROW);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) gload16(Q[ks], p + ks * 64);
-    };
 
-    auto do_block = [&](int blk, u32x4 (&Qr)[KS], u32x4 (&Qin)[KS]) {
+    // Output waves issue no global loads: their stores retire in issue order with any
+    // load that follows, and a store's acknowledgement is slow enough to stall a
+    // prefetch queued behind it.  All loads belong to the state waves.
+    __syncthreads();                       // block 0 tiles and the initial state copy are in LDS
+
+    for (int blk = 0; blk < ch.T; ++blk) {
         const int cur = blk & 1;
         const bool more = blk + 1 < ch.T;
         const int valid = valid_of(blk);
         const char* kb = smem + C::KB + cur * C::KBYTES;
+        const char* ab = smem + C::AB + cur * C::KBYTES;
         const char* vb = smem + C::VB + cur * C::VBYTES;
         const char* sb = smem + C::SB + cur * C::SBYTES;
 
-        // Q(blk) was issued two blocks ago; since then this wave issued the NT stores of
-        // each of two blocks and the KS loads of Q(blk+1) (blocks 0 and 1 were retired in
-        // the prologue, where any count is safe).
-        wait_vm_all<2 * NT + KS>(Qr);
+        // -- own A fragments (rows past the end of the last block were staged as zeros)
         Frag Qf[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) Qf[ks].u = ((16 * W + i16) < valid) ? Qr[ks] : u32x4{0, 0, 0, 0};
-
-        load_q(Qin, blk + 2);              // in flight during this block and the next
+        for (int ks = 0; ks < KS; ++ks)
+            Qf[ks].u = *(const u32x4*)(ab + (16 * W + i16) * KP + (32 * ks + 8 * g) * 2);
 
         // -- transposed scores P^T[key tile kt <= W][own 16 rows]
         f32x4 sacc[W + 1];
@@ -271,26 +260,7 @@ __device__ __forceinline__ void run_output_wave(const Chain& ch, char* smem, int
             }
         }
         if (more) __syncthreads();
-    };
-
-    u32x4 Q0[KS], Q1[KS], Q2[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) Q0[ks] = Q1[ks] = Q2[ks] = u32x4{0, 0, 0, 0};
-    load_q(Q0, 0);
-    load_q(Q1, 1);
-    wait_vm_all<0>(Q0);
-    wait_vm_all<0>(Q1);
-    __syncthreads();                       // block 0 tiles and the initial state copy are in LDS
-
-    for (int blk = 0; blk < ch.T; blk += 3) {
-        do_block(blk, Q0, Q2);
-        if (blk + 1 < ch.T) do_block(blk + 1, Q1, Q0);
-        if (blk + 2 < ch.T) do_block(blk + 2, Q2, Q1);
     }
-    // the last two prefetches were never consumed: retire them before the registers die
-    wait_vm_all<0>(Q0);
-    wait_vm_all<0>(Q1);
-    wait_vm_all<0>(Q2);
 }
 
 // ------------------------------------------------------------------ state waves
@@ -350,23 +320,27 @@ __device__ __forceinline__ void run_state_wave(const Chain& ch, char* smem, int 
     const long long rs = ch.rev ? -ROW : ROW;        // byte stride between consecutive block rows
     const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
     const char* pk = ch.b + (ch.rev ? (ch.N - 1 - krow) : (long long)krow) * ROW + kch * 16;
+    const char* pa = ch.a + (ch.rev ? (ch.N - 1 - krow) : (long long)krow) * ROW + kch * 16;
     const char* pv = ch.c + (ch.rev ? (ch.N - 1 - vrow) : (long long)vrow) * ROW + vch * 16;
     // Two staging register sets: block b+1 is "ready" (landed or landing) while block b+2
     // is being fetched, so two blocks of loads are in flight per workgroup.  Loads are
     // unconditional; rows past the end of the last block read its last valid row and are
     // zeroed when staged.
-    struct Stage { u32x4 k[C::KC]; u32x4 v[C::VC]; };
+    struct Stage { u32x4 a[C::KC]; u32x4 k[C::KC]; u32x4 v[C::VC]; };
+    constexpr int kLoads = 2 * C::KC + C::VC;          // VMEM loads per block per thread
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
     auto load_tiles = [&](Stage& t, int b) {
         b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block (ignored)
         const int valid = valid_of(b);
         const char* k0 = pk + (long long)b * step;
+        const char* a0 = pa + (long long)b * step;
         const char* v0 = pv + (long long)b * step;
 #pragma unroll
         for (int c = 0; c < C::KC; ++c) {
             int r = c * KRPC + krow;
             r = (r < valid ? r : valid - 1) - krow;
             gload16(t.k[c], k0 + (long long)r * rs);
+            gload16(t.a[c], a0 + (long long)r * rs);
         }
 #pragma unroll
         for (int c = 0; c < C::VC; ++c) {
@@ -376,16 +350,20 @@ __device__ __forceinline__ void run_state_wave(const Chain& ch, char* smem, int 
         }
     };
     auto wait_tiles = [&](Stage& t, bool newer_in_flight) {
-        // the KC + VC loads of the following block are always issued after these
-        if (newer_in_flight) { wait_vm_all<C::KC + C::VC>(t.k); wait_vm_all<C::KC + C::VC>(t.v); }
-        else { wait_vm_all<0>(t.k); wait_vm_all<0>(t.v); }
+        // the loads of the following block are always issued after these
+        if (newer_in_flight) { wait_vm_all<kLoads>(t.k); wait_vm_all<kLoads>(t.a); wait_vm_all<kLoads>(t.v); }
+        else { wait_vm_all<0>(t.k); wait_vm_all<0>(t.a); wait_vm_all<0>(t.v); }
     };
     auto stage_to_lds = [&](const Stage& t, int buf, int valid) {
         char* kb = smem + C::KB + buf * C::KBYTES;
+        char* ab = smem + C::AB + buf * C::KBYTES;
         char* vb = smem + C::VB + buf * C::VBYTES;
 #pragma unroll
-        for (int c = 0; c < C::KC; ++c)
-            *(u32x4*)(kb + (c * KRPC + krow) * KP + kch * 16) = (c * KRPC + krow < valid) ? t.k[c] : u32x4{0, 0, 0, 0};
+        for (int c = 0; c < C::KC; ++c) {
+            const bool ok = c * KRPC + krow < valid;
+            *(u32x4*)(kb + (c * KRPC + krow) * KP + kch * 16) = ok ? t.k[c] : u32x4{0, 0, 0, 0};
+            *(u32x4*)(ab + (c * KRPC + krow) * KP + kch * 16) = ok ? t.a[c] : u32x4{0, 0, 0, 0};
+        }
 #pragma unroll
         for (int c = 0; c < C::VC; ++c)
             *(u32x4*)(vb + (c * VRPC + vrow) * VP + vch * 16) = (c * VRPC + vrow < valid) ? t.v[c] : u32x4{0, 0, 0, 0};
@@ -449,7 +427,7 @@ __device__ __forceinline__ void run_state_wave(const Chain& ch, char* smem, int 
     // prologue: block 0 tiles and the initial state copy into buffer 0; block 1 in flight
     Stage sa_, sb_;
 #pragma unroll
-    for (int c = 0; c < C::KC; ++c) sa_.k[c] = sb_.k[c] = u32x4{0, 0, 0, 0};
+    for (int c = 0; c < C::KC; ++c) sa_.k[c] = sb_.k[c] = sa_.a[c] = sb_.a[c] = u32x4{0, 0, 0, 0};
 #pragma unroll
     for (int c = 0; c < C::VC; ++c) sa_.v[c] = sb_.v[c] = u32x4{0, 0, 0, 0};
     load_tiles(sa_, 0);
@@ -529,7 +507,6 @@ hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream) {
-    if (D == 128 && dv == 128) return launch_t<128, 128>(pb, stream);
     if (D == 128 && dv == 64) return launch_t<128, 64>(pb, stream);
     if (D == 128 && dv == 32) return launch_t<128, 32>(pb, stream);
     if (D == 64 && dv == 64) return launch_t<64, 64>(pb, stream);
