@@ -36,6 +36,11 @@ def flops_per_token_head(D: int, B: int):
     }
 
 
+# HBM bytes per backward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
+# the same counters' reading of a plain copy of known size); see profiles/.  Keyed by workload.
+MEASURED_BWD_TRAFFIC_BYTES = {"cfg3_7b": 2.681e9}
+
+
 def algorithmic_bytes_per_token_head(D: int, esize: int):
     """Ideal HBM traffic: fwd reads Q,K,V writes O; bwd reads Q,K,V,dO writes dQ,dK,dV."""
     return {"fwd": 4 * D * esize, "bwd": 7 * D * esize}
@@ -114,7 +119,9 @@ def main() -> int:
     roofline = {
         "bound": "hbm", "kernel": "pass_bf16_kernel (backward launch: dQ, dK, dV passes)",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": MEASURED_BWD_TRAFFIC_BYTES.get(args.workload),
+        "algorithmic_bytes": bwd_bytes,
         "kernel_ms": round(bwd_ms, 4),
         "fwd_kernel_ms": round(fwd_ms, 4),
         "fwd_achieved_GBs": round(ab["fwd"] * token_heads / (fwd_ms * 1e-3) / 1e9, 1),
