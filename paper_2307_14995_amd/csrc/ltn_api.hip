@@ -144,6 +144,12 @@ ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void*
     }
     const long long chains = (long long)Bt * H;
     if (chains == 0 || N == 0) return LTN_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == LTN_BF16) {
+        // one launch: dK and dV fused per column half (shared operand tiles), dQ as a pass
+        ltn::BwdBatch bb = {q, k, v, d_o, dq, dk, dv, decay, (int)chains, H, N};
+        return ltn::launch_bwd_bf16(bb, D, st) == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+    }
     // The three gradients are three decayed linear-attention passes with permuted
     // operands (derivative of O = ((Q K^T)(.)M) V; App. B Algorithm 4 corrected):
     //   dQ = ((dO V^T)(.)M)   K   -> pass(dO, V, K), first token -> last
@@ -158,7 +164,7 @@ ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void*
     pb.p[0] = ltn::PassArgs{k, q, d_o, dv, nullptr, nullptr, 1};
     pb.p[1] = ltn::PassArgs{v, d_o, q, dk, nullptr, nullptr, 1};
     pb.p[2] = ltn::PassArgs{d_o, v, k, dq, nullptr, nullptr, 0};
-    return run_passes(pb, D, blk, dtype, static_cast<hipStream_t>(stream));
+    return run_passes(pb, D, blk, dtype, st);
 }
 
 ltn_status ltn_attn_decode_step(const void* q, const void* k, const void* v, void* o,
