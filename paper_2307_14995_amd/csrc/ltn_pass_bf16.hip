@@ -28,16 +28,19 @@
 //     (the contraction index is permuted identically on both operands), so the masked
 //     scores never leave registers.  The output is produced transposed
 //     (O^T = C^T P^T + S^T A^T): every lane holds four consecutive output features of
-//     one token -> 8-byte stores.
+//     one token -> 8-byte stores.  Its A fragments come straight from global memory
+//     into three rotating register sets, two blocks ahead.
 //   * state waves 4..7: wave u owns state rows [u*D/4, (u+1)*D/4) x DV in fp32
 //     accumulators for the whole sequence, applies S <- lambda^len S + (decayed B)^T C
-//     and publishes a bf16 copy [dv][dk] to LDS, which the output waves read as the A
-//     operand of S^T A^T.  These waves also stage the coming blocks' tiles
-//     global -> registers -> LDS, two blocks ahead.
-//   * LDS tiles and state copies are double buffered: one barrier per block.  Row
-//     pitches are 32 bytes over a multiple of 256 (measured best for the 16-byte row
-//     reads and the transpose reads).  Operands read "down the token axis" (C for P C,
-//     B^T and C for the state update) use ds_read_b64_tr_b16.
+//     and publishes a bf16 copy [dv][dk] to LDS (double buffered), which the output waves
+//     read as the A operand of S^T A^T.  These waves also drive the tile pipeline:
+//   * B and C tiles go global -> LDS directly (global_load_lds_dwordx4, no registers)
+//     into a ring of 3-4 stages, so 2-3 blocks of loads are always in flight per
+//     workgroup; one barrier per block.  LDS rows are unpadded; the 16-byte chunk index
+//     is XOR-swizzled with the row so that row reads, transpose reads
+//     (ds_read_b64_tr_b16, for operands needed "down the token axis") and the state-copy
+//     writes spread over the banks.  Rows past the end of a short last block are fetched
+//     from a small buffer of zeros.
 //   * wave role and strip are compile-time constants of the code each wave runs, so
 //     causal tile skipping costs no branches inside a block.
 // Only non-negative powers of lambda are formed.
@@ -60,20 +63,21 @@ union Frag {          // one 16x16x32 MFMA operand: 8 bf16 per lane
     bf16x4 b[2];
 };
 
+// Source of rows past the end of a short last block.
+__device__ __attribute__((aligned(256))) const unsigned char kZeros[256] = {};
+
 // Global prefetch loads are issued from inline assembly and waited for with explicit
-// vmcnt counts.  Left to the compiler, the loads that rotate through register sets two
-// blocks ahead make its wait-count bookkeeping give up at the loop header and wait for
-// every load right after issuing it (measured: the kernel then runs at memory latency,
-// not bandwidth).  VMEM operations retire in issue order, so "vmcnt(n)" with n = the
-// number of VMEM operations issued after the wanted loads is exact; a smaller n is safe.
-// The destination is an in/out operand and every prefetch load is unconditional, so a
-// register set is one variable updated in place: the compiler has no reason to copy it
-// (a copy made between issue and wait would read stale data).
+// vmcnt counts.  Left to the compiler, loads that rotate through register sets two blocks
+// ahead make its wait-count bookkeeping give up at the loop header and wait for every load
+// right after issuing it (measured: the kernel then runs at memory latency, not
+// bandwidth).  VMEM operations retire in issue order, so "vmcnt(n)" with n = the number
+// of VMEM operations issued after the wanted ones is exact; a smaller n is safe.
+// Register loads: the destination is an in/out operand and every load is unconditional,
+// so a register set is one variable updated in place and the compiler has no reason to
+// copy it (a copy made between issue and wait would read stale data).
 __device__ __forceinline__ void gload16(u32x4& r, const char* p) {
     asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(r) : "v"(p) : "memory");
 }
-// wait until at most N VMEM operations are outstanding; the operands tie the wait to the
-// registers it protects so that no use of them can be scheduled above it
 template <int N>
 __device__ __forceinline__ void wait_vm(u32x4& a) { asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N) : "memory"); }
 template <int N>
@@ -86,6 +90,13 @@ __device__ __forceinline__ void wait_vm_all(u32x4 (&r)[CNT]) {
     else if constexpr (CNT == 3) { wait_vm<N>(r[0], r[1]); wait_vm<N>(r[2]); }
     else { wait_vm<N>(r[0], r[1]); wait_vm<N>(r[2], r[3]); }
 }
+// Direct global -> LDS load: the wave writes 64 consecutive 16-byte LDS slots starting at
+// the wave-uniform LDS byte address `lds`; lane i fills slot i from its own global address.
+__device__ __forceinline__ void dma16(unsigned lds, const char* g) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(g) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory"); }
 
 __device__ __forceinline__ s16x4 lds_tr16(const char* p) {
     // 16 lanes give the addresses of a 4 x 16 tile of 16-bit elements (lane s: row
@@ -104,33 +115,49 @@ __device__ __forceinline__ bf16x4 to_bf16(const f32x4& x) {
 
 constexpr int kBlock = 64;
 constexpr int kThreads = 512;
-constexpr int kStageThreads = 256;     // the four state waves
+
+// Unpadded row-major LDS tile of COLS bf16 columns whose 16-byte chunks are XOR-swizzled
+// with the row: chunk c of row r lives at chunk position c ^ key(r).  The key is built so
+// that (i) 8 consecutive rows put a given 32-byte chunk pair on 8 different bank groups
+// (what a transpose read or an 8-byte state-copy write touches per half wave) and (ii) 16
+// consecutive rows put a given 16-byte chunk on 16 different ones (a 16-byte row read per
+// quarter wave).  Adding a multiple of 16 rows does not change the key, so row-block
+// offsets stay compile-time immediates.
+template <int COLS>
+struct Swz {
+    static constexpr int RB = COLS * 2;        // bytes per row
+    static constexpr int CPR = RB / 16;        // chunks per row
+    static constexpr int RPB = 256 / RB;       // rows per 256 bytes (one pass over the banks)
+    static constexpr int BYTES = kBlock * RB;  // a 64-row tile
+    static constexpr int NI = BYTES / 1024;    // wave-wide direct loads per tile
+    static_assert(COLS == 128 || COLS == 64 || COLS == 32, "tile widths");
+    __device__ static __forceinline__ int key(int r) {
+        const int q = r / RPB;             // index of the row's 256-byte group member
+        return ((q % (CPR / 2)) << 1) | ((q / (CPR / 2)) & 1);
+    }
+    __device__ static __forceinline__ int off(int r, int c) { return r * RB + ((c ^ key(r)) << 4); }
+};
 
 template <int D, int DV>
 struct Cfg {
     static constexpr int KS = D / 32;          // k-steps of a D-long contraction
     static constexpr int MT = D / 64;          // 16-row state tiles owned per state wave
     static constexpr int NT = DV / 16;         // 16-column tiles of the value slice
-    static constexpr int KP = D * 2 + 32;      // LDS row pitch of a full-width tile / state copy (bytes)
-    static constexpr int VP = DV * 2 + 32;     // LDS row pitch of a DV-wide C tile (bytes)
-    static constexpr int KC = D / 32;          // 16-byte chunks of a full tile staged per staging thread
-    static constexpr int VC = DV / 32;         // 16-byte chunks of a DV-wide tile staged per staging thread
-    static constexpr int KBYTES = kBlock * KP;
-    static constexpr int VBYTES = kBlock * VP;
-    static constexpr int SBYTES = DV * KP;
-    // pass body: B tile, C tile (DV wide), state copy; two buffers each
-    static constexpr int KB = 0;
-    static constexpr int VB = 2 * KBYTES;
-    static constexpr int SB = VB + 2 * VBYTES;
-    static constexpr int PASS_TOTAL = SB + 2 * SBYTES;
-    // dK/dV body: Q tile, dO tile (full width), two state copies; two buffers each
-    static constexpr int QB = 0;
-    static constexpr int GB = 2 * KBYTES;
-    static constexpr int S1B = 4 * KBYTES;
-    static constexpr int S2B = S1B + 2 * SBYTES;
-    static constexpr int KV_TOTAL = S2B + 2 * SBYTES;
-    static constexpr int KRPC = kStageThreads / (D / 8);    // tile rows covered per chunk index
-    static constexpr int VRPC = kStageThreads / (DV / 8);
+    using F = Swz<D>;                          // full-width tiles and state copies [DV][D]
+    using V = Swz<DV>;                         // DV-wide C tile of the pass body
+    static constexpr int SBYTES = DV * F::RB;  // one bf16 state copy
+    // pass body: ring of PST stages {B tile, C tile}, then two state copies
+    static constexpr int PST = 4;
+    static constexpr int PSTAGE = F::BYTES + V::BYTES;
+    static constexpr int P_SB = PST * PSTAGE;
+    static constexpr int PASS_TOTAL = P_SB + 2 * SBYTES;
+    // dK/dV body: ring of KST stages {Q tile, dO tile}, then two copies of each state
+    static constexpr int KST = 3;
+    static constexpr int KSTAGE = 2 * F::BYTES;
+    static constexpr int K_S1B = KST * KSTAGE;
+    static constexpr int K_S2B = K_S1B + 2 * SBYTES;
+    static constexpr int KV_TOTAL = K_S2B + 2 * SBYTES;
+    static_assert(PASS_TOTAL <= 163840 && KV_TOTAL <= 163840, "LDS per workgroup");
 };
 
 // Per-lane decay constants of an output wave (non-negative exponents only).
@@ -150,31 +177,46 @@ struct OutConsts {
     }
 };
 
+// Per-lane byte offsets into swizzled tiles (computed once per wave).
+//   row[ks]  : 16-byte row read of a full-width tile / state copy: row i16, chunk 4ks + g
+//   ctr[nt]  : transpose read of the C operand: token row 4g + s/4, columns c0 + 16nt + 4(s%4)
+template <int D, int DV, int CCOLS>
+struct ReadOffs {
+    int row[D / 32];
+    int ctr[DV / 16];
+    __device__ __forceinline__ void init(int g, int i16, int c0) {
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ++ks) row[ks] = Swz<D>::off(i16, 4 * ks + g);
+#pragma unroll
+        for (int nt = 0; nt < DV / 16; ++nt) {
+            const int col = c0 + 16 * nt + 4 * (i16 & 3);
+            ctr[nt] = Swz<CCOLS>::off(4 * g + (i16 >> 2), col >> 3) + (col & 4) * 2;
+        }
+    }
+};
+
 // One pass's output for the token strip of output wave W in the current block:
 //   out^T[DV x 16] = Ct^T P^T + diag(qscale) S^T A^T,   P^T = (Bt A^T) (.) M^T
-//   btile : full-width B tile in LDS (rows = tokens)
-//   ctile : C tile in LDS, already offset to this slice's first column; pitch CP
-//   scopy : bf16 state copy [DV][D] in LDS
-//   Af    : A fragments of the strip (zero for rows past the end)
+//   btile : full-width B tile in LDS (rows = tokens);  ctile : tile holding the C operand
+//   (CCOLS columns wide);  scopy : bf16 state copy [DV][D];  Af : A fragments of the strip
 //   out   : global address of this lane's token row, slice column 4g
-template <int D, int DV, int W, int CP>
+template <int D, int DV, int W, int CCOLS>
 __device__ __forceinline__ void output_pass(const char* btile, const char* ctile, const char* scopy,
                                             const Frag (&Af)[D / 32], const OutConsts<W>& k,
-                                            char* out, bool store, int g, int i16) {
+                                            const ReadOffs<D, DV, CCOLS>& ro, char* out, bool store) {
     using C = Cfg<D, DV>;
-    constexpr int KS = C::KS, NT = C::NT, KP = C::KP;
+    constexpr int KS = C::KS, NT = C::NT, RB = C::F::RB, CRB = Swz<CCOLS>::RB;
 
     // -- transposed scores P^T[key tile kt <= W][own 16 rows]
     f32x4 sacc[W + 1];
 #pragma unroll
     for (int kt = 0; kt <= W; ++kt) sacc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const char* ka = btile + i16 * KP + (8 * g) * 2;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int kt = 0; kt <= W; ++kt) {
             Frag a;
-            a.u = *(const u32x4*)(ka + (16 * kt) * KP + (32 * ks) * 2);
+            a.u = *(const u32x4*)(btile + (16 * kt) * RB + ro.row[ks]);
             sacc[kt] = mfma16(a.v, Af[ks].v, sacc[kt]);
         }
 
@@ -185,13 +227,12 @@ __device__ __forceinline__ void output_pass(const char* btile, const char* ctile
         oi[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
         oe[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    const char* sa = scopy + i16 * KP + (8 * g) * 2;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             Frag a;
-            a.u = *(const u32x4*)(sa + (16 * nt) * KP + (32 * ks) * 2);
+            a.u = *(const u32x4*)(scopy + (16 * nt) * RB + ro.row[ks]);
             oe[nt] = mfma16(a.v, Af[ks].v, oe[nt]);
         }
 
@@ -216,7 +257,6 @@ __device__ __forceinline__ void output_pass(const char* btile, const char* ctile
     }
 
     // -- intra-block part (transposed): C^T P^T, C read down the token axis
-    const char* va = ctile + (4 * g + (i16 >> 2)) * CP + (4 * (i16 & 3)) * 2;
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         if (2 * p <= W) {
@@ -226,8 +266,8 @@ __device__ __forceinline__ void output_pass(const char* btile, const char* ctile
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 Frag vf;
-                vf.h[0] = lds_tr16(va + (32 * p) * CP + (16 * nt) * 2);
-                vf.h[1] = lds_tr16(va + (32 * p + 16) * CP + (16 * nt) * 2);
+                vf.h[0] = lds_tr16(ctile + (32 * p) * CRB + ro.ctr[nt]);
+                vf.h[1] = lds_tr16(ctile + (32 * p + 16) * CRB + ro.ctr[nt]);
                 oi[nt] = mfma16(vf.v, b.v, oi[nt]);
             }
         }
@@ -245,10 +285,14 @@ __device__ __forceinline__ void output_pass(const char* btile, const char* ctile
     }
 }
 
-// Decay factors a state wave applies to the B^T fragments: lambda^(len-1-token) per MFMA
-// k-slot, and lambda^len for the state itself.
+// What a state wave needs per lane: decay factors for the B^T fragments
+// (lambda^(len-1-token) per MFMA k-slot, lambda^len for the state) and swizzled offsets.
+template <int D, int DV, int CCOLS>
 struct StateConsts {
     float ksc[2][8], lamB;
+    int btr[D / 64];     // transpose read of B^T: token row 4g + s/4, columns dk0 + 16mt + 4(s%4)
+    int ctr[DV / 16];    // transpose read of C:   token row 4g + s/4, columns c0 + 16nt + 4(s%4)
+    int pub[D / 64];     // 8-byte write into a state copy: row i16, columns dk0 + 16mt + 4g
     __device__ __forceinline__ void set_block_len(float lam, int len, int g) {
         lamB = decay_pow(lam, len);
 #pragma unroll
@@ -259,36 +303,47 @@ struct StateConsts {
                 ksc[p][j] = (tok < len) ? decay_pow(lam, len - 1 - tok) : 0.0f;
             }
     }
+    __device__ __forceinline__ void init_offsets(int g, int i16, int dk0, int c0) {
+#pragma unroll
+        for (int mt = 0; mt < D / 64; ++mt) {
+            const int col = dk0 + 16 * mt + 4 * (i16 & 3);
+            btr[mt] = Swz<D>::off(4 * g + (i16 >> 2), col >> 3) + (col & 4) * 2;
+            const int pc = dk0 + 16 * mt + 4 * g;
+            pub[mt] = Swz<D>::off(i16, pc >> 3) + (pc & 4) * 2;
+        }
+#pragma unroll
+        for (int nt = 0; nt < DV / 16; ++nt) {
+            const int col = c0 + 16 * nt + 4 * (i16 & 3);
+            ctr[nt] = Swz<CCOLS>::off(4 * g + (i16 >> 2), col >> 3) + (col & 4) * 2;
+        }
+    }
 };
 
 // S[dk0 .. dk0 + D/4, :] <- lambda^len S + (decayed Bt)^T Ct for the rows this state wave owns.
-//   btile : full-width B tile (rows = tokens); ctile : C tile offset to the slice, pitch CP
-template <int D, int DV, int CP>
+template <int D, int DV, int CCOLS>
 __device__ __forceinline__ void state_update(f32x4 (&st)[D / 64][DV / 16], const char* btile, const char* ctile,
-                                             const StateConsts& k, int dk0, int g, int i16) {
+                                             const StateConsts<D, DV, CCOLS>& k) {
     using C = Cfg<D, DV>;
-    constexpr int MT = C::MT, NT = C::NT, KP = C::KP;
+    constexpr int MT = C::MT, NT = C::NT, RB = C::F::RB, CRB = Swz<CCOLS>::RB;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int j = 0; j < 4; ++j) st[mt][nt][j] *= k.lamB;
-    const char* va = ctile + (4 * g + (i16 >> 2)) * CP + (4 * (i16 & 3)) * 2;
-    const char* kt0 = btile + (4 * g + (i16 >> 2)) * KP + (dk0 + 4 * (i16 & 3)) * 2;
 #pragma unroll
     for (int p = 0; p < 2; ++p) {          // 32 tokens per step
         Frag Vf[NT];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            Vf[nt].h[0] = lds_tr16(va + (32 * p) * CP + (16 * nt) * 2);
-            Vf[nt].h[1] = lds_tr16(va + (32 * p + 16) * CP + (16 * nt) * 2);
+            Vf[nt].h[0] = lds_tr16(ctile + (32 * p) * CRB + k.ctr[nt]);
+            Vf[nt].h[1] = lds_tr16(ctile + (32 * p + 16) * CRB + k.ctr[nt]);
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             Frag a;
-            a.h[0] = lds_tr16(kt0 + (32 * p) * KP + (16 * mt) * 2);
-            a.h[1] = lds_tr16(kt0 + (32 * p + 16) * KP + (16 * mt) * 2);
+            a.h[0] = lds_tr16(btile + (32 * p) * RB + k.btr[mt]);
+            a.h[1] = lds_tr16(btile + (32 * p + 16) * RB + k.btr[mt]);
             f32x8 af = __builtin_convertvector(a.v, f32x8);
 #pragma unroll
             for (int j = 0; j < 8; ++j) af[j] *= k.ksc[p][j];
@@ -299,40 +354,48 @@ __device__ __forceinline__ void state_update(f32x4 (&st)[D / 64][DV / 16], const
     }
 }
 
-template <int D, int DV>
-__device__ __forceinline__ void publish_state(const f32x4 (&st)[D / 64][DV / 16], char* scopy, int dk0, int g, int i16) {
+template <int D, int DV, int CCOLS>
+__device__ __forceinline__ void publish_state(const f32x4 (&st)[D / 64][DV / 16], char* scopy,
+                                              const StateConsts<D, DV, CCOLS>& k) {
     using C = Cfg<D, DV>;
 #pragma unroll
     for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < C::NT; ++nt)
-            *(bf16x4*)(scopy + (16 * nt + i16) * C::KP + (dk0 + 16 * mt + 4 * g) * 2) = to_bf16(st[mt][nt]);
+            *(bf16x4*)(scopy + (16 * nt) * C::F::RB + k.pub[mt]) = to_bf16(st[mt][nt]);
 }
 
-// A full-width tile (64 rows x D) staged by the 256 staging threads: KC chunks per thread.
-template <int D, int DV>
-struct TileRegs {
-    u32x4 r[Cfg<D, DV>::KC];
-};
-// global -> registers; rows >= valid read row valid-1 instead (zeroed when staged)
-template <int D, int DV>
-__device__ __forceinline__ void load_full_tile(TileRegs<D, DV>& t, const char* p0, int krow, long long rs, int valid) {
-    using C = Cfg<D, DV>;
+// Direct global -> LDS fetch of one 64-row tile of COLS columns by the four state waves.
+// Wave u issues the wave-wide loads j = u, u+4, ...; load j fills LDS slots 64j .. 64j+63
+// (slot s = row s / CPR, chunk position s % CPR).  `src[i]` is this lane's byte offset
+// from the block's first row for its i-th load; `row[i]` the tile row it fetches.
+template <int COLS>
+struct TileDma {
+    static_assert(Swz<COLS>::NI % 4 == 0, "every state wave issues the same number of loads");
+    static constexpr int PER_WAVE = Swz<COLS>::NI / 4;
+    long long src[PER_WAVE];
+    int row[PER_WAVE];
+    __device__ __forceinline__ void init(int u, int lane, long long row_stride) {
+        using S = Swz<COLS>;
 #pragma unroll
-    for (int c = 0; c < C::KC; ++c) {
-        int r = c * C::KRPC + krow;
-        r = (r < valid ? r : valid - 1) - krow;
-        gload16(t.r[c], p0 + (long long)r * rs);
+        for (int i = 0; i < PER_WAVE; ++i) {
+            const int slot = 64 * (u + 4 * i) + lane;
+            const int r = slot / S::CPR;
+            const int c = (slot % S::CPR) ^ S::key(r);
+            row[i] = r;
+            src[i] = (long long)r * row_stride + c * 16;
+        }
     }
-}
-template <int D, int DV>
-__device__ __forceinline__ void stage_full_tile(const TileRegs<D, DV>& t, char* tile, int krow, int kch, int valid) {
-    using C = Cfg<D, DV>;
+    // base: global address of the block's row 0 (plus the slice's column offset);
+    // lds: LDS byte address of the tile; rows >= valid come from the zero buffer
+    __device__ __forceinline__ void issue(const char* base, unsigned lds, int u, int valid) const {
 #pragma unroll
-    for (int c = 0; c < C::KC; ++c)
-        *(u32x4*)(tile + (c * C::KRPC + krow) * C::KP + kch * 16) =
-            (c * C::KRPC + krow < valid) ? t.r[c] : u32x4{0, 0, 0, 0};
-}
+        for (int i = 0; i < PER_WAVE; ++i) {
+            const char* g = (row[i] < valid) ? base + src[i] : (const char*)kZeros;
+            dma16(lds + 1024u * (unsigned)(u + 4 * i), g);
+        }
+    }
+};
 
 struct Chain {            // what every wave of the workgroup knows about its problem
     const char* a;        // pass body: operands offset to this chain (c/out also to the slice)
@@ -348,6 +411,12 @@ struct Chain {            // what every wave of the workgroup knows about its pr
     float lam;
 };
 
+// A fragments of an output wave: register sets loaded two blocks ahead.
+template <int KS, int NTENS>
+struct ASet {
+    u32x4 f[NTENS][KS];
+};
+
 // =============================================================== pass body
 
 template <int D, int DV, int W>
@@ -358,78 +427,74 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, in
     const int g = lane >> 4, i16 = lane & 15;
     OutConsts<W> k;
     k.init(ch.lam, g, i16);
+    ReadOffs<D, DV, DV> ro;
+    ro.init(g, i16, 0);
 
     // cursors for this lane's token row (16W + i16) of block 0
     const long long r0 = ch.rev ? (ch.N - 1 - (16 * W + i16)) : (long long)(16 * W + i16);
-    const long long rs = ch.rev ? -ROW : ROW;
-    const long long step = kBlock * rs;
+    const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
     const char* pa = ch.a + r0 * ROW + (8 * g) * 2;
     char* po = ch.out + r0 * ROW + (4 * g) * 2;
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
 
-    // A fragments straight from global memory (only this wave needs them): three rotating
-    // register sets, loaded two blocks ahead.
-    struct ASet { u32x4 a[KS]; };
-    auto load_a = [&](ASet& s, int b) {
+    using Set = ASet<KS, 1>;
+    auto load_a = [&](Set& s, int b) {
         b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block (ignored)
-        const int row = 16 * W + i16, valid = valid_of(b);
-        long long off = (long long)b * step;
-        if (row >= valid) off -= (long long)(row - (valid - 1)) * rs;
+        const bool ok = (16 * W + i16) < valid_of(b);
+        const char* p = ok ? pa + (long long)b * step : (const char*)kZeros;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) gload16(s.a[ks], pa + off + ks * 64);
+        for (int ks = 0; ks < KS; ++ks) gload16(s.f[0][ks], p + ks * 64);
     };
     // Set(blk) was issued two blocks ago; since then this wave issued the NT stores of
     // each of two blocks and the KS loads of set(blk+1).
     constexpr int kAfter = 2 * NT + KS;
 
-    auto do_block = [&](int blk, ASet& cur_set, ASet& incoming) {
-        const int cur = blk & 1;
+    auto do_block = [&](int blk, int stage, Set& cur_set, Set& incoming) {
         const bool more = blk + 1 < ch.T;
         const bool row_ok = (16 * W + i16) < valid_of(blk);
-        wait_vm_all<kAfter>(cur_set.a);
+        wait_vm_all<kAfter>(cur_set.f[0]);
         Frag Af[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {      // rows past the end are zeroed in place (landed data)
-            if (!row_ok) cur_set.a[ks] = u32x4{0, 0, 0, 0};
-            Af[ks].u = cur_set.a[ks];
-        }
+        for (int ks = 0; ks < KS; ++ks) Af[ks].u = cur_set.f[0][ks];
         load_a(incoming, blk + 2);
-        output_pass<D, DV, W, C::VP>(smem + C::KB + cur * C::KBYTES, smem + C::VB + cur * C::VBYTES,
-                                     smem + C::SB + cur * C::SBYTES, Af, k,
-                                     po + (long long)blk * step, more || row_ok, g, i16);
+        const char* st = smem + stage * C::PSTAGE;
+        output_pass<D, DV, W, DV>(st, st + C::F::BYTES, smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
+                                  po + (long long)blk * step, more || row_ok);
         if (more) __syncthreads();
     };
 
-    ASet s0, s1, s2;
+    Set s0, s1, s2;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) s0.a[ks] = s1.a[ks] = s2.a[ks] = u32x4{0, 0, 0, 0};
+    for (int ks = 0; ks < KS; ++ks) s0.f[0][ks] = s1.f[0][ks] = s2.f[0][ks] = u32x4{0, 0, 0, 0};
     load_a(s0, 0);
     load_a(s1, 1);
-    wait_vm_all<0>(s0.a);                  // blocks 0 and 1 are retired here, so the
-    wait_vm_all<0>(s1.a);                  // steady-state count is safe for them too
+    wait_vm_all<0>(s0.f[0]);               // blocks 0 and 1 are retired here, so the
+    wait_vm_all<0>(s1.f[0]);               // steady-state count is safe for them too
     __syncthreads();                       // block 0 tiles and the initial state copy are in LDS
 
+    int stage = 0;
+    auto next = [&]() { stage = (stage + 1 == C::PST) ? 0 : stage + 1; };
     for (int blk = 0; blk < ch.T; blk += 3) {
-        do_block(blk, s0, s2);
-        if (blk + 1 < ch.T) do_block(blk + 1, s1, s0);
-        if (blk + 2 < ch.T) do_block(blk + 2, s2, s1);
+        do_block(blk, stage, s0, s2); next();
+        if (blk + 1 < ch.T) { do_block(blk + 1, stage, s1, s0); next(); }
+        if (blk + 2 < ch.T) { do_block(blk + 2, stage, s2, s1); next(); }
     }
     // the last two prefetches were never consumed: retire them before the registers die
-    wait_vm_all<0>(s0.a);
-    wait_vm_all<0>(s1.a);
-    wait_vm_all<0>(s2.a);
+    wait_vm_all<0>(s0.f[0]);
+    wait_vm_all<0>(s1.f[0]);
+    wait_vm_all<0>(s2.f[0]);
 }
 
 template <int D, int DV>
-__device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, int lane, int u) {
+__device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, unsigned lds0, int lane, int u) {
     using C = Cfg<D, DV>;
     constexpr int MT = C::MT, NT = C::NT;
     constexpr long long ROW = D * 2;
     const int g = lane >> 4, i16 = lane & 15;
-    const int stid = u * 64 + lane;                 // 0..255 among the staging threads
     const int dk0 = u * (D / 4);
-    StateConsts k;
+    StateConsts<D, DV, DV> k;
     k.set_block_len(ch.lam, kBlock, g);
+    k.init_offsets(g, i16, dk0, 0);
 
     // running state, fp32
     f32x4 st[MT][NT];
@@ -446,84 +511,52 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, int
             }
         }
 
-    // staging cursors: this thread's first chunk of each tile, block 0
-    const int krow = stid / (D / 8), kch = stid % (D / 8);
-    const int vrow = stid / (DV / 8), vch = stid % (DV / 8);
+    // tile pipeline: block b lives in ring stage b % PST
     const long long rs = ch.rev ? -ROW : ROW;        // byte stride between consecutive block rows
-    const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
-    const char* pk = ch.b + (ch.rev ? (ch.N - 1 - krow) : (long long)krow) * ROW + kch * 16;
-    const char* pv = ch.c + (ch.rev ? (ch.N - 1 - vrow) : (long long)vrow) * ROW + vch * 16;
-
-    // Two staging register sets: block b+1 is "ready" (landed or landing) while block b+2
-    // is being fetched, so two blocks of loads are in flight per workgroup.  Loads are
-    // unconditional; past the last block they re-read it (ignored).
-    struct Stage { TileRegs<D, DV> k; u32x4 v[C::VC]; };
-    constexpr int kLoads = C::KC + C::VC;              // VMEM loads per block per thread
+    const long long step = kBlock * rs;
+    const char* pb0 = ch.b + (ch.rev ? (ch.N - 1) * ROW : 0);
+    const char* pc0 = ch.c + (ch.rev ? (ch.N - 1) * ROW : 0);
+    TileDma<D> db;
+    TileDma<DV> dc;
+    db.init(u, lane, rs);
+    dc.init(u, lane, rs);
+    constexpr int kLoads = TileDma<D>::PER_WAVE + TileDma<DV>::PER_WAVE;   // per block, per wave
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
-    auto load_tiles = [&](Stage& t, int b) {
-        b = b < ch.T ? b : ch.T - 1;
+    auto fetch = [&](int b, int stage) {
+        b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block into a free stage
         const int valid = valid_of(b);
-        load_full_tile<D, DV>(t.k, pk + (long long)b * step, krow, rs, valid);
-        const char* v0 = pv + (long long)b * step;
-#pragma unroll
-        for (int c = 0; c < C::VC; ++c) {
-            int r = c * C::VRPC + vrow;
-            r = (r < valid ? r : valid - 1) - vrow;
-            gload16(t.v[c], v0 + (long long)r * rs);
-        }
-    };
-    auto wait_tiles = [&](Stage& t, bool newer_in_flight) {
-        // the loads of the following block are always issued after these
-        if (newer_in_flight) { wait_vm_all<kLoads>(t.k.r); wait_vm_all<kLoads>(t.v); }
-        else { wait_vm_all<0>(t.k.r); wait_vm_all<0>(t.v); }
-    };
-    auto stage_to_lds = [&](const Stage& t, int buf, int valid) {
-        stage_full_tile<D, DV>(t.k, smem + C::KB + buf * C::KBYTES, krow, kch, valid);
-        char* vb = smem + C::VB + buf * C::VBYTES;
-#pragma unroll
-        for (int c = 0; c < C::VC; ++c)
-            *(u32x4*)(vb + (c * C::VRPC + vrow) * C::VP + vch * 16) =
-                (c * C::VRPC + vrow < valid) ? t.v[c] : u32x4{0, 0, 0, 0};
+        const unsigned lds = lds0 + (unsigned)(stage * C::PSTAGE);
+        db.issue(pb0 + (long long)b * step, lds, u, valid);
+        dc.issue(pc0 + (long long)b * step, lds + C::F::BYTES, u, valid);
     };
 
-    auto do_block = [&](int blk, Stage& ready, Stage& incoming) -> bool {
-        const int cur = blk & 1;
-        const bool more = blk + 1 < ch.T;
-        load_tiles(incoming, blk + 2);     // global -> registers, two blocks ahead
-        if (!more) {
-            if (!ch.state_out) return false;   // the last update only feeds the returned state
-            if (ch.last_valid != kBlock) k.set_block_len(ch.lam, ch.last_valid, g);
-        }
-        state_update<D, DV, C::VP>(st, smem + C::KB + cur * C::KBYTES, smem + C::VB + cur * C::VBYTES, k, dk0, g, i16);
-        if (more) {
-            publish_state<D, DV>(st, smem + C::SB + (cur ^ 1) * C::SBYTES, dk0, g, i16);
-            wait_tiles(ready, true);
-            stage_to_lds(ready, cur ^ 1, valid_of(blk + 1));
-            __syncthreads();
-        }
-        return more;
-    };
-
-    // prologue: block 0 tiles and the initial state copy into buffer 0; block 1 in flight
-    Stage sa_, sb_;
+    // prologue: blocks 0 .. PST-2 in flight, block 0 landed; initial state copy published
 #pragma unroll
-    for (int c = 0; c < C::KC; ++c) sa_.k.r[c] = sb_.k.r[c] = u32x4{0, 0, 0, 0};
-#pragma unroll
-    for (int c = 0; c < C::VC; ++c) sa_.v[c] = sb_.v[c] = u32x4{0, 0, 0, 0};
-    load_tiles(sa_, 0);
-    publish_state<D, DV>(st, smem + C::SB, dk0, g, i16);
-    wait_tiles(sa_, false);
-    stage_to_lds(sa_, 0, valid_of(0));
-    load_tiles(sa_, 1);
+    for (int b = 0; b < C::PST - 1; ++b) fetch(b, b);
+    publish_state<D, DV, DV>(st, smem + C::P_SB, k);
+    wait_dma<(C::PST - 2) * kLoads>();
     __syncthreads();
 
-    for (int blk = 0; blk < ch.T; blk += 2) {
-        if (!do_block(blk, sa_, sb_)) break;
-        if (!do_block(blk + 1, sb_, sa_)) break;
+    int stage = 0;                                   // stage of block blk
+    for (int blk = 0; blk < ch.T; ++blk) {
+        const bool more = blk + 1 < ch.T;
+        int fs = stage + C::PST - 1;                 // stage of block blk + PST - 1 (free since the last barrier)
+        if (fs >= C::PST) fs -= C::PST;
+        fetch(blk + C::PST - 1, fs);
+        if (!more) {
+            if (!ch.state_out) break;                // the last update only feeds the returned state
+            if (ch.last_valid != kBlock) k.set_block_len(ch.lam, ch.last_valid, g);
+        }
+        const char* tb = smem + stage * C::PSTAGE;
+        state_update<D, DV, DV>(st, tb, tb + C::F::BYTES, k);
+        if (more) {
+            publish_state<D, DV, DV>(st, smem + C::P_SB + ((blk + 1) & 1) * C::SBYTES, k);
+            wait_dma<(C::PST - 2) * kLoads>();       // block blk+1 has landed (this wave's part)
+            __syncthreads();
+        }
+        stage = (stage + 1 == C::PST) ? 0 : stage + 1;
     }
-    // prefetches past the last block were never consumed: retire them before the registers die
-    wait_tiles(sa_, false);
-    wait_tiles(sb_, false);
+    wait_dma<0>();                                   // nothing may land in LDS after this workgroup is gone
 
     if (ch.state_out) {
 #pragma unroll
@@ -537,7 +570,8 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, int
 }
 
 template <int D, int DV>
-__device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int wg, char* smem, int wave, int lane) {
+__device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int wg, char* smem, unsigned lds0,
+                                          int wave, int lane) {
     int chain, within;
     map_workgroup(wg, pb.count * nsplit, pb.chains, chain, within);
     const int pi = within / nsplit;
@@ -564,7 +598,7 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
         case 1: pass_output_wave<D, DV, 1>(ch, smem, lane); break;
         case 2: pass_output_wave<D, DV, 2>(ch, smem, lane); break;
         case 3: pass_output_wave<D, DV, 3>(ch, smem, lane); break;
-        default: pass_state_wave<D, DV>(ch, smem, lane, wave - 4); break;
+        default: pass_state_wave<D, DV>(ch, smem, lds0, lane, wave - 4); break;
     }
 }
 
@@ -575,7 +609,7 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
 //   dK[:, half] = pass_rev(A = V, B = dO, C = Q[:, half])    state S2 = sum decayed dO^T q[half]
 // Q and dO tiles live in LDS (full width: each is the B operand of one pass and, through a
 // column offset, the C operand of the other); K and V are only A operands, so each output
-// wave fetches its own 16 rows of them straight from global memory, two blocks ahead.
+// wave fetches its own 16 rows of them straight from global memory.
 
 struct KvChain {
     const char* q;        // offset to this chain
@@ -592,11 +626,13 @@ struct KvChain {
 template <int D, int DV, int W>
 __device__ __forceinline__ void kv_output_wave(const KvChain& ch, char* smem, int lane) {
     using C = Cfg<D, DV>;
-    constexpr int KS = C::KS, NT = C::NT, KP = C::KP;
+    constexpr int KS = C::KS, NT = C::NT;
     constexpr long long ROW = D * 2;
     const int g = lane >> 4, i16 = lane & 15;
     OutConsts<W> k;
     k.init(ch.lam, g, i16);
+    ReadOffs<D, DV, D> ro;
+    ro.init(g, i16, ch.half * DV);
 
     // reversed token axis: local row r of block b is global row N-1-(64b + r)
     const long long r0 = ch.N - 1 - (16 * W + i16);
@@ -607,17 +643,16 @@ __device__ __forceinline__ void kv_output_wave(const KvChain& ch, char* smem, in
     char* pdv = ch.dv + r0 * ROW + (4 * g) * 2;
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
 
-    // A fragments of both passes: three rotating register sets, loaded two blocks ahead.
-    struct ASet { u32x4 k[KS]; u32x4 v[KS]; };
-    auto load_a = [&](ASet& s, int b) {
+    using Set = ASet<KS, 2>;               // [0] = K fragments, [1] = V fragments
+    auto load_a = [&](Set& s, int b) {
         b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block (ignored)
-        const int row = 16 * W + i16, valid = valid_of(b);
-        long long off = (long long)b * step;
-        if (row >= valid) off += (long long)(row - (valid - 1)) * ROW;   // reversed axis: previous local row is +ROW
+        const bool ok = (16 * W + i16) < valid_of(b);
+        const char* p0 = ok ? pk + (long long)b * step : (const char*)kZeros;
+        const char* p1 = ok ? pv + (long long)b * step : (const char*)kZeros;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            gload16(s.k[ks], pk + off + ks * 64);
-            gload16(s.v[ks], pv + off + ks * 64);
+            gload16(s.f[0][ks], p0 + ks * 64);
+            gload16(s.f[1][ks], p1 + ks * 64);
         }
     };
     // Set(blk) was issued two blocks ago; since then this wave issued the 2*NT stores of
@@ -625,64 +660,65 @@ __device__ __forceinline__ void kv_output_wave(const KvChain& ch, char* smem, in
     constexpr int kAfter = 4 * NT + 2 * KS;
     static_assert(kAfter <= 63, "vmcnt field");
 
-    auto do_block = [&](int blk, ASet& cur_set, ASet& incoming) {
-        const int cur = blk & 1;
+    auto do_block = [&](int blk, int stage, Set& cur_set, Set& incoming) {
         const bool more = blk + 1 < ch.T;
-        const int valid = valid_of(blk);
-        const bool row_ok = (16 * W + i16) < valid;
-        wait_vm_all<kAfter>(cur_set.k);
-        wait_vm_all<kAfter>(cur_set.v);
+        const bool row_ok = (16 * W + i16) < valid_of(blk);
+        wait_vm_all<kAfter>(cur_set.f[0]);
+        wait_vm_all<kAfter>(cur_set.f[1]);
         Frag Kf[KS], Vf[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {      // rows past the end are zeroed in place (landed data)
-            if (!row_ok) cur_set.k[ks] = cur_set.v[ks] = u32x4{0, 0, 0, 0};
-            Kf[ks].u = cur_set.k[ks];
-            Vf[ks].u = cur_set.v[ks];
+        for (int ks = 0; ks < KS; ++ks) {
+            Kf[ks].u = cur_set.f[0][ks];
+            Vf[ks].u = cur_set.f[1][ks];
         }
         load_a(incoming, blk + 2);
 
-        const char* qt = smem + C::QB + cur * C::KBYTES;
-        const char* gt = smem + C::GB + cur * C::KBYTES;
+        const char* qt = smem + stage * C::KSTAGE;
+        const char* gt = qt + C::F::BYTES;
+        const int cur = blk & 1;
         const long long o = (long long)blk * step;
         const bool store = more || row_ok;
         // dV = pass(K, Q, dO[:, half])
-        output_pass<D, DV, W, KP>(qt, gt + ch.half * DV * 2, smem + C::S1B + cur * C::SBYTES, Kf, k, pdv + o, store, g, i16);
+        output_pass<D, DV, W, D>(qt, gt, smem + C::K_S1B + cur * C::SBYTES, Kf, k, ro, pdv + o, store);
         // dK = pass(V, dO, Q[:, half])
-        output_pass<D, DV, W, KP>(gt, qt + ch.half * DV * 2, smem + C::S2B + cur * C::SBYTES, Vf, k, pdk + o, store, g, i16);
+        output_pass<D, DV, W, D>(gt, qt, smem + C::K_S2B + cur * C::SBYTES, Vf, k, ro, pdk + o, store);
         if (more) __syncthreads();
     };
 
-    ASet s0, s1, s2;
+    Set s0, s1, s2;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-        s0.k[ks] = s0.v[ks] = s1.k[ks] = s1.v[ks] = s2.k[ks] = s2.v[ks] = u32x4{0, 0, 0, 0};
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) s0.f[t][ks] = s1.f[t][ks] = s2.f[t][ks] = u32x4{0, 0, 0, 0};
     load_a(s0, 0);
     load_a(s1, 1);
-    wait_vm_all<0>(s0.k); wait_vm_all<0>(s0.v);      // blocks 0 and 1 are retired here, so the
-    wait_vm_all<0>(s1.k); wait_vm_all<0>(s1.v);      // steady-state count is safe for them too
-    __syncthreads();                                 // block 0 tiles and state copies are in LDS
+    wait_vm_all<0>(s0.f[0]); wait_vm_all<0>(s0.f[1]);      // blocks 0 and 1 are retired here, so the
+    wait_vm_all<0>(s1.f[0]); wait_vm_all<0>(s1.f[1]);      // steady-state count is safe for them too
+    __syncthreads();                                       // block 0 tiles and state copies are in LDS
 
+    int stage = 0;
+    auto next = [&]() { stage = (stage + 1 == C::KST) ? 0 : stage + 1; };
     for (int blk = 0; blk < ch.T; blk += 3) {
-        do_block(blk, s0, s2);
-        if (blk + 1 < ch.T) do_block(blk + 1, s1, s0);
-        if (blk + 2 < ch.T) do_block(blk + 2, s2, s1);
+        do_block(blk, stage, s0, s2); next();
+        if (blk + 1 < ch.T) { do_block(blk + 1, stage, s1, s0); next(); }
+        if (blk + 2 < ch.T) { do_block(blk + 2, stage, s2, s1); next(); }
     }
     // the last two prefetches were never consumed: retire them before the registers die
-    wait_vm_all<0>(s0.k); wait_vm_all<0>(s0.v);
-    wait_vm_all<0>(s1.k); wait_vm_all<0>(s1.v);
-    wait_vm_all<0>(s2.k); wait_vm_all<0>(s2.v);
+    wait_vm_all<0>(s0.f[0]); wait_vm_all<0>(s0.f[1]);
+    wait_vm_all<0>(s1.f[0]); wait_vm_all<0>(s1.f[1]);
+    wait_vm_all<0>(s2.f[0]); wait_vm_all<0>(s2.f[1]);
 }
 
 template <int D, int DV>
-__device__ __forceinline__ void kv_state_wave(const KvChain& ch, char* smem, int lane, int u) {
+__device__ __forceinline__ void kv_state_wave(const KvChain& ch, char* smem, unsigned lds0, int lane, int u) {
     using C = Cfg<D, DV>;
-    constexpr int MT = C::MT, NT = C::NT, KP = C::KP;
+    constexpr int MT = C::MT, NT = C::NT;
     constexpr long long ROW = D * 2;
     const int g = lane >> 4, i16 = lane & 15;
-    const int stid = u * 64 + lane;
     const int dk0 = u * (D / 4);
-    StateConsts k;
+    StateConsts<D, DV, D> k;
     k.set_block_len(ch.lam, kBlock, g);      // a short last block never updates the states
+    k.init_offsets(g, i16, dk0, ch.half * DV);
 
     f32x4 st1[MT][NT], st2[MT][NT];
 #pragma unroll
@@ -693,61 +729,51 @@ __device__ __forceinline__ void kv_state_wave(const KvChain& ch, char* smem, int
             st2[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
 
-    const int krow = stid / (D / 8), kch = stid % (D / 8);
     constexpr long long rs = -ROW;                   // reversed token axis
-    constexpr long long step = -(long long)kBlock * ROW;
-    const char* pq = ch.q + (ch.N - 1 - krow) * ROW + kch * 16;
-    const char* pg = ch.g + (ch.N - 1 - krow) * ROW + kch * 16;
-
-    struct Stage { TileRegs<D, DV> q, g; };
-    constexpr int kLoads = 2 * C::KC;
+    constexpr long long step = kBlock * rs;
+    const char* pq0 = ch.q + (ch.N - 1) * ROW;
+    const char* pg0 = ch.g + (ch.N - 1) * ROW;
+    TileDma<D> dq;
+    dq.init(u, lane, rs);
+    constexpr int kLoads = 2 * TileDma<D>::PER_WAVE;
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
-    auto load_tiles = [&](Stage& t, int b) {
+    auto fetch = [&](int b, int stage) {
         b = b < ch.T ? b : ch.T - 1;
         const int valid = valid_of(b);
-        load_full_tile<D, DV>(t.q, pq + (long long)b * step, krow, rs, valid);
-        load_full_tile<D, DV>(t.g, pg + (long long)b * step, krow, rs, valid);
-    };
-    auto wait_tiles = [&](Stage& t, bool newer_in_flight) {
-        if (newer_in_flight) { wait_vm_all<kLoads>(t.q.r); wait_vm_all<kLoads>(t.g.r); }
-        else { wait_vm_all<0>(t.q.r); wait_vm_all<0>(t.g.r); }
-    };
-    auto stage_to_lds = [&](const Stage& t, int buf, int valid) {
-        stage_full_tile<D, DV>(t.q, smem + C::QB + buf * C::KBYTES, krow, kch, valid);
-        stage_full_tile<D, DV>(t.g, smem + C::GB + buf * C::KBYTES, krow, kch, valid);
+        const unsigned lds = lds0 + (unsigned)(stage * C::KSTAGE);
+        dq.issue(pq0 + (long long)b * step, lds, u, valid);
+        dq.issue(pg0 + (long long)b * step, lds + C::F::BYTES, u, valid);
     };
 
-    // One staging set, fetched one block ahead: a block of this body carries two passes'
-    // worth of math, so one block time already covers the load latency, and the registers
-    // of a second set are needed for the second state.
-    Stage sa_;
 #pragma unroll
-    for (int c = 0; c < C::KC; ++c) sa_.q.r[c] = sa_.g.r[c] = u32x4{0, 0, 0, 0};
-    load_tiles(sa_, 0);
-    publish_state<D, DV>(st1, smem + C::S1B, dk0, g, i16);
-    publish_state<D, DV>(st2, smem + C::S2B, dk0, g, i16);
-    wait_tiles(sa_, false);
-    stage_to_lds(sa_, 0, valid_of(0));
+    for (int b = 0; b < C::KST - 1; ++b) fetch(b, b);
+    publish_state<D, DV, D>(st1, smem + C::K_S1B, k);
+    publish_state<D, DV, D>(st2, smem + C::K_S2B, k);
+    wait_dma<(C::KST - 2) * kLoads>();
     __syncthreads();
 
-    for (int blk = 0; blk + 1 < ch.T; ++blk) {     // no state is returned: the last block needs no update
-        const int cur = blk & 1;
-        load_tiles(sa_, blk + 1);
-        const char* qt = smem + C::QB + cur * C::KBYTES;
-        const char* gt = smem + C::GB + cur * C::KBYTES;
+    int stage = 0;
+    for (int blk = 0; blk + 1 < ch.T; ++blk) {       // no state is returned: the last block needs no update
+        int fs = stage + C::KST - 1;
+        if (fs >= C::KST) fs -= C::KST;
+        fetch(blk + C::KST - 1, fs);
+        const char* qt = smem + stage * C::KSTAGE;
+        const char* gt = qt + C::F::BYTES;
+        const int nxt = (blk + 1) & 1;
         // S1 <- lambda^64 S1 + (decayed Q)^T dO[:, half];   S2 <- lambda^64 S2 + (decayed dO)^T Q[:, half]
-        state_update<D, DV, KP>(st1, qt, gt + ch.half * DV * 2, k, dk0, g, i16);
-        publish_state<D, DV>(st1, smem + C::S1B + (cur ^ 1) * C::SBYTES, dk0, g, i16);
-        state_update<D, DV, KP>(st2, gt, qt + ch.half * DV * 2, k, dk0, g, i16);
-        publish_state<D, DV>(st2, smem + C::S2B + (cur ^ 1) * C::SBYTES, dk0, g, i16);
-        wait_tiles(sa_, false);
-        stage_to_lds(sa_, cur ^ 1, valid_of(blk + 1));
+        state_update<D, DV, D>(st1, qt, gt, k);
+        publish_state<D, DV, D>(st1, smem + C::K_S1B + nxt * C::SBYTES, k);
+        state_update<D, DV, D>(st2, gt, qt, k);
+        publish_state<D, DV, D>(st2, smem + C::K_S2B + nxt * C::SBYTES, k);
+        wait_dma<(C::KST - 2) * kLoads>();
         __syncthreads();
+        stage = (stage + 1 == C::KST) ? 0 : stage + 1;
     }
+    wait_dma<0>();                                   // nothing may land in LDS after this workgroup is gone
 }
 
 template <int D, int DV>
-__device__ __forceinline__ void kv_body(const BwdBatch& bb, int wg, char* smem, int wave, int lane) {
+__device__ __forceinline__ void kv_body(const BwdBatch& bb, int wg, char* smem, unsigned lds0, int wave, int lane) {
     // two halves of a chain sit 8 workgroup ids apart (same XCD, shared L2) when possible
     int chain, half;
     map_workgroup(wg, 2, bb.chains, chain, half);
@@ -769,19 +795,23 @@ __device__ __forceinline__ void kv_body(const BwdBatch& bb, int wg, char* smem, 
         case 1: kv_output_wave<D, DV, 1>(ch, smem, lane); break;
         case 2: kv_output_wave<D, DV, 2>(ch, smem, lane); break;
         case 3: kv_output_wave<D, DV, 3>(ch, smem, lane); break;
-        default: kv_state_wave<D, DV>(ch, smem, lane, wave - 4); break;
+        default: kv_state_wave<D, DV>(ch, smem, lds0, lane, wave - 4); break;
     }
 }
 
 // =============================================================== kernels
 
+__device__ __forceinline__ unsigned lds_address(const char* p) {
+    return (unsigned)(size_t)(const __attribute__((address_space(3))) char*)p;
+}
+
 template <int D, int DV>
 __global__ __launch_bounds__(kThreads)
 void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
-    __shared__ __attribute__((aligned(16))) char smem[Cfg<D, DV>::PASS_TOTAL];
+    __shared__ __attribute__((aligned(1024))) char smem[Cfg<D, DV>::PASS_TOTAL];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: role dispatch is a uniform branch
-    pass_body<D, DV>(pb, nsplit, blockIdx.x, smem, wave, tid & 63);
+    pass_body<D, DV>(pb, nsplit, blockIdx.x, smem, lds_address(smem), wave, tid & 63);
 }
 
 // Backward in one launch: the first 2*chains workgroups run the dK/dV body, the
@@ -792,12 +822,12 @@ void bwd_bf16_kernel(const BwdBatch bb) {
     constexpr int DV = D / 2;
     using C = Cfg<D, DV>;
     constexpr int LDS = C::KV_TOTAL > C::PASS_TOTAL ? C::KV_TOTAL : C::PASS_TOTAL;
-    __shared__ __attribute__((aligned(16))) char smem[LDS];
+    __shared__ __attribute__((aligned(1024))) char smem[LDS];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wg = blockIdx.x;
     if (wg < 2 * bb.chains) {
-        kv_body<D, DV>(bb, wg, smem, wave, tid & 63);
+        kv_body<D, DV>(bb, wg, smem, lds_address(smem), wave, tid & 63);
     } else {
         PassBatch pb = {};
         pb.p[0] = PassArgs{bb.d_o, bb.v, bb.k, bb.dq, nullptr, nullptr, 0};
@@ -806,7 +836,7 @@ void bwd_bf16_kernel(const BwdBatch bb) {
         pb.chains = bb.chains;
         pb.H = bb.H;
         pb.N = bb.N;
-        pass_body<D, DV>(pb, 2, wg - 2 * bb.chains, smem, wave, tid & 63);
+        pass_body<D, DV>(pb, 2, wg - 2 * bb.chains, smem, lds_address(smem), wave, tid & 63);
     }
 }
 
