@@ -113,11 +113,11 @@ def main() -> int:
     ab = algorithmic_bytes_per_token_head(w.D, esize)
     tflops = {n: f * token_heads / (ms_per_step * 1e-3) / 1e12 for n, f in fl.items()}
 
-    # Dominant kernel: the backward launch (three gradient passes in one kernel).
+    # Dominant kernel: the backward launch (all three gradients in one kernel).
     bwd_bytes = ab["bwd"] * token_heads
     achieved = bwd_bytes / (bwd_ms * 1e-3) / 1e9
     roofline = {
-        "bound": "hbm", "kernel": "pass_bf16_kernel (backward launch: dQ, dK, dV passes)",
+        "bound": "hbm", "kernel": "bwd_bf16_kernel<128> (the backward launch: fused dK/dV workgroups + dQ workgroups)",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": MEASURED_BWD_TRAFFIC_BYTES.get(args.workload),

@@ -27,8 +27,8 @@
 //     accumulators already sit in the lane layout the next MFMA wants as its B operand
 //     (the contraction index is permuted identically on both operands), so the masked
 //     scores never leave registers.  The output is produced transposed
-//     (O^T = C^T P^T + S^T A^T): every lane holds four consecutive output features of
-//     one token -> 8-byte stores.  Its A fragments come straight from global memory
+//     (O^T = C^T P^T + S^T A^T): every lane holds groups of four consecutive output
+//     features of one token; lane-row swaps regroup them into 16-byte stores.  Its A fragments come straight from global memory
 //     into three rotating register sets, two blocks ahead.
 //   * state waves 4..7: wave u owns state rows [u*D/4, (u+1)*D/4) x DV in fp32
 //     accumulators for the whole sequence, applies S <- lambda^len S + (decayed B)^T C
@@ -199,7 +199,7 @@ struct ReadOffs {
 //   out^T[DV x 16] = Ct^T P^T + diag(qscale) S^T A^T,   P^T = (Bt A^T) (.) M^T
 //   btile : full-width B tile in LDS (rows = tokens);  ctile : tile holding the C operand
 //   (CCOLS columns wide);  scopy : bf16 state copy [DV][D];  Af : A fragments of the strip
-//   out   : global address of this lane's token row, slice column 4g
+//   out   : global address of this lane's token row, slice column 8g
 template <int D, int DV, int W, int CCOLS>
 __device__ __forceinline__ void output_pass(const char* btile, const char* ctile, const char* scopy,
                                             const Frag (&Af)[D / 32], const OutConsts<W>& k,
@@ -273,15 +273,33 @@ __device__ __forceinline__ void output_pass(const char* btile, const char* ctile
         }
     }
 
-    // -- combine and store: lane holds one token, features 16nt + 4g .. +3
-    if (store) {
+    // -- combine.  The lane now holds, for its token, features 16nt + 4g .. +3 of every tile
+    // nt.  Two lane-row swaps per tile pair (rows of 16 lanes: first between the wave's
+    // halves, then between neighbouring rows) regroup them so that the lane holds the eight
+    // consecutive features 32p + 8g .. +7 of its token: one 16-byte store per tile pair,
+    // and the four lanes of a token write 64 contiguous bytes.
+    unsigned w[NT][2];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            f32x4 r;
+    for (int nt = 0; nt < NT; ++nt) {
+        f32x4 r;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) r[j] = oi[nt][j] + k.qscale * oe[nt][j];
-            *(bf16x4*)(out + 32 * nt) = to_bf16(r);
+        for (int j = 0; j < 4; ++j) r[j] = oi[nt][j] + k.qscale * oe[nt][j];
+        union { bf16x4 h; unsigned u[2]; } cv;
+        cv.h = to_bf16(r);
+        w[nt][0] = cv.u[0];
+        w[nt][1] = cv.u[1];
+    }
+#pragma unroll
+    for (int p = 0; p < NT / 2; ++p) {
+        u32x4 q;
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            auto s = __builtin_amdgcn_permlane32_swap(w[2 * p][d], w[2 * p + 1][d], false, false);
+            auto t = __builtin_amdgcn_permlane16_swap(s[0], s[1], false, false);
+            q[d] = t[0];
+            q[2 + d] = t[1];
         }
+        if (store) *(u32x4*)(out + 64 * p) = q;
     }
 }
 
@@ -434,7 +452,7 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, in
     const long long r0 = ch.rev ? (ch.N - 1 - (16 * W + i16)) : (long long)(16 * W + i16);
     const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
     const char* pa = ch.a + r0 * ROW + (8 * g) * 2;
-    char* po = ch.out + r0 * ROW + (4 * g) * 2;
+    char* po = ch.out + r0 * ROW + (8 * g) * 2;
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
 
     using Set = ASet<KS, 1>;
@@ -445,9 +463,9 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, in
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) gload16(s.f[0][ks], p + ks * 64);
     };
-    // Set(blk) was issued two blocks ago; since then this wave issued the NT stores of
+    // Set(blk) was issued two blocks ago; since then this wave issued the NT/2 stores of
     // each of two blocks and the KS loads of set(blk+1).
-    constexpr int kAfter = 2 * NT + KS;
+    constexpr int kAfter = NT + KS;
 
     auto do_block = [&](int blk, int stage, Set& cur_set, Set& incoming) {
         const bool more = blk + 1 < ch.T;
@@ -639,8 +657,8 @@ __device__ __forceinline__ void kv_output_wave(const KvChain& ch, char* smem, in
     constexpr long long step = -(long long)kBlock * ROW;
     const char* pk = ch.k + r0 * ROW + (8 * g) * 2;
     const char* pv = ch.v + r0 * ROW + (8 * g) * 2;
-    char* pdk = ch.dk + r0 * ROW + (4 * g) * 2;
-    char* pdv = ch.dv + r0 * ROW + (4 * g) * 2;
+    char* pdk = ch.dk + r0 * ROW + (8 * g) * 2;
+    char* pdv = ch.dv + r0 * ROW + (8 * g) * 2;
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
 
     using Set = ASet<KS, 2>;               // [0] = K fragments, [1] = V fragments
@@ -655,9 +673,9 @@ __device__ __forceinline__ void kv_output_wave(const KvChain& ch, char* smem, in
             gload16(s.f[1][ks], p1 + ks * 64);
         }
     };
-    // Set(blk) was issued two blocks ago; since then this wave issued the 2*NT stores of
-    // each of two blocks and the 2*KS loads of set(blk+1).
-    constexpr int kAfter = 4 * NT + 2 * KS;
+    // Set(blk) was issued two blocks ago; since then this wave issued the NT stores (two
+    // outputs, NT/2 each) of each of two blocks and the 2*KS loads of set(blk+1).
+    constexpr int kAfter = 2 * NT + 2 * KS;
     static_assert(kAfter <= 63, "vmcnt field");
 
     auto do_block = [&](int blk, int stage, Set& cur_set, Set& incoming) {
