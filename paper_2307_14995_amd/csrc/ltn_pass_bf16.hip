@@ -28,19 +28,22 @@
 //     (the contraction index is permuted identically on both operands), so the masked
 //     scores never leave registers.  The output is produced transposed
 //     (O^T = C^T P^T + S^T A^T): every lane holds groups of four consecutive output
-//     features of one token; lane-row swaps regroup them into 16-byte stores.  Its A fragments come straight from global memory
-//     into three rotating register sets, two blocks ahead.
+//     features of one token; lane-row swaps regroup them into 16-byte stores.
 //   * state waves 4..7: wave u owns state rows [u*D/4, (u+1)*D/4) x DV in fp32
 //     accumulators for the whole sequence, applies S <- lambda^len S + (decayed B)^T C
 //     and publishes a bf16 copy [dv][dk] to LDS (double buffered), which the output waves
 //     read as the A operand of S^T A^T.  These waves also drive the tile pipeline:
-//   * B and C tiles go global -> LDS directly (global_load_lds_dwordx4, no registers)
-//     into a ring of 3-4 stages, so 2-3 blocks of loads are always in flight per
-//     workgroup; one barrier per block.  LDS rows are unpadded; the 16-byte chunk index
-//     is XOR-swizzled with the row so that row reads, transpose reads
-//     (ds_read_b64_tr_b16, for operands needed "down the token axis") and the state-copy
-//     writes spread over the banks.  Rows past the end of a short last block are fetched
-//     from a small buffer of zeros.
+//   * operand tiles go global -> LDS directly (global_load_lds_dwordx4: no registers, every
+//     wave-wide load covers 1 KB of consecutive addresses) into a ring of 3-4 stages, so two
+//     to three blocks of loads are always in flight per workgroup; one barrier per block.
+//     The pass body rings all three tiles (its output waves read their A fragments from
+//     LDS and issue no global loads at all); the dK/dV body rings Q and dO, and its output
+//     waves fetch their own 16 rows of K and V straight into three rotating register sets,
+//     two blocks ahead (LDS is full).  LDS rows are unpadded; the 16-byte chunk index is
+//     XOR-swizzled with the row so that row reads, transpose reads (ds_read_b64_tr_b16, for
+//     operands needed "down the token axis") and the state-copy writes spread over the
+//     banks.  Rows past the end of a short last block are fetched from a small buffer of
+//     zeros.
 //   * wave role and strip are compile-time constants of the code each wave runs, so
 //     causal tile skipping costs no branches inside a block.
 // Only non-negative powers of lambda are formed.
@@ -146,9 +149,9 @@ struct Cfg {
     using F = Swz<D>;                          // full-width tiles and state copies [DV][D]
     using V = Swz<DV>;                         // DV-wide C tile of the pass body
     static constexpr int SBYTES = DV * F::RB;  // one bf16 state copy
-    // pass body: ring of PST stages {B tile, C tile}, then two state copies
-    static constexpr int PST = 4;
-    static constexpr int PSTAGE = F::BYTES + V::BYTES;
+    // pass body: ring of PST stages {A tile, B tile, C tile}, then two state copies
+    static constexpr int PSTAGE = 2 * F::BYTES + V::BYTES;
+    static constexpr int PST = (4 * PSTAGE + 2 * SBYTES <= 163840) ? 4 : 3;
     static constexpr int P_SB = PST * PSTAGE;
     static constexpr int PASS_TOTAL = P_SB + 2 * SBYTES;
     // dK/dV body: ring of KST stages {Q tile, dO tile}, then two copies of each state
@@ -429,7 +432,8 @@ struct Chain {            // what every wave of the workgroup knows about its pr
     float lam;
 };
 
-// A fragments of an output wave: register sets loaded two blocks ahead.
+// A fragments (K and V rows) of an output wave of the dK/dV body: register sets loaded two
+// blocks ahead.
 template <int KS, int NTENS>
 struct ASet {
     u32x4 f[NTENS][KS];
@@ -440,7 +444,7 @@ struct ASet {
 template <int D, int DV, int W>
 __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, int lane) {
     using C = Cfg<D, DV>;
-    constexpr int KS = C::KS, NT = C::NT;
+    constexpr int KS = C::KS;
     constexpr long long ROW = D * 2;
     const int g = lane >> 4, i16 = lane & 15;
     OutConsts<W> k;
@@ -448,59 +452,25 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, in
     ReadOffs<D, DV, DV> ro;
     ro.init(g, i16, 0);
 
-    // cursors for this lane's token row (16W + i16) of block 0
+    // this lane's token row (16W + i16) of block 0
     const long long r0 = ch.rev ? (ch.N - 1 - (16 * W + i16)) : (long long)(16 * W + i16);
     const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
-    const char* pa = ch.a + r0 * ROW + (8 * g) * 2;
     char* po = ch.out + r0 * ROW + (8 * g) * 2;
-    auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
 
-    using Set = ASet<KS, 1>;
-    auto load_a = [&](Set& s, int b) {
-        b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block (ignored)
-        const bool ok = (16 * W + i16) < valid_of(b);
-        const char* p = ok ? pa + (long long)b * step : (const char*)kZeros;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) gload16(s.f[0][ks], p + ks * 64);
-    };
-    // Set(blk) was issued two blocks ago; since then this wave issued the NT/2 stores of
-    // each of two blocks and the KS loads of set(blk+1).
-    constexpr int kAfter = NT + KS;
-
-    auto do_block = [&](int blk, int stage, Set& cur_set, Set& incoming) {
+    __syncthreads();                       // block 0 tiles and the initial state copy are in LDS
+    int stage = 0;
+    for (int blk = 0; blk < ch.T; ++blk) {
         const bool more = blk + 1 < ch.T;
-        const bool row_ok = (16 * W + i16) < valid_of(blk);
-        wait_vm_all<kAfter>(cur_set.f[0]);
+        const bool row_ok = (16 * W + i16) < ((blk + 1 == ch.T) ? ch.last_valid : kBlock);
+        const char* st = smem + stage * C::PSTAGE;
         Frag Af[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) Af[ks].u = cur_set.f[0][ks];
-        load_a(incoming, blk + 2);
-        const char* st = smem + stage * C::PSTAGE;
-        output_pass<D, DV, W, DV>(st, st + C::F::BYTES, smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
-                                  po + (long long)blk * step, more || row_ok);
+        for (int ks = 0; ks < KS; ++ks) Af[ks].u = *(const u32x4*)(st + (16 * W) * C::F::RB + ro.row[ks]);
+        output_pass<D, DV, W, DV>(st + C::F::BYTES, st + 2 * C::F::BYTES, smem + C::P_SB + (blk & 1) * C::SBYTES,
+                                  Af, k, ro, po + (long long)blk * step, more || row_ok);
         if (more) __syncthreads();
-    };
-
-    Set s0, s1, s2;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) s0.f[0][ks] = s1.f[0][ks] = s2.f[0][ks] = u32x4{0, 0, 0, 0};
-    load_a(s0, 0);
-    load_a(s1, 1);
-    wait_vm_all<0>(s0.f[0]);               // blocks 0 and 1 are retired here, so the
-    wait_vm_all<0>(s1.f[0]);               // steady-state count is safe for them too
-    __syncthreads();                       // block 0 tiles and the initial state copy are in LDS
-
-    int stage = 0;
-    auto next = [&]() { stage = (stage + 1 == C::PST) ? 0 : stage + 1; };
-    for (int blk = 0; blk < ch.T; blk += 3) {
-        do_block(blk, stage, s0, s2); next();
-        if (blk + 1 < ch.T) { do_block(blk + 1, stage, s1, s0); next(); }
-        if (blk + 2 < ch.T) { do_block(blk + 2, stage, s2, s1); next(); }
+        stage = (stage + 1 == C::PST) ? 0 : stage + 1;
     }
-    // the last two prefetches were never consumed: retire them before the registers die
-    wait_vm_all<0>(s0.f[0]);
-    wait_vm_all<0>(s1.f[0]);
-    wait_vm_all<0>(s2.f[0]);
 }
 
 template <int D, int DV>
@@ -532,20 +502,23 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
     // tile pipeline: block b lives in ring stage b % PST
     const long long rs = ch.rev ? -ROW : ROW;        // byte stride between consecutive block rows
     const long long step = kBlock * rs;
+    const char* pa0 = ch.a + (ch.rev ? (ch.N - 1) * ROW : 0);
     const char* pb0 = ch.b + (ch.rev ? (ch.N - 1) * ROW : 0);
     const char* pc0 = ch.c + (ch.rev ? (ch.N - 1) * ROW : 0);
-    TileDma<D> db;
+    TileDma<D> db;                                   // A and B tiles: same shape, same offsets
     TileDma<DV> dc;
     db.init(u, lane, rs);
     dc.init(u, lane, rs);
-    constexpr int kLoads = TileDma<D>::PER_WAVE + TileDma<DV>::PER_WAVE;   // per block, per wave
+    constexpr int kLoads = 2 * TileDma<D>::PER_WAVE + TileDma<DV>::PER_WAVE;   // per block, per wave
+    static_assert((C::PST - 2) * kLoads <= 63, "vmcnt field");
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
     auto fetch = [&](int b, int stage) {
         b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block into a free stage
         const int valid = valid_of(b);
         const unsigned lds = lds0 + (unsigned)(stage * C::PSTAGE);
-        db.issue(pb0 + (long long)b * step, lds, u, valid);
-        dc.issue(pc0 + (long long)b * step, lds + C::F::BYTES, u, valid);
+        db.issue(pa0 + (long long)b * step, lds, u, valid);
+        db.issue(pb0 + (long long)b * step, lds + C::F::BYTES, u, valid);
+        dc.issue(pc0 + (long long)b * step, lds + 2 * C::F::BYTES, u, valid);
     };
 
     // prologue: blocks 0 .. PST-2 in flight, block 0 landed; initial state copy published
@@ -565,7 +538,7 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
             if (!ch.state_out) break;                // the last update only feeds the returned state
             if (ch.last_valid != kBlock) k.set_block_len(ch.lam, ch.last_valid, g);
         }
-        const char* tb = smem + stage * C::PSTAGE;
+        const char* tb = smem + stage * C::PSTAGE + C::F::BYTES;
         state_update<D, DV, DV>(st, tb, tb + C::F::BYTES, k);
         if (more) {
             publish_state<D, DV, DV>(st, smem + C::P_SB + ((blk + 1) & 1) * C::SBYTES, k);
