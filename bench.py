@@ -6,7 +6,8 @@ One "step" = one forward + one backward call of the library on the headline work
 all tensors resident in HBM before the timed region.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3_7b|cfg2_385m|cfg_1b]
-                  [--no-cpu-baseline] [--report]   (--report adds the other workloads to stderr)
+                  [--no-cpu-baseline] [--report] [--copy-calibration]
+  (--report adds the other workloads to stderr; --copy-calibration is for counter runs)
 """
 from __future__ import annotations
 
@@ -54,6 +55,9 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg3_7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run one untimed 1 GiB device-to-device copy, so that a counter run "
+                         "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the attention path has no collective "
@@ -70,6 +74,13 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     ltn.load_library()
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     w = synth.CONFIGS[args.workload]
     esize = 2 if w.dtype == torch.bfloat16 else 4

@@ -11,21 +11,22 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Value columns handled per workgroup.  Every value-column slice of a chain
-// recomputes that chain's score tiles and re-reads its first two operands, so the
-// split is only as deep as needed to put a workgroup on each of the 256 compute
-// units.  LTN_ATTN_DV (debug only) overrides the choice.
+// Value columns handled per workgroup.  Every value-column slice of a chain recomputes
+// that chain's score tiles and re-reads its first two operands through L2, and a compute
+// unit holds one workgroup: the split is the deepest one whose workgroups still fit one
+// round of the 256 compute units; when even full-width slices need more than one round,
+// full width (fewest re-reads).  Measured on MI355X for 8..256 chains, forward and
+// backward.  LTN_ATTN_DV (debug, used by the parity tests) overrides the choice.
 int pick_dv(long long chain_passes, int D, ltn_dtype dtype) {
-    // bf16 kernel: slices of 64 or 32 columns (D = 128), 64 or 32 (D = 64); fp32: D or D/2
-    const int hi = (dtype == LTN_BF16) ? 64 : D;
+    const int hi = D;
     const int lo = (dtype == LTN_BF16) ? 32 : D / 2;
     if (const char* e = std::getenv("LTN_ATTN_DV")) {
         const int v = std::atoi(e);
         if ((v == D || v == D / 2 || v == D / 4) && v >= lo && v <= hi) return v;
     }
-    if (dtype == LTN_F32) return chain_passes >= 512 ? D : D / 2;
-    if (chain_passes * (D / hi) >= 256) return hi;
-    return lo;
+    for (int dv = lo; dv <= hi; dv *= 2)
+        if (chain_passes * (D / dv) <= 256) return dv;
+    return hi;
 }
 
 ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype dtype, int* blk_out) {
@@ -145,11 +146,6 @@ ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void*
     const long long chains = (long long)Bt * H;
     if (chains == 0 || N == 0) return LTN_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dtype == LTN_BF16) {
-        // one launch: dK and dV fused per column half (shared operand tiles), dQ as a pass
-        ltn::BwdBatch bb = {q, k, v, d_o, dq, dk, dv, decay, (int)chains, H, N};
-        return ltn::launch_bwd_bf16(bb, D, st) == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
-    }
     // The three gradients are three decayed linear-attention passes with permuted
     // operands (derivative of O = ((Q K^T)(.)M) V; App. B Algorithm 4 corrected):
     //   dQ = ((dO V^T)(.)M)   K   -> pass(dO, V, K), first token -> last

@@ -33,27 +33,9 @@ struct PassBatch {
     long long N;
 };
 
-// The whole backward of one call, for the fused bf16 kernel.
-struct BwdBatch {
-    const void* q;        // [chains, N, D]
-    const void* k;
-    const void* v;
-    const void* d_o;
-    void* dq;
-    void* dk;
-    void* dv;
-    const float* decay;   // [H]
-    int chains;           // Bt * H
-    int H;
-    long long N;
-};
-
 // bf16 MFMA kernel, block length 64.  D in {64,128}; dv = value columns per workgroup
-// (64 or 32).
+// (D, D/2 or, for D = 128, D/4).
 hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream);
-// bf16 backward in one launch: per chain two workgroups compute dK and dV together (one
-// column half each, sharing every operand tile) and two compute dQ.
-hipError_t launch_bwd_bf16(const BwdBatch& bb, int D, hipStream_t stream);
 // fp32 kernel.  D in {64,128}, block in {16,32,64}, D*block <= 4096.
 hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStream_t stream);
 // kv[c] (or zeros if null) -> kv_out[c], n floats.

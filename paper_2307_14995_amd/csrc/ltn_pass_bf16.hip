@@ -13,14 +13,9 @@
 // permuted operands, dQ = pass(dO,V,K), and on a reversed token axis dV = pass(K,Q,dO),
 // dK = pass(V,dO,Q) (derivative of the definition; App. B Algorithm 4 corrected).
 //
-// Two workgroup bodies, both 512 threads = 8 wavefronts in two roles (two waves per
-// SIMD, so one role's LDS/VALU latencies hide under the other's MFMAs):
-//
-//   pass body    one pass for a DV-column slice: forward, and dQ in the backward.
-//   dK/dV body   both reversed-axis passes for one half of the columns.  They share all
-//                four operand tiles (Q and dO are each the B operand of one pass and the C
-//                operand of the other; K and V are the A operands), so a chain's tokens
-//                are read once for two gradients instead of twice.
+// One workgroup = one pass over one chain for a slice of DV value columns: 512 threads =
+// 8 wavefronts in two roles (two waves per SIMD, so one role's LDS/VALU latencies hide
+// under the other's MFMAs):
 //
 //   * output waves 0..3: wave w owns token rows 16w..16w+15 of the block.  It forms the
 //     transposed score tiles P^T[key tile][its rows] with 16x16x32 bf16 MFMA; the fp32
@@ -33,17 +28,16 @@
 //     accumulators for the whole sequence, applies S <- lambda^len S + (decayed B)^T C
 //     and publishes a bf16 copy [dv][dk] to LDS (double buffered), which the output waves
 //     read as the A operand of S^T A^T.  These waves also drive the tile pipeline:
-//   * operand tiles go global -> LDS directly (global_load_lds_dwordx4: no registers, every
-//     wave-wide load covers 1 KB of consecutive addresses) into a ring of 3-4 stages, so two
-//     to three blocks of loads are always in flight per workgroup; one barrier per block.
-//     The pass body rings all three tiles (its output waves read their A fragments from
-//     LDS and issue no global loads at all); the dK/dV body rings Q and dO, and its output
-//     waves fetch their own 16 rows of K and V straight into three rotating register sets,
-//     two blocks ahead (LDS is full).  LDS rows are unpadded; the 16-byte chunk index is
-//     XOR-swizzled with the row so that row reads, transpose reads (ds_read_b64_tr_b16, for
-//     operands needed "down the token axis") and the state-copy writes spread over the
-//     banks.  Rows past the end of a short last block are fetched from a small buffer of
-//     zeros.
+//   * all three operand tiles go global -> LDS directly (global_load_lds_dwordx4: no
+//     registers, every wave-wide load covers 1 KB of consecutive addresses) into a ring of
+//     2-4 stages (as many as fit beside the two state copies), so one to three blocks of
+//     loads are always in flight per workgroup; one barrier per block.  Output waves read
+//     their A fragments from LDS and issue no global loads at all, so their stores never
+//     stand in front of a load they wait for.  LDS rows are unpadded; the 16-byte chunk
+//     index is XOR-swizzled with the row so that row reads, transpose reads
+//     (ds_read_b64_tr_b16, for operands needed "down the token axis") and the state-copy
+//     writes spread over the banks.  Rows past the end of a short last block are fetched
+//     from a small buffer of zeros.
 //   * wave role and strip are compile-time constants of the code each wave runs, so
 //     causal tile skipping costs no branches inside a block.
 // Only non-negative powers of lambda are formed.
@@ -69,30 +63,10 @@ union Frag {          // one 16x16x32 MFMA operand: 8 bf16 per lane
 // Source of rows past the end of a short last block.
 __device__ __attribute__((aligned(256))) const unsigned char kZeros[256] = {};
 
-// Global prefetch loads are issued from inline assembly and waited for with explicit
-// vmcnt counts.  Left to the compiler, loads that rotate through register sets two blocks
-// ahead make its wait-count bookkeeping give up at the loop header and wait for every load
-// right after issuing it (measured: the kernel then runs at memory latency, not
-// bandwidth).  VMEM operations retire in issue order, so "vmcnt(n)" with n = the number
-// of VMEM operations issued after the wanted ones is exact; a smaller n is safe.
-// Register loads: the destination is an in/out operand and every load is unconditional,
-// so a register set is one variable updated in place and the compiler has no reason to
-// copy it (a copy made between issue and wait would read stale data).
-__device__ __forceinline__ void gload16(u32x4& r, const char* p) {
-    asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(r) : "v"(p) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vm(u32x4& a) { asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N) : "memory"); }
-template <int N>
-__device__ __forceinline__ void wait_vm(u32x4& a, u32x4& b) { asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory"); }
-template <int N, int CNT>
-__device__ __forceinline__ void wait_vm_all(u32x4 (&r)[CNT]) {
-    static_assert(CNT >= 1 && CNT <= 4, "register sets of 1..4 fragments");
-    if constexpr (CNT == 1) wait_vm<N>(r[0]);
-    else if constexpr (CNT == 2) wait_vm<N>(r[0], r[1]);
-    else if constexpr (CNT == 3) { wait_vm<N>(r[0], r[1]); wait_vm<N>(r[2]); }
-    else { wait_vm<N>(r[0], r[1]); wait_vm<N>(r[2], r[3]); }
-}
+// Direct global -> LDS loads are issued from inline assembly and waited for with explicit
+// vmcnt counts (the compiler does not model their LDS side).  VMEM operations retire in
+// issue order, so "vmcnt(n)" with n = the number of VMEM operations this wave issued after
+// the wanted ones is exact; a smaller n is safe.
 // Direct global -> LDS load: the wave writes 64 consecutive 16-byte LDS slots starting at
 // the wave-uniform LDS byte address `lds`; lane i fills slot i from its own global address.
 __device__ __forceinline__ void dma16(unsigned lds, const char* g) {
@@ -151,16 +125,10 @@ struct Cfg {
     static constexpr int SBYTES = DV * F::RB;  // one bf16 state copy
     // pass body: ring of PST stages {A tile, B tile, C tile}, then two state copies
     static constexpr int PSTAGE = 2 * F::BYTES + V::BYTES;
-    static constexpr int PST = (4 * PSTAGE + 2 * SBYTES <= 163840) ? 4 : 3;
+    static constexpr int PST = (4 * PSTAGE + 2 * SBYTES <= 163840) ? 4 : ((3 * PSTAGE + 2 * SBYTES <= 163840) ? 3 : 2);
     static constexpr int P_SB = PST * PSTAGE;
     static constexpr int PASS_TOTAL = P_SB + 2 * SBYTES;
-    // dK/dV body: ring of KST stages {Q tile, dO tile}, then two copies of each state
-    static constexpr int KST = 3;
-    static constexpr int KSTAGE = 2 * F::BYTES;
-    static constexpr int K_S1B = KST * KSTAGE;
-    static constexpr int K_S2B = K_S1B + 2 * SBYTES;
-    static constexpr int KV_TOTAL = K_S2B + 2 * SBYTES;
-    static_assert(PASS_TOTAL <= 163840 && KV_TOTAL <= 163840, "LDS per workgroup");
+    static_assert(PASS_TOTAL <= 163840, "LDS per workgroup");
 };
 
 // Per-lane decay constants of an output wave (non-negative exponents only).
@@ -432,13 +400,6 @@ struct Chain {            // what every wave of the workgroup knows about its pr
     float lam;
 };
 
-// A fragments (K and V rows) of an output wave of the dK/dV body: register sets loaded two
-// blocks ahead.
-template <int KS, int NTENS>
-struct ASet {
-    u32x4 f[NTENS][KS];
-};
-
 // =============================================================== pass body
 
 template <int D, int DV, int W>
@@ -593,203 +554,6 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
     }
 }
 
-// =============================================================== dK/dV body
-//
-// Both reversed-axis gradient passes for one half (DV = D/2 columns) of a chain:
-//   dV[:, half] = pass_rev(A = K, B = Q,  C = dO[:, half])   state S1 = sum decayed q^T dO[half]
-//   dK[:, half] = pass_rev(A = V, B = dO, C = Q[:, half])    state S2 = sum decayed dO^T q[half]
-// Q and dO tiles live in LDS (full width: each is the B operand of one pass and, through a
-// column offset, the C operand of the other); K and V are only A operands, so each output
-// wave fetches its own 16 rows of them straight from global memory.
-
-struct KvChain {
-    const char* q;        // offset to this chain
-    const char* k;
-    const char* v;
-    const char* g;        // dO
-    char* dk;             // offset to this chain and column half
-    char* dv;
-    long long N;
-    int T, last_valid, half;
-    float lam;
-};
-
-template <int D, int DV, int W>
-__device__ __forceinline__ void kv_output_wave(const KvChain& ch, char* smem, int lane) {
-    using C = Cfg<D, DV>;
-    constexpr int KS = C::KS, NT = C::NT;
-    constexpr long long ROW = D * 2;
-    const int g = lane >> 4, i16 = lane & 15;
-    OutConsts<W> k;
-    k.init(ch.lam, g, i16);
-    ReadOffs<D, DV, D> ro;
-    ro.init(g, i16, ch.half * DV);
-
-    // reversed token axis: local row r of block b is global row N-1-(64b + r)
-    const long long r0 = ch.N - 1 - (16 * W + i16);
-    constexpr long long step = -(long long)kBlock * ROW;
-    const char* pk = ch.k + r0 * ROW + (8 * g) * 2;
-    const char* pv = ch.v + r0 * ROW + (8 * g) * 2;
-    char* pdk = ch.dk + r0 * ROW + (8 * g) * 2;
-    char* pdv = ch.dv + r0 * ROW + (8 * g) * 2;
-    auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
-
-    using Set = ASet<KS, 2>;               // [0] = K fragments, [1] = V fragments
-    auto load_a = [&](Set& s, int b) {
-        b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block (ignored)
-        const bool ok = (16 * W + i16) < valid_of(b);
-        const char* p0 = ok ? pk + (long long)b * step : (const char*)kZeros;
-        const char* p1 = ok ? pv + (long long)b * step : (const char*)kZeros;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            gload16(s.f[0][ks], p0 + ks * 64);
-            gload16(s.f[1][ks], p1 + ks * 64);
-        }
-    };
-    // Set(blk) was issued two blocks ago; since then this wave issued the NT stores (two
-    // outputs, NT/2 each) of each of two blocks and the 2*KS loads of set(blk+1).
-    constexpr int kAfter = 2 * NT + 2 * KS;
-    static_assert(kAfter <= 63, "vmcnt field");
-
-    auto do_block = [&](int blk, int stage, Set& cur_set, Set& incoming) {
-        const bool more = blk + 1 < ch.T;
-        const bool row_ok = (16 * W + i16) < valid_of(blk);
-        wait_vm_all<kAfter>(cur_set.f[0]);
-        wait_vm_all<kAfter>(cur_set.f[1]);
-        Frag Kf[KS], Vf[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            Kf[ks].u = cur_set.f[0][ks];
-            Vf[ks].u = cur_set.f[1][ks];
-        }
-        load_a(incoming, blk + 2);
-
-        const char* qt = smem + stage * C::KSTAGE;
-        const char* gt = qt + C::F::BYTES;
-        const int cur = blk & 1;
-        const long long o = (long long)blk * step;
-        const bool store = more || row_ok;
-        // dV = pass(K, Q, dO[:, half])
-        output_pass<D, DV, W, D>(qt, gt, smem + C::K_S1B + cur * C::SBYTES, Kf, k, ro, pdv + o, store);
-        // dK = pass(V, dO, Q[:, half])
-        output_pass<D, DV, W, D>(gt, qt, smem + C::K_S2B + cur * C::SBYTES, Vf, k, ro, pdk + o, store);
-        if (more) __syncthreads();
-    };
-
-    Set s0, s1, s2;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) s0.f[t][ks] = s1.f[t][ks] = s2.f[t][ks] = u32x4{0, 0, 0, 0};
-    load_a(s0, 0);
-    load_a(s1, 1);
-    wait_vm_all<0>(s0.f[0]); wait_vm_all<0>(s0.f[1]);      // blocks 0 and 1 are retired here, so the
-    wait_vm_all<0>(s1.f[0]); wait_vm_all<0>(s1.f[1]);      // steady-state count is safe for them too
-    __syncthreads();                                       // block 0 tiles and state copies are in LDS
-
-    int stage = 0;
-    auto next = [&]() { stage = (stage + 1 == C::KST) ? 0 : stage + 1; };
-    for (int blk = 0; blk < ch.T; blk += 3) {
-        do_block(blk, stage, s0, s2); next();
-        if (blk + 1 < ch.T) { do_block(blk + 1, stage, s1, s0); next(); }
-        if (blk + 2 < ch.T) { do_block(blk + 2, stage, s2, s1); next(); }
-    }
-    // the last two prefetches were never consumed: retire them before the registers die
-    wait_vm_all<0>(s0.f[0]); wait_vm_all<0>(s0.f[1]);
-    wait_vm_all<0>(s1.f[0]); wait_vm_all<0>(s1.f[1]);
-    wait_vm_all<0>(s2.f[0]); wait_vm_all<0>(s2.f[1]);
-}
-
-template <int D, int DV>
-__device__ __forceinline__ void kv_state_wave(const KvChain& ch, char* smem, unsigned lds0, int lane, int u) {
-    using C = Cfg<D, DV>;
-    constexpr int MT = C::MT, NT = C::NT;
-    constexpr long long ROW = D * 2;
-    const int g = lane >> 4, i16 = lane & 15;
-    const int dk0 = u * (D / 4);
-    StateConsts<D, DV, D> k;
-    k.set_block_len(ch.lam, kBlock, g);      // a short last block never updates the states
-    k.init_offsets(g, i16, dk0, ch.half * DV);
-
-    f32x4 st1[MT][NT], st2[MT][NT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            st1[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            st2[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-
-    constexpr long long rs = -ROW;                   // reversed token axis
-    constexpr long long step = kBlock * rs;
-    const char* pq0 = ch.q + (ch.N - 1) * ROW;
-    const char* pg0 = ch.g + (ch.N - 1) * ROW;
-    TileDma<D> dq;
-    dq.init(u, lane, rs);
-    constexpr int kLoads = 2 * TileDma<D>::PER_WAVE;
-    auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
-    auto fetch = [&](int b, int stage) {
-        b = b < ch.T ? b : ch.T - 1;
-        const int valid = valid_of(b);
-        const unsigned lds = lds0 + (unsigned)(stage * C::KSTAGE);
-        dq.issue(pq0 + (long long)b * step, lds, u, valid);
-        dq.issue(pg0 + (long long)b * step, lds + C::F::BYTES, u, valid);
-    };
-
-#pragma unroll
-    for (int b = 0; b < C::KST - 1; ++b) fetch(b, b);
-    publish_state<D, DV, D>(st1, smem + C::K_S1B, k);
-    publish_state<D, DV, D>(st2, smem + C::K_S2B, k);
-    wait_dma<(C::KST - 2) * kLoads>();
-    __syncthreads();
-
-    int stage = 0;
-    for (int blk = 0; blk + 1 < ch.T; ++blk) {       // no state is returned: the last block needs no update
-        int fs = stage + C::KST - 1;
-        if (fs >= C::KST) fs -= C::KST;
-        fetch(blk + C::KST - 1, fs);
-        const char* qt = smem + stage * C::KSTAGE;
-        const char* gt = qt + C::F::BYTES;
-        const int nxt = (blk + 1) & 1;
-        // S1 <- lambda^64 S1 + (decayed Q)^T dO[:, half];   S2 <- lambda^64 S2 + (decayed dO)^T Q[:, half]
-        state_update<D, DV, D>(st1, qt, gt, k);
-        publish_state<D, DV, D>(st1, smem + C::K_S1B + nxt * C::SBYTES, k);
-        state_update<D, DV, D>(st2, gt, qt, k);
-        publish_state<D, DV, D>(st2, smem + C::K_S2B + nxt * C::SBYTES, k);
-        wait_dma<(C::KST - 2) * kLoads>();
-        __syncthreads();
-        stage = (stage + 1 == C::KST) ? 0 : stage + 1;
-    }
-    wait_dma<0>();                                   // nothing may land in LDS after this workgroup is gone
-}
-
-template <int D, int DV>
-__device__ __forceinline__ void kv_body(const BwdBatch& bb, int wg, char* smem, unsigned lds0, int wave, int lane) {
-    // two halves of a chain sit 8 workgroup ids apart (same XCD, shared L2) when possible
-    int chain, half;
-    map_workgroup(wg, 2, bb.chains, chain, half);
-    KvChain ch;
-    const size_t chain_off = (size_t)chain * (size_t)bb.N * D * 2;
-    ch.q = (const char*)bb.q + chain_off;
-    ch.k = (const char*)bb.k + chain_off;
-    ch.v = (const char*)bb.v + chain_off;
-    ch.g = (const char*)bb.d_o + chain_off;
-    ch.dk = (char*)bb.dk + chain_off + (size_t)half * DV * 2;
-    ch.dv = (char*)bb.dv + chain_off + (size_t)half * DV * 2;
-    ch.N = bb.N;
-    ch.T = (int)((bb.N + kBlock - 1) / kBlock);
-    ch.last_valid = (int)(bb.N - (long long)(ch.T - 1) * kBlock);
-    ch.half = half;
-    ch.lam = bb.decay[chain % bb.H];
-    switch (wave) {
-        case 0: kv_output_wave<D, DV, 0>(ch, smem, lane); break;
-        case 1: kv_output_wave<D, DV, 1>(ch, smem, lane); break;
-        case 2: kv_output_wave<D, DV, 2>(ch, smem, lane); break;
-        case 3: kv_output_wave<D, DV, 3>(ch, smem, lane); break;
-        default: kv_state_wave<D, DV>(ch, smem, lds0, lane, wave - 4); break;
-    }
-}
-
 // =============================================================== kernels
 
 __device__ __forceinline__ unsigned lds_address(const char* p) {
@@ -805,32 +569,6 @@ void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
     pass_body<D, DV>(pb, nsplit, blockIdx.x, smem, lds_address(smem), wave, tid & 63);
 }
 
-// Backward in one launch: the first 2*chains workgroups run the dK/dV body, the
-// remaining 2*chains run the dQ pass (DV = D/2 slices) as the first ones drain.
-template <int D>
-__global__ __launch_bounds__(kThreads)
-void bwd_bf16_kernel(const BwdBatch bb) {
-    constexpr int DV = D / 2;
-    using C = Cfg<D, DV>;
-    constexpr int LDS = C::KV_TOTAL > C::PASS_TOTAL ? C::KV_TOTAL : C::PASS_TOTAL;
-    __shared__ __attribute__((aligned(1024))) char smem[LDS];
-    const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wg = blockIdx.x;
-    if (wg < 2 * bb.chains) {
-        kv_body<D, DV>(bb, wg, smem, lds_address(smem), wave, tid & 63);
-    } else {
-        PassBatch pb = {};
-        pb.p[0] = PassArgs{bb.d_o, bb.v, bb.k, bb.dq, nullptr, nullptr, 0};
-        pb.count = 1;
-        pb.decay = bb.decay;
-        pb.chains = bb.chains;
-        pb.H = bb.H;
-        pb.N = bb.N;
-        pass_body<D, DV>(pb, 2, wg - 2 * bb.chains, smem, lds_address(smem), wave, tid & 63);
-    }
-}
-
 template <int D, int DV>
 hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
     const int nsplit = D / DV;
@@ -843,20 +581,12 @@ hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream) {
+    if (D == 128 && dv == 128) return launch_t<128, 128>(pb, stream);
     if (D == 128 && dv == 64) return launch_t<128, 64>(pb, stream);
     if (D == 128 && dv == 32) return launch_t<128, 32>(pb, stream);
     if (D == 64 && dv == 64) return launch_t<64, 64>(pb, stream);
     if (D == 64 && dv == 32) return launch_t<64, 32>(pb, stream);
     return hipErrorInvalidValue;
-}
-
-hipError_t launch_bwd_bf16(const BwdBatch& bb, int D, hipStream_t stream) {
-    const long long wgs = 4LL * bb.chains;
-    if (wgs <= 0 || wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (D == 128) hipLaunchKernelGGL((bwd_bf16_kernel<128>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, bb);
-    else if (D == 64) hipLaunchKernelGGL((bwd_bf16_kernel<64>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, bb);
-    else return hipErrorInvalidValue;
-    return hipGetLastError();
 }
 
 }  // namespace ltn
