@@ -31,15 +31,15 @@ def flops_per_token_head(D: int, B: int):
         "F_min": 14 * D * D,                               # recurrent form, block independent
         "F_alg": 14 * D * D + 7 * (B + 1) * D,             # blockwise method, causal half of each tile
         # what the kernels issue: four passes (fwd + three gradient passes), each 4 D^2 for the
-        # state products plus, per 64-token block at a two-way value-column split, 10 of 16
-        # score tiles twice and 12 of 16 score-times-value tiles once
-        "F_exec": 16 * D * D + 16 * B * D,
+        # state products plus, per 64-token block, 10 of 16 score tiles (twice in the forward,
+        # which runs two value-column slices per chain) and 12 of 16 score-times-value tiles
+        "F_exec": 16 * D * D + (5 * 1.25 + 4 * 1.5) * B * D,
     }
 
 
 # HBM bytes per backward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
 # the same counters' reading of a plain copy of known size); see profiles/.  Keyed by workload.
-MEASURED_BWD_TRAFFIC_BYTES = {"cfg3_7b": 2.681e9}
+MEASURED_BWD_TRAFFIC_BYTES = {"cfg3_7b": 2.663e9}
 
 
 def algorithmic_bytes_per_token_head(D: int, esize: int):
@@ -128,7 +128,7 @@ def main() -> int:
     bwd_bytes = ab["bwd"] * token_heads
     achieved = bwd_bytes / (bwd_ms * 1e-3) / 1e9
     roofline = {
-        "bound": "hbm", "kernel": "bwd_bf16_kernel<128> (the backward launch: fused dK/dV workgroups + dQ workgroups)",
+        "bound": "hbm", "kernel": "pass_bf16_kernel<128,128> (the backward launch: dV, dK and dQ passes of every chain)",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": MEASURED_BWD_TRAFFIC_BYTES.get(args.workload),
