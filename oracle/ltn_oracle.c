@@ -27,6 +27,11 @@
  * doubles in [0,1]; states [Bt, H, D, D] with kv[i][j] = sum k[i]*v[j]
  * (row = key feature, column = value feature).
  *
+ *   Gated, normalised output of the token mixer (Sec. 3.1.2, Eq. 3, with the
+ *   SimpleRMSNorm of Sec. 3.1.3 taken per head over its D features):
+ *       y = x / sqrt(|x|^2 / D + eps) (.) u      (eps = 0 is the printed formula)
+ *   and its derivative with respect to x and u.
+ *
  * Parity pins live in tests/test_oracle_pins.py (brute force, closed forms,
  * cumulative-sum special case, finite differences, Algorithm 1 == Algorithm 2
  * identity of App. C, block-form re-association).  Nothing is "parity unpinned".
@@ -495,6 +500,49 @@ void ltn_oracle_decode_step(const double* q, const double* k, const double* v,
             double acc = 0.0;
             for (int i = 0; i < D; ++i) acc += q[c * D + i] * S[i * D + j];
             o[c * D + j] = acc;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------
+ * Gated SimpleRMSNorm (Sec. 3.1.2 Eq. 3: O = Norm(.) (.) U; Sec. 3.1.3:
+ * SRMSNorm(x) = x / (|x|_2 / sqrt(d))), row by row over `rows` vectors of d
+ * features.  eps is added to the mean square under the root; eps = 0 is the
+ * printed formula (a zero row then gives 0/0 = NaN, as the formula does).
+ * ---------------------------------------------------------------------- */
+void ltn_oracle_gate_fwd(const double* x, const double* u, double eps, i64 rows, int d, double* y) {
+#pragma omp parallel for schedule(static)
+    for (i64 r = 0; r < rows; ++r) {
+        const double* xr = x + r * d;
+        const double* ur = u + r * d;
+        double ss = 0.0;
+        for (int i = 0; i < d; ++i) ss += xr[i] * xr[i];
+        const double rms = sqrt(ss / (double)d + eps);
+        for (int i = 0; i < d; ++i) y[r * d + i] = xr[i] / rms * ur[i];
+    }
+}
+
+/* Derivative of the map above.  With n = x / rms (the normalised row):
+ *   du = dy (.) n
+ *   dx = (g - n * mean(g (.) n)) / rms,   g = dy (.) u
+ * (quotient rule on x_i / sqrt(mean(x^2) + eps)). */
+void ltn_oracle_gate_bwd(const double* x, const double* u, const double* dy, double eps, i64 rows, int d,
+                         double* dx, double* du) {
+#pragma omp parallel for schedule(static)
+    for (i64 r = 0; r < rows; ++r) {
+        const double* xr = x + r * d;
+        const double* ur = u + r * d;
+        const double* gr = dy + r * d;
+        double ss = 0.0;
+        for (int i = 0; i < d; ++i) ss += xr[i] * xr[i];
+        const double rms = sqrt(ss / (double)d + eps);
+        double dot = 0.0;
+        for (int i = 0; i < d; ++i) dot += gr[i] * ur[i] * (xr[i] / rms);
+        const double mean = dot / (double)d;
+        for (int i = 0; i < d; ++i) {
+            const double n = xr[i] / rms;
+            du[r * d + i] = gr[i] * n;
+            dx[r * d + i] = (gr[i] * ur[i] - n * mean) / rms;
         }
     }
 }

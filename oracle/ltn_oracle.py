@@ -54,7 +54,10 @@ def _load():
         lib.ltn_oracle_bwd_recurrent.argtypes = [dp, dp, dp, dp, dp, ci, ci, cl, ci, dp, dp, dp]
         lib.ltn_oracle_bwd_block.argtypes = [dp, dp, dp, dp, dp, ci, ci, cl, ci, ci, dp, dp, dp]
         lib.ltn_oracle_decode_step.argtypes = [dp, dp, dp, dp, ci, ci, ci, dp, dp]
-        for name in ("fwd_quadratic", "fwd_recurrent", "fwd_origin", "fwd_tiled", "fwd_block",
+        cd = ctypes.c_double
+        lib.ltn_oracle_gate_fwd.argtypes = [dp, dp, cd, cl, ci, dp]
+        lib.ltn_oracle_gate_bwd.argtypes = [dp, dp, dp, cd, cl, ci, dp, dp]
+        for name in ("gate_fwd", "gate_bwd", "fwd_quadratic", "fwd_recurrent", "fwd_origin", "fwd_tiled", "fwd_block",
                      "bwd_quadratic", "bwd_recurrent", "bwd_block", "decode_step",
                      "set_num_threads"):
             getattr(lib, "ltn_oracle_" + name).restype = None
@@ -176,6 +179,34 @@ def decode_step(q, k, v, kv, decay):
     o = np.empty_like(q)
     _load().ltn_oracle_decode_step(_p(q), _p(k), _p(v), _p(decay), Bt, H, D, _p(kv), _p(o))
     return o, kv
+
+
+def gate_fwd(x, u, eps=0.0):
+    """Eq. 3 with the SimpleRMSNorm of Sec. 3.1.3 over the last axis:
+    y = x / sqrt(mean(x^2) + eps) * u."""
+    x, u = _f64(x), _f64(u)
+    assert x.shape == u.shape
+    y = np.empty_like(x)
+    d = x.shape[-1]
+    _load().ltn_oracle_gate_fwd(_p(x), _p(u), float(eps), x.size // d, d, _p(y))
+    return y
+
+
+def gate_bwd(x, u, dy, eps=0.0):
+    """Derivative of gate_fwd: returns (dx, du)."""
+    x, u, dy = _f64(x), _f64(u), _f64(dy)
+    assert x.shape == u.shape == dy.shape
+    dx, du = np.empty_like(x), np.empty_like(x)
+    d = x.shape[-1]
+    _load().ltn_oracle_gate_bwd(_p(x), _p(u), _p(dy), float(eps), x.size // d, d, _p(dx), _p(du))
+    return dx, du
+
+
+def fwd_gated(q, k, v, u, decay, eps=0.0, kv_in=None):
+    """Token mixer of Eq. 3: the attention output of the definition (Sec. 3.2.1), normalised
+    per head and gated.  Returns (o, y)."""
+    o = fwd_recurrent(q, k, v, decay, kv_in=kv_in) if kv_in is not None else fwd_quadratic(q, k, v, decay)
+    return o, gate_fwd(o, u, eps)
 
 
 def rel_l2(x, ref) -> float:

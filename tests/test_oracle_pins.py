@@ -369,3 +369,99 @@ def test_error_metric():
     y[0, 1] *= 1.1
     assert abs(orc.rel_l2(y, x) - np.sqrt(12 * 0.01 / 24)) < 1e-12
     assert abs(orc.max_rel_l2(y, x) - 0.1) < 1e-12
+
+
+# --------------------------------------------------------------------------- gated SimpleRMSNorm
+# Sec. 3.1.2 Eq. 3 (O = Norm(.) (.) U) with the norm of Sec. 3.1.3, taken per head.
+
+
+def _read_vectors(path):
+    out = {}
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                name, *vals = line.split()
+                out[name] = np.array([float(x) for x in vals])
+    return out
+
+
+def test_gate_hand_example_golden():
+    g = _read_vectors(os.path.join(GOLDEN, "hand_example_gate_d2.txt"))
+    y = orc.gate_fwd(g["x"][None], g["u"][None])
+    dx, du = orc.gate_bwd(g["x"][None], g["u"][None], g["dy"][None])
+    np.testing.assert_allclose(y[0], g["y"], rtol=1e-14)
+    np.testing.assert_allclose(dx[0], g["dx"], rtol=1e-13)
+    np.testing.assert_allclose(du[0], g["du"], rtol=1e-14)
+
+
+def test_gate_norm_is_sqrt_d_and_scale_invariant():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((7, 3, 11, 24))
+    ones = np.ones_like(x)
+    n = orc.gate_fwd(x, ones)
+    np.testing.assert_allclose(np.linalg.norm(n, axis=-1), np.sqrt(24.0), rtol=1e-13)
+    np.testing.assert_allclose(orc.gate_fwd(37.5 * x, ones), n, rtol=1e-13)
+    np.testing.assert_allclose(orc.gate_fwd(-x, ones), -n, rtol=1e-13)
+
+
+def test_gate_constant_row_and_library_norm():
+    # a constant row c*1 normalises to sign(c)*1; in general x / (numpy's 2-norm / sqrt(d)) * u
+    d = 16
+    u = np.linspace(-2.0, 3.0, d)[None]
+    np.testing.assert_allclose(orc.gate_fwd(np.full((1, d), -0.3), u), -u, rtol=1e-14)
+    rng = np.random.default_rng(6)
+    x, uu = rng.standard_normal((40, d)), rng.standard_normal((40, d))
+    ref = x / (np.linalg.norm(x, axis=-1, keepdims=True) / np.sqrt(d)) * uu
+    np.testing.assert_allclose(orc.gate_fwd(x, uu), ref, rtol=1e-13)
+
+
+def test_gate_eps_enters_under_the_root():
+    x = np.array([[0.0, 0.0, 0.0, 0.0], [1.0, -1.0, 1.0, -1.0]])
+    u = np.array([[1.0, 2.0, 3.0, 4.0], [1.0, 2.0, 3.0, 4.0]])
+    y = orc.gate_fwd(x, u, eps=3.0)          # second row: mean square 1, root of 1 + 3 = 2
+    np.testing.assert_allclose(y, [[0, 0, 0, 0], [0.5, -1.0, 1.5, -2.0]], rtol=1e-15, atol=0)
+    with np.errstate(all="ignore"):
+        assert np.isnan(orc.gate_fwd(x, u)[0]).all()     # the printed formula: 0/0
+
+
+@pytest.mark.parametrize("eps", [0.0, 1e-3])
+def test_gate_bwd_finite_differences(eps):
+    rng = np.random.default_rng(7)
+    d = 12
+    x, u, dy = (rng.standard_normal((5, d)) for _ in range(3))
+    dx, du = orc.gate_bwd(x, u, dy, eps)
+    h = 1e-6
+    for arr, grad in ((x, dx), (u, du)):
+        num = np.zeros_like(arr)
+        for idx in np.ndindex(arr.shape):
+            old = arr[idx]
+            arr[idx] = old + h
+            fp = float((orc.gate_fwd(x, u, eps) * dy).sum())
+            arr[idx] = old - h
+            fm = float((orc.gate_fwd(x, u, eps) * dy).sum())
+            arr[idx] = old
+            num[idx] = (fp - fm) / (2 * h)
+        np.testing.assert_allclose(grad, num, rtol=2e-7, atol=2e-8)
+
+
+def test_gate_bwd_invariants():
+    # scale invariance of the norm (eps = 0) makes dx orthogonal to x; du is dy times the
+    # normalised row; the map is linear in u, so <du, u> = <dy, y>
+    rng = np.random.default_rng(8)
+    x, u, dy = (rng.standard_normal((9, 32)) for _ in range(3))
+    dx, du = orc.gate_bwd(x, u, dy)
+    np.testing.assert_allclose((dx * x).sum(-1), 0.0, atol=1e-13)
+    np.testing.assert_allclose(du, dy * orc.gate_fwd(x, np.ones_like(x)), rtol=1e-13)
+    np.testing.assert_allclose((du * u).sum(), (dy * orc.gate_fwd(x, u)).sum(), rtol=1e-12)
+
+
+def test_fwd_gated_composes_definition_and_gate():
+    rng = np.random.default_rng(9)
+    Bt, H, N, D = 1, 2, 9, 4
+    q, k, v, u = (rng.standard_normal((Bt, H, N, D)) for _ in range(4))
+    decay = np.array([0.9, 0.3])
+    o, y = orc.fwd_gated(q, k, v, u, decay)
+    np.testing.assert_allclose(o, brute_force_fwd(q, k, v, decay), rtol=1e-12, atol=1e-13)
+    rms = np.sqrt((o ** 2).mean(-1, keepdims=True))
+    np.testing.assert_allclose(y, o / rms * u, rtol=1e-12)
