@@ -230,6 +230,31 @@ def extended_report(ltn, synth, torch, dev):
                           "F_alg_TFLOPs": round((14 * D * D + 7 * 65 * D) * th / ((f + b) * 1e-3) / 1e12, 1)}),
               file=sys.stderr, flush=True)
         del q, k, v, g, o, gr
+    # token mixer epilogue (gated SimpleRMSNorm): fused into the forward vs. forward + gate kernel
+    for name, Bt, H, N in (("cfg3_7b", 4, 32, 8192), ("256chains", 8, 32, 4096)):
+        q, k, v = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
+                   for _ in range(3))
+        u, g = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(2))
+        dd = synth.decay_bench_rule(H).to(dev)
+        o, y, dx, du = (torch.empty_like(q) for _ in range(4))
+        th = Bt * H * N
+        unit = D * 2 * th                      # bytes of one tensor
+        t_plain = time_call(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o))
+        t_gate = time_call(lambda: ltn.ltn_gate_fwd(o, u, 1e-6, out=y))
+        t_inf = time_call(lambda: ltn.ltn_attn_fwd_gated(q, k, v, u, dd, eps=1e-6, store_o=False, y_out=y))
+        t_trn = time_call(lambda: ltn.ltn_attn_fwd_gated(q, k, v, u, dd, eps=1e-6, out=o, y_out=y))
+        t_gbwd = time_call(lambda: ltn.ltn_gate_bwd(o, u, g, 1e-6, out=(dx, du)))
+        print(json.dumps({"workload": "gated_" + name, "Bt": Bt, "H": H, "N": N,
+                          "fwd_plain_ms": round(t_plain, 4), "gate_fwd_ms": round(t_gate, 4),
+                          "unfused_ms": round(t_plain + t_gate, 4),
+                          "fused_inference_ms": round(t_inf, 4), "fused_training_ms": round(t_trn, 4),
+                          "gate_bwd_ms": round(t_gbwd, 4),
+                          "gate_fwd_GBs": round(3 * unit / (t_gate * 1e-3) / 1e9, 1),
+                          "gate_bwd_GBs": round(5 * unit / (t_gbwd * 1e-3) / 1e9, 1),
+                          "fused_inference_GBs": round(5 * unit / (t_inf * 1e-3) / 1e9, 1),
+                          "fused_training_GBs": round(6 * unit / (t_trn * 1e-3) / 1e9, 1)}),
+              file=sys.stderr, flush=True)
+        del q, k, v, u, g, o, y, dx, du
     c = synth.DECODE
     Bt, H = c["Bt"], c["H"]
     kv = torch.zeros(Bt, H, D, D, device=dev)

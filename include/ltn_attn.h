@@ -85,6 +85,49 @@ ltn_status ltn_attn_fwd(const void* q, const void* k, const void* v, void* o,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Forward pass with the token mixer's epilogue fused in (Sec. 3.1.2, Eq. 3:
+ * O = Norm(Q K^T V) (.) U, with the SimpleRMSNorm of Sec. 3.1.3,
+ * SRMSNorm(x) = x / (|x|_2 / sqrt(d)), taken per head over its D features):
+ *
+ *   o as in ltn_attn_fwd;   y[b,h,t,:] = o[b,h,t,:] / sqrt(mean_d(o[b,h,t,:]^2) + eps) (.) u[b,h,t,:]
+ *
+ * The normalisation and the gate are applied to the fp32 attention output while
+ * it is still on chip, so an inference caller (o == NULL) never writes or re-reads
+ * the attention output; a training caller passes `o` as well, because the
+ * derivative of the epilogue (ltn_gate_bwd) needs it.
+ *
+ *   u     in : device, [Bt,H,N,D] dtype  (the gate)
+ *   o     out: device, [Bt,H,N,D] dtype, or NULL
+ *   y     out: device, [Bt,H,N,D] dtype
+ * (With few chains and `o` requested, the library may instead run the plain forward and
+ * apply the epilogue to the stored o in a second kernel; y then derives from o rounded
+ * to `dtype`, so the two forms of the call agree to rounding, not bit for bit.)
+ *   eps   >= 0, added to the mean square under the root (0 is the printed formula:
+ *         an all-zero output row then yields NaN, as the formula does)
+ * Other arguments, layout and errors as for ltn_attn_fwd.
+ */
+ltn_status ltn_attn_fwd_gated(const void* q, const void* k, const void* v, const void* u, void* o, void* y,
+                              const float* decay, const float* kv_in, float* kv_out, float eps,
+                              int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The same epilogue on its own, row by row (Sec. 3.1.2 Eq. 3, Sec. 3.1.3):
+ *   y[r,:] = x[r,:] / sqrt(mean(x[r,:]^2) + eps) (.) u[r,:]
+ * and its derivative: with n = x / sqrt(mean(x^2) + eps) and g = d_y (.) u,
+ *   d_u = d_y (.) n,    d_x = (g - n * mean(g (.) n)) / sqrt(mean(x^2) + eps).
+ * In training, d_x is the d_o handed to ltn_attn_bwd.
+ *
+ *   x, u, d_y in : device, [rows, D] dtype (for attention tensors rows = Bt*H*N)
+ *   y, d_x, d_u out: device, [rows, D] dtype; must not alias an input or each other
+ *   D in {64, 128}; fp32 arithmetic inside for either dtype.
+ */
+ltn_status ltn_gate_fwd(const void* x, const void* u, void* y, float eps,
+                        long long rows, int D, ltn_dtype dtype, void* stream);
+ltn_status ltn_gate_bwd(const void* x, const void* u, const void* d_y, void* d_x, void* d_u, float eps,
+                        long long rows, int D, ltn_dtype dtype, void* stream);
+
+/*
  * Backward pass: gradients of the definition above (App. B Algorithm 4 read
  * with its misprints corrected: dK = dA^T Q, dQ accumulates dA K).  With
  * A = (Q K^T)(.)M and dA = (dO V^T)(.)M:  dQ = dA K, dK = dA^T Q, dV = A^T dO.

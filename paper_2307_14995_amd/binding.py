@@ -17,7 +17,8 @@ _lib = None
 
 LTN_F32, LTN_BF16 = 0, 1
 SYMBOLS = (
-    "ltn_attn_fwd", "ltn_attn_bwd", "ltn_attn_decode_step", "ltn_attn_pick_block",
+    "ltn_attn_fwd", "ltn_attn_fwd_gated", "ltn_gate_fwd", "ltn_gate_bwd",
+    "ltn_attn_bwd", "ltn_attn_decode_step", "ltn_attn_pick_block",
     "ltn_attn_workspace_bytes", "ltn_attn_check_decay", "ltn_status_str",
 )
 
@@ -46,6 +47,13 @@ def load_library():
     vp, fp, ci, cl, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_size_t
     lib.ltn_attn_fwd.argtypes = [vp, vp, vp, vp, fp, fp, fp, ci, ci, cl, ci, ci, ci, vp, sz, vp]
     lib.ltn_attn_fwd.restype = ci
+    cf = ctypes.c_float
+    lib.ltn_attn_fwd_gated.argtypes = [vp, vp, vp, vp, vp, vp, fp, fp, fp, cf, ci, ci, cl, ci, ci, ci, vp, sz, vp]
+    lib.ltn_attn_fwd_gated.restype = ci
+    lib.ltn_gate_fwd.argtypes = [vp, vp, vp, cf, cl, ci, ci, vp]
+    lib.ltn_gate_fwd.restype = ci
+    lib.ltn_gate_bwd.argtypes = [vp, vp, vp, vp, vp, cf, cl, ci, ci, vp]
+    lib.ltn_gate_bwd.restype = ci
     lib.ltn_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, fp, ci, ci, cl, ci, ci, ci, vp, sz, vp]
     lib.ltn_attn_bwd.restype = ci
     lib.ltn_attn_decode_step.argtypes = [vp, vp, vp, vp, fp, fp, ci, ci, ci, ci, vp]
@@ -135,6 +143,81 @@ def ltn_attn_fwd(q, k, v, decay, kv_in=None, return_state=False, block=0, out=No
     if rc != 0:
         raise LtnError(rc, "ltn_attn_fwd")
     return (o, kv_out) if (return_state or kv_out is not None) else o
+
+
+def ltn_attn_fwd_gated(q, k, v, u, decay, eps=0.0, kv_in=None, return_state=False, store_o=True, block=0,
+                       out=None, y_out=None, kv_out=None):
+    """Forward with the fused epilogue y = SRMSNorm_D(o) (.) u.  Returns (o or None, y[, kv_out])."""
+    lib = load_library()
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (u, "u"), (decay, "decay")):
+        _dev(t, n)
+    if not (q.shape == k.shape == v.shape == u.shape) or q.dim() != 4:
+        raise ValueError("q, k, v, u must be [Bt,H,N,D] tensors of one shape")
+    if not (q.dtype == k.dtype == v.dtype == u.dtype):
+        raise ValueError("q, k, v, u must share a dtype")
+    Bt, H, N, D = q.shape
+    if decay.dtype != torch.float32 or decay.numel() != H:
+        raise ValueError("decay must be fp32 [H]")
+    o = (torch.empty_like(q) if out is None else _dev(out, "out")) if store_o else None
+    y = torch.empty_like(q) if y_out is None else _dev(y_out, "y_out")
+    if kv_in is not None:
+        _dev(kv_in, "kv_in")
+        if kv_in.dtype != torch.float32 or tuple(kv_in.shape) != (Bt, H, D, D):
+            raise ValueError("kv_in must be fp32 [Bt,H,D,D]")
+    if kv_out is None and return_state:
+        kv_out = torch.empty((Bt, H, D, D), dtype=torch.float32, device=q.device)
+    code = _dtype_code(q.dtype)
+    ws_bytes = int(lib.ltn_attn_workspace_bytes(Bt, H, N, D, block, code, 0))
+    ws = _workspace(ws_bytes, q.device)
+    with torch.cuda.device(q.device):
+        rc = lib.ltn_attn_fwd_gated(_ptr(q), _ptr(k), _ptr(v), _ptr(u), _ptr(o), _ptr(y), _ptr(decay),
+                                    _ptr(kv_in), _ptr(kv_out), float(eps), Bt, H, N, D, int(block), code,
+                                    _ptr(ws), ws_bytes, _stream(q.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_fwd_gated")
+    return (o, y, kv_out) if (return_state or kv_out is not None) else (o, y)
+
+
+def _rows(x, what):
+    _dev(x, what)
+    if x.dim() < 1:
+        raise ValueError(f"{what} must have a feature axis")
+    return x.numel() // x.shape[-1] if x.numel() else 0, x.shape[-1]
+
+
+def ltn_gate_fwd(x, u, eps=0.0, out=None):
+    """y = x / sqrt(mean(x^2) + eps) (.) u over the last axis."""
+    lib = load_library()
+    rows, D = _rows(x, "x")
+    _dev(u, "u")
+    if u.shape != x.shape or u.dtype != x.dtype:
+        raise ValueError("x and u must share shape and dtype")
+    y = torch.empty_like(x) if out is None else _dev(out, "out")
+    with torch.cuda.device(x.device):
+        rc = lib.ltn_gate_fwd(_ptr(x), _ptr(u), _ptr(y), float(eps), rows, D, _dtype_code(x.dtype), _stream(x.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_gate_fwd")
+    return y
+
+
+def ltn_gate_bwd(x, u, d_y, eps=0.0, out=None):
+    """(d_x, d_u) of ltn_gate_fwd."""
+    lib = load_library()
+    rows, D = _rows(x, "x")
+    for t, n in ((u, "u"), (d_y, "d_y")):
+        _dev(t, n)
+        if t.shape != x.shape or t.dtype != x.dtype:
+            raise ValueError("x, u and d_y must share shape and dtype")
+    if out is None:
+        dx, du = torch.empty_like(x), torch.empty_like(x)
+    else:
+        dx, du = (_dev(t, "out") for t in out)
+    with torch.cuda.device(x.device):
+        rc = lib.ltn_gate_bwd(_ptr(x), _ptr(u), _ptr(d_y), _ptr(dx), _ptr(du), float(eps), rows, D,
+                              _dtype_code(x.dtype), _stream(x.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_gate_bwd")
+    return dx, du
 
 
 def ltn_attn_bwd(q, k, v, d_o, decay, block=0, out=None):

@@ -86,23 +86,32 @@ const char* ltn_status_str(ltn_status s) {
     return "LTN_ERR_?: unknown status";
 }
 
-ltn_status ltn_attn_fwd(const void* q, const void* k, const void* v, void* o,
-                        const float* decay, const float* kv_in, float* kv_out,
-                        int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
-                        void* workspace, size_t workspace_bytes, void* stream) {
-    (void)workspace;
+// Shared body of ltn_attn_fwd and ltn_attn_fwd_gated (u == nullptr: plain forward).
+static ltn_status fwd_common(const void* q, const void* k, const void* v, const void* u, void* o, void* y,
+                             const float* decay, const float* kv_in, float* kv_out, float eps,
+                             int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
+                             size_t workspace_bytes, void* stream, bool gated) {
     const bool empty = (Bt == 0 || H == 0 || N == 0);   // no token is read or written
-    if (!decay || (!empty && (!q || !k || !v || !o))) return LTN_ERR_NULL;
+    if (!decay || (!empty && (!q || !k || !v || (gated ? (!u || !y) : !o)))) return LTN_ERR_NULL;
     int blk = 0;
     const ltn_status cs = check_common(Bt, H, N, D, block, dtype, &blk);
     if (cs != LTN_OK) return cs;
+    if (gated && !(eps >= 0.0f)) return LTN_ERR_SHAPE;
     if (workspace_bytes < ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, 0)) return LTN_ERR_SHAPE;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) ||
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(u) || !aligned16(y) ||
         !aligned16(kv_in) || !aligned16(kv_out) || (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
-    if (!empty && (o == q || o == k || o == v || (const void*)kv_out == q || (const void*)kv_out == k ||
-                   (const void*)kv_out == v || (const void*)kv_out == o))
-        return LTN_ERR_UNSUPPORTED;
+    if (!empty) {
+        const void* ins[4] = {q, k, v, u};
+        const void* outs[3] = {o, y, kv_out};
+        for (int a = 0; a < 3; ++a) {
+            if (!outs[a]) continue;
+            for (int b = 0; b < 4; ++b)
+                if (outs[a] == ins[b]) return LTN_ERR_UNSUPPORTED;
+            for (int b = a + 1; b < 3; ++b)
+                if (outs[a] == outs[b]) return LTN_ERR_UNSUPPORTED;
+        }
+    }
     const long long chains = (long long)Bt * H;
     if (chains == 0) return LTN_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -117,8 +126,68 @@ ltn_status ltn_attn_fwd(const void* q, const void* k, const void* v, void* o,
     pb.chains = (int)chains;
     pb.H = H;
     pb.N = N;
-    pb.p[0] = ltn::PassArgs{q, k, v, o, kv_in, kv_out, 0};
-    return run_passes(pb, D, blk, dtype, st);
+    pb.p[0] = ltn::PassArgs{q, k, v, o, kv_in, kv_out, 0, gated ? u : nullptr, gated ? y : nullptr, eps};
+    if (!gated) return run_passes(pb, D, blk, dtype, st);
+    // The fused epilogue needs complete output rows in one workgroup, i.e. full-width
+    // slices and one workgroup per chain.  With few chains that leaves compute units idle;
+    // when the caller wants the attention output stored anyway (training), the plain
+    // forward at its usual split followed by the gate kernel on the stored output is then
+    // the faster way to the same result (measured on MI355X: below about 192 chains).
+    if (o && dtype == LTN_BF16 && chains < 192) {
+        pb.p[0].gate = nullptr;
+        pb.p[0].gated_out = nullptr;
+        const ltn_status s1 = run_passes(pb, D, blk, dtype, st);
+        if (s1 != LTN_OK) return s1;
+        return ltn::launch_gate(o, u, nullptr, y, nullptr, eps, chains * N, D, 1, 0, st) == hipSuccess
+                   ? LTN_OK : LTN_ERR_LAUNCH;
+    }
+    const hipError_t e = (dtype == LTN_BF16) ? ltn::launch_pass_bf16(pb, D, D, st)
+                                             : ltn::launch_pass_f32(pb, D, D, blk, st);
+    return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+}
+
+ltn_status ltn_attn_fwd(const void* q, const void* k, const void* v, void* o,
+                        const float* decay, const float* kv_in, float* kv_out,
+                        int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace;
+    return fwd_common(q, k, v, nullptr, o, nullptr, decay, kv_in, kv_out, 0.0f, Bt, H, N, D, block, dtype,
+                      workspace_bytes, stream, false);
+}
+
+ltn_status ltn_attn_fwd_gated(const void* q, const void* k, const void* v, const void* u, void* o, void* y,
+                              const float* decay, const float* kv_in, float* kv_out, float eps,
+                              int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace;
+    return fwd_common(q, k, v, u, o, y, decay, kv_in, kv_out, eps, Bt, H, N, D, block, dtype,
+                      workspace_bytes, stream, true);
+}
+
+static ltn_status gate_common(const void* x, const void* u, const void* d_y, void* o0, void* o1, float eps,
+                              long long rows, int D, ltn_dtype dtype, void* stream, bool bwd) {
+    if (rows < 0 || D <= 0) return LTN_ERR_SHAPE;
+    if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
+    if (D != 64 && D != 128) return LTN_ERR_UNSUPPORTED;
+    if (!(eps >= 0.0f)) return LTN_ERR_SHAPE;
+    if (rows == 0) return LTN_OK;
+    if (!x || !u || !o0 || (bwd && (!d_y || !o1))) return LTN_ERR_NULL;
+    if (!aligned16(x) || !aligned16(u) || !aligned16(d_y) || !aligned16(o0) || !aligned16(o1)) return LTN_ERR_ALIGN;
+    if (o0 == x || o0 == u || o0 == d_y || (bwd && (o1 == x || o1 == u || o1 == d_y || o1 == o0)))
+        return LTN_ERR_UNSUPPORTED;
+    const hipError_t e = ltn::launch_gate(x, u, d_y, o0, o1, eps, rows, D, dtype == LTN_BF16, bwd,
+                                          static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+}
+
+ltn_status ltn_gate_fwd(const void* x, const void* u, void* y, float eps,
+                        long long rows, int D, ltn_dtype dtype, void* stream) {
+    return gate_common(x, u, nullptr, y, nullptr, eps, rows, D, dtype, stream, false);
+}
+
+ltn_status ltn_gate_bwd(const void* x, const void* u, const void* d_y, void* d_x, void* d_u, float eps,
+                        long long rows, int D, ltn_dtype dtype, void* stream) {
+    return gate_common(x, u, d_y, d_x, d_u, eps, rows, D, dtype, stream, true);
 }
 
 ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void* d_o,

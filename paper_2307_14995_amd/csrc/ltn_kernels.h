@@ -22,6 +22,13 @@ struct PassArgs {
     const float* state_in;  // [chains, D, D] fp32 or nullptr (zero)
     float* state_out;       // [chains, D, D] fp32 or nullptr
     int rev;              // 0: first token -> last; 1: last -> first
+    // Gated, normalised epilogue (arXiv 2307.14995 Eq. 3 with the SimpleRMSNorm of
+    // Sec. 3.1.3 per head): when gate != nullptr the pass also writes
+    //   gated_out[t,:] = out[t,:] / sqrt(mean(out[t,:]^2) + eps) (.) gate[t,:]
+    // and `out` itself may be nullptr.  Needs full-width slices (dv = D), one pass.
+    const void* gate;     // [chains, N, D] or nullptr
+    void* gated_out;      // [chains, N, D]
+    float eps;
 };
 
 struct PassBatch {
@@ -44,6 +51,11 @@ hipError_t launch_state_copy(const float* kv_in, float* kv_out, size_t n, hipStr
 hipError_t launch_decode(const void* q, const void* k, const void* v, void* o, float* kv,
                          const float* decay, int chains, int H, int D, int is_bf16,
                          hipStream_t stream);
+
+// Gated SimpleRMSNorm on `rows` rows of D features (see ltn_gate.hip).  is_bwd = 0:
+// o0 = y (dy, o1 unused); is_bwd = 1: o0 = dx, o1 = du.
+hipError_t launch_gate(const void* x, const void* u, const void* dy, void* o0, void* o1, float eps,
+                       long long rows, int D, int is_bf16, int is_bwd, hipStream_t stream);
 
 // lambda^n, n >= 0, by binary powering in fp64 (only multiplications: exact up to
 // rounding, lambda = 0 gives 0^0 = 1, no transcendental).  Never called with n < 0.

@@ -171,12 +171,25 @@ struct ReadOffs {
 //   btile : full-width B tile in LDS (rows = tokens);  ctile : tile holding the C operand
 //   (CCOLS columns wide);  scopy : bf16 state copy [DV][D];  Af : A fragments of the strip
 //   out   : global address of this lane's token row, slice column 8g
-template <int D, int DV, int W, int CCOLS>
+//   GATED (full-width slices only): the strip's rows are complete output rows, so the
+//   token mixer's epilogue (Sec. 3.1.2 Eq. 3 with the SimpleRMSNorm of Sec. 3.1.3 per head),
+//   y = o / sqrt(mean(o^2) + eps) (.) u, is applied before anything is stored; gate/yout are
+//   this lane's addresses in U and Y (same position as out), out may be null.
+template <int D, int DV, int W, int CCOLS, bool GATED = false>
 __device__ __forceinline__ void output_pass(const char* btile, const char* ctile, const char* scopy,
                                             const Frag (&Af)[D / 32], const OutConsts<W>& k,
-                                            const ReadOffs<D, DV, CCOLS>& ro, char* out, bool store) {
+                                            const ReadOffs<D, DV, CCOLS>& ro, char* out, bool store,
+                                            const char* gate = nullptr, char* yout = nullptr, float eps = 0.f) {
     using C = Cfg<D, DV>;
     constexpr int KS = C::KS, NT = C::NT, RB = C::F::RB, CRB = Swz<CCOLS>::RB;
+    static_assert(!GATED || DV == D, "the gated epilogue needs complete output rows");
+
+    // gate values of this lane's token: issued first, used last
+    u32x4 uq[GATED ? NT / 2 : 1];
+    if constexpr (GATED) {
+#pragma unroll
+        for (int p = 0; p < NT / 2; ++p) uq[p] = store ? *(const u32x4*)(gate + 64 * p) : u32x4{0, 0, 0, 0};
+    }
 
     // -- transposed scores P^T[key tile kt <= W][own 16 rows]
     f32x4 sacc[W + 1];
@@ -249,28 +262,75 @@ __device__ __forceinline__ void output_pass(const char* btile, const char* ctile
     // halves, then between neighbouring rows) regroup them so that the lane holds the eight
     // consecutive features 32p + 8g .. +7 of its token: one 16-byte store per tile pair,
     // and the four lanes of a token write 64 contiguous bytes.
-    unsigned w[NT][2];
+    if constexpr (!GATED) {
+        unsigned w[NT][2];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        f32x4 r;
+        for (int nt = 0; nt < NT; ++nt) {
+            f32x4 r;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) r[j] = oi[nt][j] + k.qscale * oe[nt][j];
-        union { bf16x4 h; unsigned u[2]; } cv;
-        cv.h = to_bf16(r);
-        w[nt][0] = cv.u[0];
-        w[nt][1] = cv.u[1];
-    }
-#pragma unroll
-    for (int p = 0; p < NT / 2; ++p) {
-        u32x4 q;
-#pragma unroll
-        for (int d = 0; d < 2; ++d) {
-            auto s = __builtin_amdgcn_permlane32_swap(w[2 * p][d], w[2 * p + 1][d], false, false);
-            auto t = __builtin_amdgcn_permlane16_swap(s[0], s[1], false, false);
-            q[d] = t[0];
-            q[2 + d] = t[1];
+            for (int j = 0; j < 4; ++j) r[j] = oi[nt][j] + k.qscale * oe[nt][j];
+            union { bf16x4 h; unsigned u[2]; } cv;
+            cv.h = to_bf16(r);
+            w[nt][0] = cv.u[0];
+            w[nt][1] = cv.u[1];
         }
-        if (store) *(u32x4*)(out + 64 * p) = q;
+#pragma unroll
+        for (int p = 0; p < NT / 2; ++p) {
+            u32x4 q;
+#pragma unroll
+            for (int d = 0; d < 2; ++d) {
+                auto s = __builtin_amdgcn_permlane32_swap(w[2 * p][d], w[2 * p + 1][d], false, false);
+                auto t = __builtin_amdgcn_permlane16_swap(s[0], s[1], false, false);
+                q[d] = t[0];
+                q[2 + d] = t[1];
+            }
+            if (store) *(u32x4*)(out + 64 * p) = q;
+        }
+    } else {
+        // the same regrouping on fp32 values, after the row's mean square: the four lanes of
+        // a token (one per lane row) each hold a quarter of its D features
+        float ss = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                oi[nt][j] += k.qscale * oe[nt][j];
+                ss = fmaf(oi[nt][j], oi[nt][j], ss);
+            }
+        {   // sum over the four lane rows: swapping two copies leaves both halves' parts side by side
+            auto s = __builtin_amdgcn_permlane32_swap(__float_as_uint(ss), __float_as_uint(ss), false, false);
+            ss = __uint_as_float(s[0]) + __uint_as_float(s[1]);
+            auto t = __builtin_amdgcn_permlane16_swap(__float_as_uint(ss), __float_as_uint(ss), false, false);
+            ss = __uint_as_float(t[0]) + __uint_as_float(t[1]);
+        }
+        const float rstd = 1.0f / sqrtf(ss * (1.0f / D) + eps);
+#pragma unroll
+        for (int p = 0; p < NT / 2; ++p) {
+            float x[8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float lo = oi[2 * p][j], hi = oi[2 * p + 1][j];
+                auto s = __builtin_amdgcn_permlane32_swap(__float_as_uint(lo), __float_as_uint(hi), false, false);
+                auto t = __builtin_amdgcn_permlane16_swap(s[0], s[1], false, false);
+                x[j] = __uint_as_float(t[0]);
+                x[4 + j] = __uint_as_float(t[1]);
+            }
+            Frag uf, of, yf;
+            uf.u = uq[p];
+            const f32x8 ug = __builtin_convertvector(uf.v, f32x8);
+            f32x8 xo, xy;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                xo[j] = x[j];
+                xy[j] = x[j] * rstd * ug[j];
+            }
+            yf.v = __builtin_convertvector(xy, bf16x8);
+            if (store) *(u32x4*)(yout + 64 * p) = yf.u;
+            if (out) {
+                of.v = __builtin_convertvector(xo, bf16x8);
+                if (store) *(u32x4*)(out + 64 * p) = of.u;
+            }
+        }
     }
 }
 
@@ -391,6 +451,9 @@ struct Chain {            // what every wave of the workgroup knows about its pr
     const char* b;
     const char* c;
     char* out;
+    const char* gate;        // gated epilogue: U and Y, offset like out (out may then be null)
+    char* y;
+    float eps;
     const float* state_in;   // offset to this chain and column slice, or nullptr
     float* state_out;
     long long N;
@@ -402,7 +465,7 @@ struct Chain {            // what every wave of the workgroup knows about its pr
 
 // =============================================================== pass body
 
-template <int D, int DV, int W>
+template <int D, int DV, int W, bool GATED>
 __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, int lane) {
     using C = Cfg<D, DV>;
     constexpr int KS = C::KS;
@@ -416,7 +479,10 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, in
     // this lane's token row (16W + i16) of block 0
     const long long r0 = ch.rev ? (ch.N - 1 - (16 * W + i16)) : (long long)(16 * W + i16);
     const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
-    char* po = ch.out + r0 * ROW + (8 * g) * 2;
+    const long long lane_off = r0 * ROW + (8 * g) * 2;
+    char* po = ch.out ? ch.out + lane_off : nullptr;
+    const char* pu = GATED ? ch.gate + lane_off : nullptr;
+    char* py = GATED ? ch.y + lane_off : nullptr;
 
     __syncthreads();                       // block 0 tiles and the initial state copy are in LDS
     int stage = 0;
@@ -427,8 +493,11 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, in
         Frag Af[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) Af[ks].u = *(const u32x4*)(st + (16 * W) * C::F::RB + ro.row[ks]);
-        output_pass<D, DV, W, DV>(st + C::F::BYTES, st + 2 * C::F::BYTES, smem + C::P_SB + (blk & 1) * C::SBYTES,
-                                  Af, k, ro, po + (long long)blk * step, more || row_ok);
+        const long long bo = (long long)blk * step;
+        output_pass<D, DV, W, DV, GATED>(st + C::F::BYTES, st + 2 * C::F::BYTES,
+                                         smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
+                                         po ? po + bo : nullptr, more || row_ok,
+                                         GATED ? pu + bo : nullptr, GATED ? py + bo : nullptr, ch.eps);
         if (more) __syncthreads();
         stage = (stage + 1 == C::PST) ? 0 : stage + 1;
     }
@@ -521,7 +590,7 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
     }
 }
 
-template <int D, int DV>
+template <int D, int DV, bool GATED>
 __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int wg, char* smem, unsigned lds0,
                                           int wave, int lane) {
     int chain, within;
@@ -536,7 +605,10 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
     ch.a = (const char*)P.a + chain_off;
     ch.b = (const char*)P.b + chain_off;
     ch.c = (const char*)P.c + chain_off + col_off;
-    ch.out = (char*)P.out + chain_off + col_off;
+    ch.out = P.out ? (char*)P.out + chain_off + col_off : nullptr;
+    ch.gate = GATED ? (const char*)P.gate + chain_off : nullptr;
+    ch.y = GATED ? (char*)P.gated_out + chain_off : nullptr;
+    ch.eps = P.eps;
     ch.state_in = P.state_in ? P.state_in + (size_t)chain * D * D + (size_t)split * DV : nullptr;
     ch.state_out = P.state_out ? P.state_out + (size_t)chain * D * D + (size_t)split * DV : nullptr;
     ch.N = pb.N;
@@ -546,10 +618,10 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
     ch.lam = pb.decay[chain % pb.H];
 
     switch (wave) {
-        case 0: pass_output_wave<D, DV, 0>(ch, smem, lane); break;
-        case 1: pass_output_wave<D, DV, 1>(ch, smem, lane); break;
-        case 2: pass_output_wave<D, DV, 2>(ch, smem, lane); break;
-        case 3: pass_output_wave<D, DV, 3>(ch, smem, lane); break;
+        case 0: pass_output_wave<D, DV, 0, GATED>(ch, smem, lane); break;
+        case 1: pass_output_wave<D, DV, 1, GATED>(ch, smem, lane); break;
+        case 2: pass_output_wave<D, DV, 2, GATED>(ch, smem, lane); break;
+        case 3: pass_output_wave<D, DV, 3, GATED>(ch, smem, lane); break;
         default: pass_state_wave<D, DV>(ch, smem, lds0, lane, wave - 4); break;
     }
 }
@@ -560,27 +632,33 @@ __device__ __forceinline__ unsigned lds_address(const char* p) {
     return (unsigned)(size_t)(const __attribute__((address_space(3))) char*)p;
 }
 
-template <int D, int DV>
+template <int D, int DV, bool GATED>
 __global__ __launch_bounds__(kThreads)
 void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
     __shared__ __attribute__((aligned(1024))) char smem[Cfg<D, DV>::PASS_TOTAL];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: role dispatch is a uniform branch
-    pass_body<D, DV>(pb, nsplit, blockIdx.x, smem, lds_address(smem), wave, tid & 63);
+    pass_body<D, DV, GATED>(pb, nsplit, blockIdx.x, smem, lds_address(smem), wave, tid & 63);
 }
 
-template <int D, int DV>
+template <int D, int DV, bool GATED = false>
 hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
     const int nsplit = D / DV;
     const long long wgs = (long long)pb.chains * pb.count * nsplit;
     if (wgs <= 0 || wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((pass_bf16_kernel<D, DV>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
+    hipLaunchKernelGGL((pass_bf16_kernel<D, DV, GATED>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream) {
+    if (pb.p[0].gate) {                    // gated epilogue: one pass, complete output rows
+        if (pb.count != 1 || dv != D || !pb.p[0].gated_out) return hipErrorInvalidValue;
+        if (D == 128) return launch_t<128, 128, true>(pb, stream);
+        if (D == 64) return launch_t<64, 64, true>(pb, stream);
+        return hipErrorInvalidValue;
+    }
     if (D == 128 && dv == 128) return launch_t<128, 128>(pb, stream);
     if (D == 128 && dv == 64) return launch_t<128, 64>(pb, stream);
     if (D == 128 && dv == 32) return launch_t<128, 32>(pb, stream);

@@ -16,9 +16,13 @@ namespace {
 
 constexpr int kThreads = 256;
 
-template <int D, int DV, int B>
+// GATED (full-width slices, one pass): the block's output rows are complete, so the token
+// mixer's epilogue (Sec. 3.1.2 Eq. 3 with the SimpleRMSNorm of Sec. 3.1.3 per head),
+// y = o / sqrt(mean(o^2) + eps) (.) u, is applied to them from an LDS copy.
+template <int D, int DV, int B, bool GATED>
 __global__ __launch_bounds__(kThreads)
 void pass_f32_kernel(const PassBatch pb, const int nsplit) {
+    static_assert(!GATED || DV == D, "the gated epilogue needs complete output rows");
     constexpr int DP = D + 1;     // padded pitches: conflict-free column walks
     constexpr int BP = B + 1;
     __shared__ float As[B * DP];
@@ -27,6 +31,8 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
     __shared__ float Ps[B * BP];
     __shared__ float St[D * DV];
     __shared__ float pw[B + 1];   // lambda^0 .. lambda^B
+    __shared__ float Os[GATED ? B * DV : 1];
+    __shared__ float rstd[GATED ? B : 1];
 
     const int tid = threadIdx.x;
     int chain, within;
@@ -42,7 +48,9 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
     const float* Ap = (const float*)P.a + chain_off;
     const float* Bp = (const float*)P.b + chain_off;
     const float* Cp = (const float*)P.c + chain_off + (size_t)split * DV;
-    float* Op = (float*)P.out + chain_off + (size_t)split * DV;
+    float* Op = P.out ? (float*)P.out + chain_off + (size_t)split * DV : nullptr;
+    const float* Up = GATED ? (const float*)P.gate + chain_off : nullptr;
+    float* Yp = GATED ? (float*)P.gated_out + chain_off : nullptr;
 
     for (int n = tid; n <= B; n += kThreads) pw[n] = decay_pow(lam, n);
     for (int e = tid; e < D * DV; e += kThreads) {
@@ -88,13 +96,32 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
             for (int c = 0; c <= r; ++c) intra = fmaf(Ps[r * BP + c], Cs[c * DV + j], intra);
 #pragma unroll 8
             for (int i = 0; i < D; ++i) inter = fmaf(As[r * DP + i], St[i * DV + j], inter);
-            if (r < len) {
+            const float o = fmaf(pw[r + 1], inter, intra);
+            if (GATED) Os[e] = o;
+            if (r < len && Op) {
                 const long long t = t0 + r;
                 const size_t gr = (size_t)(rev ? (N - 1 - t) : t);
-                Op[gr * D + j] = fmaf(pw[r + 1], inter, intra);
+                Op[gr * D + j] = o;
             }
         }
         __syncthreads();
+        if constexpr (GATED) {
+            if (tid < len) {
+                float ss = 0.0f;
+                for (int j = 0; j < DV; ++j) {
+                    const float o = Os[tid * DV + (j + tid) % DV];   // skewed walk: no bank conflicts
+                    ss = fmaf(o, o, ss);
+                }
+                rstd[tid] = 1.0f / sqrtf(ss * (1.0f / D) + P.eps);
+            }
+            __syncthreads();
+            for (int e = tid; e < len * DV; e += kThreads) {
+                const int r = e / DV, j = e % DV;
+                const long long t = t0 + r;
+                const size_t gr = (size_t)(rev ? (N - 1 - t) : t);
+                Yp[gr * D + j] = Os[e] * rstd[r] * Up[gr * D + j];
+            }
+        }
         // ---- state update (each thread owns its state entries: no hazard inside the step)
         for (int e = tid; e < D * DV; e += kThreads) {
             const int i = e / DV, j = e % DV;
@@ -113,12 +140,12 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
     }
 }
 
-template <int D, int DV, int B>
+template <int D, int DV, int B, bool GATED = false>
 hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
     const int nsplit = D / DV;
     const long long wgs = (long long)pb.chains * pb.count * nsplit;
     if (wgs <= 0 || wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((pass_f32_kernel<D, DV, B>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
+    hipLaunchKernelGGL((pass_f32_kernel<D, DV, B, GATED>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
     return hipGetLastError();
 }
 
@@ -131,6 +158,14 @@ __global__ void state_copy_kernel(const float* __restrict__ in, float* __restric
 }  // namespace
 
 hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStream_t stream) {
+    if (pb.p[0].gate) {                    // gated epilogue: one pass, complete output rows
+        if (pb.count != 1 || dv != D || !pb.p[0].gated_out) return hipErrorInvalidValue;
+#define LTN_F32_GATED(d, b) if (D == d && block == b) return launch_t<d, d, b, true>(pb, stream)
+        LTN_F32_GATED(64, 16); LTN_F32_GATED(64, 32); LTN_F32_GATED(64, 64);
+        LTN_F32_GATED(128, 16); LTN_F32_GATED(128, 32);
+#undef LTN_F32_GATED
+        return hipErrorInvalidValue;
+    }
 #define LTN_F32_CASE(d, v, b) if (D == d && dv == v && block == b) return launch_t<d, v, b>(pb, stream)
     LTN_F32_CASE(64, 64, 16); LTN_F32_CASE(64, 64, 32); LTN_F32_CASE(64, 64, 64);
     LTN_F32_CASE(64, 32, 16); LTN_F32_CASE(64, 32, 32); LTN_F32_CASE(64, 32, 64);

@@ -59,6 +59,11 @@ def make_do(Bt: int, H: int, N: int, D: int, dtype: torch.dtype, seed: int) -> t
     return _randn((Bt, H, N, D), seed * 16 + 4, 1.0, dtype)
 
 
+def make_gate(Bt: int, H: int, N: int, D: int, dtype: torch.dtype, seed: int) -> torch.Tensor:
+    """Gate U ~ N(0,1), shape [Bt,H,N,D] (a projection of normalised activations)."""
+    return _randn((Bt, H, N, D), seed * 16 + 9, 1.0, dtype)
+
+
 def make_step_qkv(Bt: int, H: int, D: int, dtype: torch.dtype, seed: int, step: int):
     """One decode token per (b,h): q, k, v ~ N(0,1)/sqrt(D), shape [Bt,H,D]."""
     s = 1.0 / math.sqrt(D)

@@ -1,0 +1,183 @@
+"""GPU parity of the gated, normalised output (Sec. 3.1.2 Eq. 3 with the SimpleRMSNorm of
+Sec. 3.1.3 per head): the fused forward epilogue and the stand-alone gate kernels, through
+the C ABI, against the fp64 oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2307_14995_amd as ltn
+from paper_2307_14995_amd import synth
+from oracle import ltn_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float32: 1e-4, torch.bfloat16: 1e-2}
+
+
+def dev():
+    return torch.device("cuda:0")
+
+
+def gpu(*ts):
+    return tuple(None if t is None else t.to(dev()) for t in ts)
+
+
+def check(name, got, ref, tol):
+    assert torch.isfinite(got.float()).all(), f"{name}: non-finite values"
+    err = orc.max_rel_l2(got, ref)
+    assert err <= tol, f"{name}: rel-L2 {err:.3e} > {tol:g}"
+
+
+def mixed_decay(H):
+    d = synth.decay_bench_rule(H).clone()
+    d[0] = 1.0
+    if H > 1:
+        d[1] = 0.0
+    if H > 2:
+        d[2] = float(np.exp(-8.0))
+    return d
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("eps", [0.0, 1e-5])
+def test_gate_rows_forward_backward(dtype, D, eps):
+    rows = 4099                               # not a multiple of any rows-per-workgroup step
+    g = torch.Generator().manual_seed(900 + D)
+    x = (torch.randn(rows, D, generator=g) * 0.7).to(dtype)
+    u = torch.randn(rows, D, generator=g).to(dtype)
+    dy = torch.randn(rows, D, generator=g).to(dtype)
+    xd, ud, dyd = gpu(x, u, dy)
+    y = ltn.ltn_gate_fwd(xd, ud, eps)
+    dx, du = ltn.ltn_gate_bwd(xd, ud, dyd, eps)
+    tol = TOL[dtype]
+    assert orc.rel_l2(y, orc.gate_fwd(x, u, eps)) <= tol
+    dx_ref, du_ref = orc.gate_bwd(x, u, dy, eps)
+    assert orc.rel_l2(dx, dx_ref) <= tol
+    assert orc.rel_l2(du, du_ref) <= tol
+    # row-wise too: no row may be off (catches a reduction that mixes neighbouring rows)
+    yr = orc.gate_fwd(x, u, eps)
+    row_err = np.linalg.norm(y.double().cpu().numpy() - yr, axis=1) / np.linalg.norm(yr, axis=1)
+    assert row_err.max() <= 4 * tol
+
+
+def test_gate_rows_empty_and_errors():
+    x = torch.zeros(0, 128, dtype=torch.bfloat16, device=dev())
+    assert ltn.ltn_gate_fwd(x, x).shape == (0, 128)
+    a = torch.ones(4, 128, dtype=torch.bfloat16, device=dev())
+    with pytest.raises(ltn.LtnError):
+        ltn.ltn_gate_fwd(a, a, out=a)                     # output aliases an input
+    with pytest.raises(ltn.LtnError):
+        ltn.ltn_gate_fwd(a[:, :96].contiguous(), a[:, :96].contiguous())   # D = 96 not built
+    with pytest.raises(ltn.LtnError):
+        ltn.ltn_gate_fwd(a, a, eps=-1.0)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("N", [1, 63, 64, 65, 200, 517])
+def test_bf16_forward_gated_ragged(D, N):
+    Bt, H = 1, 3
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 400 + N)
+    u = synth.make_gate(Bt, H, N, D, torch.bfloat16, 400 + N)
+    decay = mixed_decay(H)
+    o_ref, y_ref = orc.fwd_gated(q, k, v, u, decay, eps=1e-6)
+    _, kv_ref = orc.fwd_recurrent(q, k, v, decay, return_state=True)
+    o, y, kv = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6, return_state=True)
+    check("O", o, o_ref, 1e-2)
+    check("Y", y, y_ref, 1e-2)
+    check("kv", kv, kv_ref, 1e-2)
+    # inference form: the attention output is not stored (always the fused epilogue)
+    o2, y2 = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6, store_o=False)
+    assert o2 is None
+    check("Y (o not stored)", y2, y_ref, 1e-2)
+    # and O is what the plain forward at full width gives
+    assert orc.rel_l2(o, ltn.ltn_attn_fwd(*gpu(q, k, v, decay))) <= 1e-2
+
+
+@pytest.mark.parametrize("D,block", [(64, 16), (64, 64), (128, 32)])
+@pytest.mark.parametrize("N", [1, 37, 130])
+def test_fp32_forward_gated(D, block, N):
+    Bt, H = 2, 3
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.float32, 500 + N)
+    u = synth.make_gate(Bt, H, N, D, torch.float32, 500 + N)
+    decay = mixed_decay(H)
+    o_ref, y_ref = orc.fwd_gated(q, k, v, u, decay, eps=0.0)
+    o, y = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=0.0, block=block)
+    check("O", o, o_ref, 1e-4)
+    check("Y", y, y_ref, 1e-4)
+    _, y2 = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=0.0, block=block, store_o=False)
+    assert torch.equal(y2, y)
+
+
+def test_bf16_forward_gated_continues_a_state():
+    Bt, H, N, D = 2, 4, 300, 128
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 43)
+    u = synth.make_gate(Bt, H, N, D, torch.bfloat16, 43)
+    decay = mixed_decay(H)
+    cut = 131
+    qd, kd, vd, ud, dd = gpu(q, k, v, u, decay)
+    _, kv1 = ltn.ltn_attn_fwd(qd[:, :, :cut].contiguous(), kd[:, :, :cut].contiguous(),
+                              vd[:, :, :cut].contiguous(), dd, return_state=True)
+    _, y2 = ltn.ltn_attn_fwd_gated(qd[:, :, cut:].contiguous(), kd[:, :, cut:].contiguous(),
+                                   vd[:, :, cut:].contiguous(), ud[:, :, cut:].contiguous(), dd,
+                                   eps=1e-6, kv_in=kv1)
+    _, y_ref = orc.fwd_gated(q, k, v, u, decay, eps=1e-6)
+    check("Y tail", y2, y_ref[:, :, cut:], 1e-2)
+
+
+def test_bf16_forward_gated_many_chains_fused_with_o():
+    """>= 192 chains: the fused epilogue also when O is stored; both outputs against the oracle."""
+    Bt, H, N, D = 8, 25, 70, 128             # 200 chains, ragged N
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 45)
+    u = synth.make_gate(Bt, H, N, D, torch.bfloat16, 45)
+    decay = synth.decay_bench_rule(H)
+    o_ref, y_ref = orc.fwd_gated(q, k, v, u, decay, eps=1e-6)
+    o, y = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6)
+    check("O", o, o_ref, 1e-2)
+    check("Y", y, y_ref, 1e-2)
+    _, y2 = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6, store_o=False)
+    assert torch.equal(y2, y)                # same kernel, same bits
+
+
+def test_training_chain_through_the_gate():
+    """fwd_gated (stores O) -> gate_bwd -> attn_bwd equals the oracle's chain rule."""
+    Bt, H, N, D = 2, 3, 160, 128
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 47)
+    u = synth.make_gate(Bt, H, N, D, torch.bfloat16, 47)
+    dy = synth.make_do(Bt, H, N, D, torch.bfloat16, 47)
+    decay = synth.decay_bench_rule(H)
+    qd, kd, vd, ud, dyd, dd = gpu(q, k, v, u, dy, decay)
+    o, y = ltn.ltn_attn_fwd_gated(qd, kd, vd, ud, dd, eps=1e-6)
+    d_o, d_u = ltn.ltn_gate_bwd(o, ud, dyd, eps=1e-6)
+    dq, dk, dv = ltn.ltn_attn_bwd(qd, kd, vd, d_o, dd)
+    o_ref, _ = orc.fwd_gated(q, k, v, u, decay, eps=1e-6)
+    do_ref, du_ref = orc.gate_bwd(o_ref, u, dy, eps=1e-6)
+    check("dO", d_o, do_ref, 2e-2)          # two bf16 roundings deep (O stored, then dO)
+    check("dU", d_u, du_ref, 1e-2)
+    for n, x, r in zip(("dQ", "dK", "dV"), (dq, dk, dv), orc.bwd_recurrent(q, k, v, do_ref, decay)):
+        check(n, x, r, 2e-2)
+
+
+def test_forward_gated_full_size_sampled_chains():
+    """The 7B-shaped workload in the launch configuration the report times; sampled chains."""
+    w = synth.CONFIGS["cfg3_7b"]
+    q, k, v = synth.make_qkv(w.Bt, w.H, w.N, w.D, w.dtype, w.seed)
+    u = synth.make_gate(w.Bt, w.H, w.N, w.D, w.dtype, w.seed)
+    decay = synth.decay_bench_rule(w.H)
+    _, y = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6, store_o=False)
+    for b, h in ((0, 0), (1, 17), (3, 31)):
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        o_ref = orc.fwd_recurrent(q[sl], k[sl], v[sl], decay[h:h + 1])
+        y_ref = orc.gate_fwd(o_ref, u[sl], 1e-6)
+        assert orc.rel_l2(y[sl], y_ref) <= 1e-2, (b, h)
+
+
+def test_forward_gated_argument_errors():
+    Bt, H, N, D = 1, 2, 64, 128
+    q, k, v = gpu(*synth.make_qkv(Bt, H, N, D, torch.bfloat16, 3))
+    u, = gpu(synth.make_gate(Bt, H, N, D, torch.bfloat16, 3))
+    dd, = gpu(synth.decay_bench_rule(H))
+    with pytest.raises(ltn.LtnError):
+        ltn.ltn_attn_fwd_gated(q, k, v, u, dd, y_out=u)          # Y aliases the gate
+    with pytest.raises(ltn.LtnError):
+        ltn.ltn_attn_fwd_gated(q, k, v, u, dd, eps=float("nan"))
