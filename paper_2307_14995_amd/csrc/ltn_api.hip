@@ -45,11 +45,75 @@ ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype 
     return LTN_OK;
 }
 
-ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, hipStream_t stream) {
-    const int dv = pick_dv((long long)pb.chains * pb.count, D, dtype);
-    const hipError_t e = (dtype == LTN_BF16) ? ltn::launch_pass_bf16(pb, D, dv, stream)
-                                             : ltn::launch_pass_f32(pb, D, dv, blk, stream);
-    return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+// Sequence-parallel plan.  With few chains even the deepest value-column split leaves
+// compute units idle and makes every workgroup re-read A and B; cutting each chain into
+// segments instead gives full-width workgroups to all compute units at the price of one
+// extra read of B and C (the state-only sweep) and two more launches.  Measured on MI355X
+// (8 and 32 chains, N = 4096 .. 16384, forward and backward): pays when a chain can be cut at
+// least 8 ways into segments of at least 1024 tokens without exceeding one round of compute
+// units, and never otherwise.  bf16 kernels only.
+// LTN_ATTN_SEGS (debug, used by the parity tests) forces a segment count.
+struct SegPlan { int segs; long long seg_len; };
+
+SegPlan pick_segments(long long chain_passes, long long N, ltn_dtype dtype) {
+    SegPlan plan = {1, 0};
+    if (dtype != LTN_BF16 || chain_passes <= 0 || N <= 64) return plan;
+    long long want = 256 / chain_passes;
+    if (want > N / 1024) want = N / 1024;
+    if (want < 8) want = 1;
+    if (const char* e = std::getenv("LTN_ATTN_SEGS")) {
+        const long long v = std::atoll(e);
+        if (v >= 1 && v <= 4096) want = v;
+    }
+    if (want <= 1) return plan;
+    long long len = (N + want - 1) / want;
+    len = (len + 63) / 64 * 64;
+    const long long segs = (N + len - 1) / len;
+    if (segs <= 1 || segs > 0x7fff) return plan;
+    plan.segs = (int)segs;
+    plan.seg_len = len;
+    return plan;
+}
+
+ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void* workspace, hipStream_t stream) {
+    const long long chain_passes = (long long)pb.chains * pb.count;
+    const SegPlan plan = pick_segments(chain_passes, pb.N, dtype);
+    pb.segs = 1;
+    if (plan.segs == 1) {
+        const int dv = pick_dv(chain_passes, D, dtype);
+        const hipError_t e = (dtype == LTN_BF16) ? ltn::launch_pass_bf16(pb, D, dv, stream)
+                                                 : ltn::launch_pass_f32(pb, D, dv, blk, stream);
+        return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+    }
+    // three launches: segment end states from zero, scan, then the pass proper per segment
+    if (!workspace) return LTN_ERR_NULL;
+    float* states = static_cast<float*>(workspace);
+    const size_t per_pass = (size_t)pb.chains * plan.segs * D * D;
+    const float* kv_in = pb.p[0].state_in;
+    float* kv_out = pb.p[0].state_out;
+    ltn::PassBatch sweep = pb;
+    sweep.segs = plan.segs;
+    sweep.seg_len = plan.seg_len;
+    sweep.state_only = 1;
+    sweep.need_last = kv_out != nullptr;
+    for (int i = 0; i < pb.count; ++i) {
+        sweep.p[i].out = nullptr;
+        sweep.p[i].state_in = nullptr;
+        sweep.p[i].state_out = states + i * per_pass;
+    }
+    if (ltn::launch_pass_bf16(sweep, D, D, stream) != hipSuccess) return LTN_ERR_LAUNCH;
+    if (ltn::launch_segment_scan(states, kv_in, kv_out, pb.decay, pb.count, pb.chains, pb.H, plan.segs,
+                                 plan.seg_len, pb.N, D, stream) != hipSuccess)
+        return LTN_ERR_LAUNCH;
+    ltn::PassBatch main = pb;
+    main.segs = plan.segs;
+    main.seg_len = plan.seg_len;
+    for (int i = 0; i < pb.count; ++i) {
+        main.p[i].state_in = states + i * per_pass;
+        main.p[i].state_out = nullptr;
+    }
+    const int dv = pick_dv(chain_passes * plan.segs, D, dtype);
+    return ltn::launch_pass_bf16(main, D, dv, stream) == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
 }
 
 }  // namespace
@@ -63,7 +127,15 @@ int ltn_attn_pick_block(int D, ltn_dtype dtype) {
     return 0;
 }
 
-size_t ltn_attn_workspace_bytes(int, int, long long, int, int, ltn_dtype, int) { return 0; }
+size_t ltn_attn_workspace_bytes(int Bt, int H, long long N, int D, int block, ltn_dtype dtype, int is_bwd) {
+    (void)block;
+    if (Bt <= 0 || H <= 0 || N <= 0 || (D != 64 && D != 128)) return 0;
+    const long long chains = (long long)Bt * H;
+    const int count = is_bwd ? 3 : 1;
+    const SegPlan plan = pick_segments(chains * count, N, dtype);
+    if (plan.segs == 1) return 0;
+    return (size_t)count * (size_t)chains * (size_t)plan.segs * D * D * sizeof(float);   // one fp32 state per segment
+}
 
 ltn_status ltn_attn_check_decay(const float* decay_host, int H) {
     if (!decay_host) return LTN_ERR_NULL;
@@ -90,7 +162,7 @@ const char* ltn_status_str(ltn_status s) {
 static ltn_status fwd_common(const void* q, const void* k, const void* v, const void* u, void* o, void* y,
                              const float* decay, const float* kv_in, float* kv_out, float eps,
                              int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
-                             size_t workspace_bytes, void* stream, bool gated) {
+                             void* workspace, size_t workspace_bytes, void* stream, bool gated) {
     const bool empty = (Bt == 0 || H == 0 || N == 0);   // no token is read or written
     if (!decay || (!empty && (!q || !k || !v || (gated ? (!u || !y) : !o)))) return LTN_ERR_NULL;
     int blk = 0;
@@ -99,7 +171,8 @@ static ltn_status fwd_common(const void* q, const void* k, const void* v, const 
     if (gated && !(eps >= 0.0f)) return LTN_ERR_SHAPE;
     if (workspace_bytes < ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, 0)) return LTN_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(u) || !aligned16(y) ||
-        !aligned16(kv_in) || !aligned16(kv_out) || (reinterpret_cast<uintptr_t>(decay) & 3u))
+        !aligned16(kv_in) || !aligned16(kv_out) || !aligned16(workspace) ||
+        (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
     if (!empty) {
         const void* ins[4] = {q, k, v, u};
@@ -121,13 +194,14 @@ static ltn_status fwd_common(const void* q, const void* k, const void* v, const 
                    ? LTN_OK : LTN_ERR_LAUNCH;
     }
     ltn::PassBatch pb = {};
+    pb.segs = 1;
     pb.count = 1;
     pb.decay = decay;
     pb.chains = (int)chains;
     pb.H = H;
     pb.N = N;
     pb.p[0] = ltn::PassArgs{q, k, v, o, kv_in, kv_out, 0, gated ? u : nullptr, gated ? y : nullptr, eps};
-    if (!gated) return run_passes(pb, D, blk, dtype, st);
+    if (!gated) return run_passes(pb, D, blk, dtype, workspace, st);
     // The fused epilogue needs complete output rows in one workgroup, i.e. full-width
     // slices and one workgroup per chain.  With few chains that leaves compute units idle;
     // when the caller wants the attention output stored anyway (training), the plain
@@ -136,7 +210,7 @@ static ltn_status fwd_common(const void* q, const void* k, const void* v, const 
     if (o && dtype == LTN_BF16 && chains < 192) {
         pb.p[0].gate = nullptr;
         pb.p[0].gated_out = nullptr;
-        const ltn_status s1 = run_passes(pb, D, blk, dtype, st);
+        const ltn_status s1 = run_passes(pb, D, blk, dtype, workspace, st);
         if (s1 != LTN_OK) return s1;
         return ltn::launch_gate(o, u, nullptr, y, nullptr, eps, chains * N, D, 1, 0, st) == hipSuccess
                    ? LTN_OK : LTN_ERR_LAUNCH;
@@ -150,18 +224,16 @@ ltn_status ltn_attn_fwd(const void* q, const void* k, const void* v, void* o,
                         const float* decay, const float* kv_in, float* kv_out,
                         int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
                         void* workspace, size_t workspace_bytes, void* stream) {
-    (void)workspace;
     return fwd_common(q, k, v, nullptr, o, nullptr, decay, kv_in, kv_out, 0.0f, Bt, H, N, D, block, dtype,
-                      workspace_bytes, stream, false);
+                      workspace, workspace_bytes, stream, false);
 }
 
 ltn_status ltn_attn_fwd_gated(const void* q, const void* k, const void* v, const void* u, void* o, void* y,
                               const float* decay, const float* kv_in, float* kv_out, float eps,
                               int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
                               void* workspace, size_t workspace_bytes, void* stream) {
-    (void)workspace;
     return fwd_common(q, k, v, u, o, y, decay, kv_in, kv_out, eps, Bt, H, N, D, block, dtype,
-                      workspace_bytes, stream, true);
+                      workspace, workspace_bytes, stream, true);
 }
 
 static ltn_status gate_common(const void* x, const void* u, const void* d_y, void* o0, void* o1, float eps,
@@ -194,7 +266,6 @@ ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void*
                         void* dq, void* dk, void* dv, const float* decay,
                         int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
                         void* workspace, size_t workspace_bytes, void* stream) {
-    (void)workspace;
     const bool empty = (Bt == 0 || H == 0 || N == 0);
     if (!decay || (!empty && (!q || !k || !v || !d_o || !dq || !dk || !dv))) return LTN_ERR_NULL;
     int blk = 0;
@@ -202,7 +273,7 @@ ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void*
     if (cs != LTN_OK) return cs;
     if (workspace_bytes < ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, 1)) return LTN_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) ||
-        !aligned16(dk) || !aligned16(dv) || (reinterpret_cast<uintptr_t>(decay) & 3u))
+        !aligned16(dk) || !aligned16(dv) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
     const void* ins[4] = {q, k, v, d_o};
     const void* outs[3] = {dq, dk, dv};
@@ -221,6 +292,7 @@ ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void*
     //   dV = ((Q K^T)(.)M)^T  dO  -> pass(K, Q, dO), last token -> first
     //   dK = ((dO V^T)(.)M)^T Q   -> pass(V, dO, Q), last token -> first
     ltn::PassBatch pb = {};
+    pb.segs = 1;
     pb.count = 3;
     pb.decay = decay;
     pb.chains = (int)chains;
@@ -229,7 +301,7 @@ ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void*
     pb.p[0] = ltn::PassArgs{k, q, d_o, dv, nullptr, nullptr, 1};
     pb.p[1] = ltn::PassArgs{v, d_o, q, dk, nullptr, nullptr, 1};
     pb.p[2] = ltn::PassArgs{d_o, v, k, dq, nullptr, nullptr, 0};
-    return run_passes(pb, D, blk, dtype, st);
+    return run_passes(pb, D, blk, dtype, workspace, st);
 }
 
 ltn_status ltn_attn_decode_step(const void* q, const void* k, const void* v, void* o,

@@ -38,6 +38,14 @@ struct PassBatch {
     int chains;           // Bt * H
     int H;
     long long N;
+    // Sequence-parallel form: every chain is cut into `segs` segments of seg_len tokens
+    // (a multiple of 64; the last may be shorter) along the pass's own token order, each
+    // handled by its own workgroups.  state_in / state_out then hold one state per
+    // (chain, segment): [chains * segs, D, D].  segs = 1: the whole chain, seg_len unused.
+    int segs;
+    long long seg_len;
+    int state_only;       // 1: compute only each segment's end state from a zero state
+    int need_last;        // state_only: also for the last segment of a chain
 };
 
 // bf16 MFMA kernel, block length 64.  D in {64,128}; dv = value columns per workgroup
@@ -45,6 +53,13 @@ struct PassBatch {
 hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream);
 // fp32 kernel.  D in {64,128}, block in {16,32,64}, D*block <= 4096.
 hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStream_t stream);
+// Turns the segment-local end states L[pass][chain][g] in `states` (as written by a
+// state_only launch) into the states at each segment's start, in place:
+//   S[0] = kv_in (pass 0 only) or 0,   S[g+1] = lambda^len(g) S[g] + L[g],
+// and writes the state after the last segment to kv_out (pass 0) when given.
+hipError_t launch_segment_scan(float* states, const float* kv_in, float* kv_out, const float* decay,
+                               int count, int chains, int H, int segs, long long seg_len, long long N,
+                               int D, hipStream_t stream);
 // kv[c] (or zeros if null) -> kv_out[c], n floats.
 hipError_t launch_state_copy(const float* kv_in, float* kv_out, size_t n, hipStream_t stream);
 // One decode step, see ltn_attn_decode_step.

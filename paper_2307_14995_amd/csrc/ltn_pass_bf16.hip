@@ -465,9 +465,19 @@ struct Chain {            // what every wave of the workgroup knows about its pr
 
 // =============================================================== pass body
 
-template <int D, int DV, int W, bool GATED>
+// MODE of a workgroup: the plain pass, the pass with the gated epilogue, or the
+// state-only sweep of the sequence-parallel form (no outputs: only the segment's end state).
+enum { kPlain = 0, kGated = 1, kStateOnly = 2 };
+
+template <int D, int DV, int W, int MODE>
 __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, int lane) {
     using C = Cfg<D, DV>;
+    constexpr bool GATED = MODE == kGated;
+    if constexpr (MODE == kStateOnly) {    // nothing to produce: keep the barriers company
+        __syncthreads();
+        for (int blk = 0; blk + 1 < ch.T; ++blk) __syncthreads();
+        return;
+    }
     constexpr int KS = C::KS;
     constexpr long long ROW = D * 2;
     const int g = lane >> 4, i16 = lane & 15;
@@ -503,10 +513,11 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, in
     }
 }
 
-template <int D, int DV>
+template <int D, int DV, int MODE>
 __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, unsigned lds0, int lane, int u) {
     using C = Cfg<D, DV>;
     constexpr int MT = C::MT, NT = C::NT;
+    constexpr bool SO = MODE == kStateOnly;          // no A tile, no published state copies
     constexpr long long ROW = D * 2;
     const int g = lane >> 4, i16 = lane & 15;
     const int dk0 = u * (D / 4);
@@ -539,14 +550,14 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
     TileDma<DV> dc;
     db.init(u, lane, rs);
     dc.init(u, lane, rs);
-    constexpr int kLoads = 2 * TileDma<D>::PER_WAVE + TileDma<DV>::PER_WAVE;   // per block, per wave
+    constexpr int kLoads = (SO ? 1 : 2) * TileDma<D>::PER_WAVE + TileDma<DV>::PER_WAVE;   // per block, per wave
     static_assert((C::PST - 2) * kLoads <= 63, "vmcnt field");
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
     auto fetch = [&](int b, int stage) {
         b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block into a free stage
         const int valid = valid_of(b);
         const unsigned lds = lds0 + (unsigned)(stage * C::PSTAGE);
-        db.issue(pa0 + (long long)b * step, lds, u, valid);
+        if constexpr (!SO) db.issue(pa0 + (long long)b * step, lds, u, valid);
         db.issue(pb0 + (long long)b * step, lds + C::F::BYTES, u, valid);
         dc.issue(pc0 + (long long)b * step, lds + 2 * C::F::BYTES, u, valid);
     };
@@ -554,7 +565,7 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
     // prologue: blocks 0 .. PST-2 in flight, block 0 landed; initial state copy published
 #pragma unroll
     for (int b = 0; b < C::PST - 1; ++b) fetch(b, b);
-    publish_state<D, DV, DV>(st, smem + C::P_SB, k);
+    if constexpr (!SO) publish_state<D, DV, DV>(st, smem + C::P_SB, k);
     wait_dma<(C::PST - 2) * kLoads>();
     __syncthreads();
 
@@ -571,7 +582,7 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
         const char* tb = smem + stage * C::PSTAGE + C::F::BYTES;
         state_update<D, DV, DV>(st, tb, tb + C::F::BYTES, k);
         if (more) {
-            publish_state<D, DV, DV>(st, smem + C::P_SB + ((blk + 1) & 1) * C::SBYTES, k);
+            if constexpr (!SO) publish_state<D, DV, DV>(st, smem + C::P_SB + ((blk + 1) & 1) * C::SBYTES, k);
             wait_dma<(C::PST - 2) * kLoads>();       // block blk+1 has landed (this wave's part)
             __syncthreads();
         }
@@ -590,17 +601,29 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
     }
 }
 
-template <int D, int DV, bool GATED>
+template <int D, int DV, int MODE>
 __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int wg, char* smem, unsigned lds0,
                                           int wave, int lane) {
-    int chain, within;
-    map_workgroup(wg, pb.count * nsplit, pb.chains, chain, within);
+    constexpr bool GATED = MODE == kGated;
+    // (chain, segment) pairs are dealt to workgroups like chains; with one segment per
+    // chain the pair index is the chain index
+    int vchain, within;
+    map_workgroup(wg, pb.count * nsplit, pb.chains * pb.segs, vchain, within);
+    const int chain = vchain / pb.segs;
+    const int seg = vchain - chain * pb.segs;
+    if (MODE == kStateOnly && seg + 1 == pb.segs && !pb.need_last) return;   // nobody consumes this end state
     const int pi = within / nsplit;
     const int split = within - pi * nsplit;
     const PassArgs P = pb.p[pi];
 
+    // the segment's tokens [seg_start, seg_start + n) of the pass's (possibly reversed) token
+    // axis are rows [row0, row0 + n) of the tensors
+    const long long seg_start = (long long)seg * pb.seg_len;
+    const long long n = (pb.segs > 1 && pb.N - seg_start > pb.seg_len) ? pb.seg_len : pb.N - seg_start;
+    const long long row0 = P.rev ? (pb.N - seg_start - n) : seg_start;
+
     Chain ch;
-    const size_t chain_off = (size_t)chain * (size_t)pb.N * D * 2;
+    const size_t chain_off = ((size_t)chain * (size_t)pb.N + (size_t)row0) * D * 2;
     const size_t col_off = (size_t)split * DV * 2;
     ch.a = (const char*)P.a + chain_off;
     ch.b = (const char*)P.b + chain_off;
@@ -609,20 +632,20 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
     ch.gate = GATED ? (const char*)P.gate + chain_off : nullptr;
     ch.y = GATED ? (char*)P.gated_out + chain_off : nullptr;
     ch.eps = P.eps;
-    ch.state_in = P.state_in ? P.state_in + (size_t)chain * D * D + (size_t)split * DV : nullptr;
-    ch.state_out = P.state_out ? P.state_out + (size_t)chain * D * D + (size_t)split * DV : nullptr;
-    ch.N = pb.N;
-    ch.T = (int)((pb.N + kBlock - 1) / kBlock);
-    ch.last_valid = (int)(pb.N - (long long)(ch.T - 1) * kBlock);
+    ch.state_in = P.state_in ? P.state_in + (size_t)vchain * D * D + (size_t)split * DV : nullptr;
+    ch.state_out = P.state_out ? P.state_out + (size_t)vchain * D * D + (size_t)split * DV : nullptr;
+    ch.N = n;
+    ch.T = (int)((n + kBlock - 1) / kBlock);
+    ch.last_valid = (int)(n - (long long)(ch.T - 1) * kBlock);
     ch.rev = P.rev;
     ch.lam = pb.decay[chain % pb.H];
 
     switch (wave) {
-        case 0: pass_output_wave<D, DV, 0, GATED>(ch, smem, lane); break;
-        case 1: pass_output_wave<D, DV, 1, GATED>(ch, smem, lane); break;
-        case 2: pass_output_wave<D, DV, 2, GATED>(ch, smem, lane); break;
-        case 3: pass_output_wave<D, DV, 3, GATED>(ch, smem, lane); break;
-        default: pass_state_wave<D, DV>(ch, smem, lds0, lane, wave - 4); break;
+        case 0: pass_output_wave<D, DV, 0, MODE>(ch, smem, lane); break;
+        case 1: pass_output_wave<D, DV, 1, MODE>(ch, smem, lane); break;
+        case 2: pass_output_wave<D, DV, 2, MODE>(ch, smem, lane); break;
+        case 3: pass_output_wave<D, DV, 3, MODE>(ch, smem, lane); break;
+        default: pass_state_wave<D, DV, MODE>(ch, smem, lds0, lane, wave - 4); break;
     }
 }
 
@@ -632,21 +655,21 @@ __device__ __forceinline__ unsigned lds_address(const char* p) {
     return (unsigned)(size_t)(const __attribute__((address_space(3))) char*)p;
 }
 
-template <int D, int DV, bool GATED>
+template <int D, int DV, int MODE>
 __global__ __launch_bounds__(kThreads)
 void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
     __shared__ __attribute__((aligned(1024))) char smem[Cfg<D, DV>::PASS_TOTAL];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: role dispatch is a uniform branch
-    pass_body<D, DV, GATED>(pb, nsplit, blockIdx.x, smem, lds_address(smem), wave, tid & 63);
+    pass_body<D, DV, MODE>(pb, nsplit, blockIdx.x, smem, lds_address(smem), wave, tid & 63);
 }
 
-template <int D, int DV, bool GATED = false>
+template <int D, int DV, int MODE = kPlain>
 hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
     const int nsplit = D / DV;
-    const long long wgs = (long long)pb.chains * pb.count * nsplit;
-    if (wgs <= 0 || wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((pass_bf16_kernel<D, DV, GATED>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
+    const long long wgs = (long long)pb.chains * pb.segs * pb.count * nsplit;
+    if (wgs <= 0 || wgs > 0x7fffffffLL || pb.segs < 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((pass_bf16_kernel<D, DV, MODE>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
     return hipGetLastError();
 }
 
@@ -654,9 +677,15 @@ hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
 
 hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream) {
     if (pb.p[0].gate) {                    // gated epilogue: one pass, complete output rows
-        if (pb.count != 1 || dv != D || !pb.p[0].gated_out) return hipErrorInvalidValue;
-        if (D == 128) return launch_t<128, 128, true>(pb, stream);
-        if (D == 64) return launch_t<64, 64, true>(pb, stream);
+        if (pb.count != 1 || dv != D || !pb.p[0].gated_out || pb.state_only) return hipErrorInvalidValue;
+        if (D == 128) return launch_t<128, 128, kGated>(pb, stream);
+        if (D == 64) return launch_t<64, 64, kGated>(pb, stream);
+        return hipErrorInvalidValue;
+    }
+    if (pb.state_only) {                   // segment end states only (sequence-parallel form)
+        if (D == 128 && dv == 128) return launch_t<128, 128, kStateOnly>(pb, stream);
+        if (D == 128 && dv == 64) return launch_t<128, 64, kStateOnly>(pb, stream);
+        if (D == 64 && dv == 64) return launch_t<64, 64, kStateOnly>(pb, stream);
         return hipErrorInvalidValue;
     }
     if (D == 128 && dv == 128) return launch_t<128, 128>(pb, stream);

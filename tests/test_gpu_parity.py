@@ -370,3 +370,79 @@ def test_decode_config5_sampled():
     for (b, h) in picks:
         sl = (slice(b, b + 1), slice(h, h + 1))
         check(f"kv[{b},{h}]", kv[sl], ref_state[(b, h)], 1e-2)
+
+
+# --------------------------------------------------------------------------- sequence-parallel form
+
+
+class force_segs:
+    """Debug override of the number of sequence segments per chain."""
+
+    def __init__(self, segs):
+        self.segs = segs
+
+    def __enter__(self):
+        self.old = os.environ.get("LTN_ATTN_SEGS")
+        os.environ["LTN_ATTN_SEGS"] = str(self.segs)
+
+    def __exit__(self, *a):
+        os.environ.pop("LTN_ATTN_SEGS", None)
+        if self.old is not None:
+            os.environ["LTN_ATTN_SEGS"] = self.old
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("N,segs", [(130, 2), (517, 3), (1000, 5), (640, 10)])
+def test_bf16_segmented_forward_backward(D, N, segs):
+    """Chains cut into segments (end states from zero, scan, per-segment pass) give the same
+    O, final state and gradients as the definition; initial state included."""
+    Bt, H = 1, 3
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 600 + N)
+    g = synth.make_do(Bt, H, N, D, torch.bfloat16, 600 + N)
+    kv0 = torch.randn(Bt, H, D, D, generator=torch.Generator().manual_seed(N)) * 0.1
+    decay = decays(H)["mix"]
+    ref, kv_ref = orc.fwd_recurrent(q, k, v, decay, kv_in=kv0, return_state=True)
+    refs = orc.bwd_recurrent(q, k, v, g, decay)
+    with force_segs(segs):
+        assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 0) > 0
+        o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), kv_in=kv0.to(dev()), return_state=True)
+        o2 = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), kv_in=kv0.to(dev()))      # final state not requested
+        outs = ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay))
+    check("O", o, ref, 1e-2)
+    check("kv", kv, kv_ref, 1e-2)
+    assert torch.equal(o2, o)
+    for n, x, r in zip(("dQ", "dK", "dV"), outs, refs):
+        check(n, x, r, 1e-2)
+
+
+def test_bf16_segmented_by_default_for_few_long_chains():
+    Bt, H, N, D = 1, 2, 8192 + 77, 128
+    assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 0) > 0
+    assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 1) > 0
+    assert ltn.ltn_attn_workspace_bytes(4, 32, 8192, D, 0, torch.bfloat16, 1) == 0    # headline shape: whole chains
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 91)
+    g = synth.make_do(Bt, H, N, D, torch.bfloat16, 91)
+    decay = synth.decay_bench_rule(H)
+    o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), return_state=True)
+    ref, kv_ref = orc.fwd_recurrent(q, k, v, decay, return_state=True)
+    check("O", o, ref, 1e-2)
+    check("kv", kv, kv_ref, 1e-2)
+    for n, x, r in zip(("dQ", "dK", "dV"), ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay)),
+                       orc.bwd_recurrent(q, k, v, g, decay)):
+        check(n, x, r, 1e-2)
+
+
+def test_segmented_call_needs_its_workspace():
+    Bt, H, N, D = 1, 2, 8192, 128
+    q, k, v = gpu(*synth.make_qkv(Bt, H, N, D, torch.bfloat16, 93))
+    dd, = gpu(synth.decay_bench_rule(H))
+    o = torch.empty_like(q)
+    lib = ltn.load_library()
+    import ctypes
+    need = ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 0)
+    assert need == 8 * Bt * H * D * D * 4               # 8192 tokens: eight segments of 1024
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    rc = lib.ltn_attn_fwd(p(q), p(k), p(v), p(o), p(dd), None, None, Bt, H, N, D, 0, 1, None, 0, None)
+    assert rc == 2, ltn.ltn_status_str(rc)               # LTN_ERR_SHAPE: workspace too small
+    rc = lib.ltn_attn_fwd(p(q), p(k), p(v), p(o), p(dd), None, None, Bt, H, N, D, 0, 1, None, need, None)
+    assert rc == 1, ltn.ltn_status_str(rc)               # LTN_ERR_NULL: bytes needed, no pointer
