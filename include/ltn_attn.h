@@ -153,6 +153,21 @@ ltn_status ltn_attn_decode_step(const void* q, const void* k, const void* v, voi
                                 float* kv, const float* decay,
                                 int Bt, int H, int D, ltn_dtype dtype, void* stream);
 
+/*
+ * S consecutive decode steps in one call (Algorithm 2, S loop iterations): the state is
+ * read once, kept on chip over the S tokens and written once, for callers that hold
+ * several tokens per sequence (a short prompt tail, drafted tokens).
+ *     for s = 0..S-1:  kv <- lambda_h kv + k_s^T v_s,   o_s = q_s kv
+ *
+ *   q, k, v in : device, [Bt,H,S,D] dtype     o out: device, [Bt,H,S,D] dtype
+ *   kv  in/out : device, [Bt,H,D,D] fp32      S == 0 is a successful no-op
+ * All arithmetic is fp32 whatever `dtype` is (unlike ltn_attn_fwd with kv_in/kv_out, which
+ * computes the same thing blockwise with bf16 MFMA for bf16 tensors).
+ */
+ltn_status ltn_attn_decode_steps(const void* q, const void* k, const void* v, void* o,
+                                 float* kv, const float* decay,
+                                 int Bt, int H, int S, int D, ltn_dtype dtype, void* stream);
+
 /* Block length the library uses for (D, dtype) when `block` is 0; 0 if unsupported. */
 int ltn_attn_pick_block(int D, ltn_dtype dtype);
 

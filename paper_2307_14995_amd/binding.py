@@ -18,7 +18,7 @@ _lib = None
 LTN_F32, LTN_BF16 = 0, 1
 SYMBOLS = (
     "ltn_attn_fwd", "ltn_attn_fwd_gated", "ltn_gate_fwd", "ltn_gate_bwd",
-    "ltn_attn_bwd", "ltn_attn_decode_step", "ltn_attn_pick_block",
+    "ltn_attn_bwd", "ltn_attn_decode_step", "ltn_attn_decode_steps", "ltn_attn_pick_block",
     "ltn_attn_workspace_bytes", "ltn_attn_check_decay", "ltn_status_str",
 )
 
@@ -58,6 +58,8 @@ def load_library():
     lib.ltn_attn_bwd.restype = ci
     lib.ltn_attn_decode_step.argtypes = [vp, vp, vp, vp, fp, fp, ci, ci, ci, ci, vp]
     lib.ltn_attn_decode_step.restype = ci
+    lib.ltn_attn_decode_steps.argtypes = [vp, vp, vp, vp, fp, fp, ci, ci, ci, ci, ci, vp]
+    lib.ltn_attn_decode_steps.restype = ci
     lib.ltn_attn_pick_block.argtypes = [ci, ci]
     lib.ltn_attn_pick_block.restype = ci
     lib.ltn_attn_workspace_bytes.argtypes = [ci, ci, cl, ci, ci, ci, ci]
@@ -265,4 +267,25 @@ def ltn_attn_decode_step(q, k, v, kv, decay, out=None):
                                       Bt, H, D, _dtype_code(q.dtype), _stream(q.device))
     if rc != 0:
         raise LtnError(rc, "ltn_attn_decode_step")
+    return o
+
+
+def ltn_attn_decode_steps(q, k, v, kv, decay, out=None):
+    """S decode steps in one call: q, k, v: [Bt,H,S,D]; kv: fp32 [Bt,H,D,D] updated in place; returns o."""
+    lib = load_library()
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (kv, "kv"), (decay, "decay")):
+        _dev(t, n)
+    if not (q.shape == k.shape == v.shape) or q.dim() != 4 or not (q.dtype == k.dtype == v.dtype):
+        raise ValueError("q, k, v must be [Bt,H,S,D] tensors of one shape and dtype")
+    Bt, H, S, D = q.shape
+    if kv.dtype != torch.float32 or tuple(kv.shape) != (Bt, H, D, D):
+        raise ValueError("kv must be fp32 [Bt,H,D,D]")
+    if decay.dtype != torch.float32 or decay.numel() != H:
+        raise ValueError("decay must be fp32 [H]")
+    o = torch.empty_like(q) if out is None else _dev(out, "out")
+    with torch.cuda.device(q.device):
+        rc = lib.ltn_attn_decode_steps(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(kv), _ptr(decay),
+                                       Bt, H, S, D, _dtype_code(q.dtype), _stream(q.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_decode_steps")
     return o

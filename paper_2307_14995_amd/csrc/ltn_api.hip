@@ -304,25 +304,32 @@ ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void*
     return run_passes(pb, D, blk, dtype, workspace, st);
 }
 
-ltn_status ltn_attn_decode_step(const void* q, const void* k, const void* v, void* o,
-                                float* kv, const float* decay,
-                                int Bt, int H, int D, ltn_dtype dtype, void* stream) {
-    if (!q || !k || !v || !o || !kv || !decay) return LTN_ERR_NULL;
-    if (Bt < 0 || H < 0 || D <= 0) return LTN_ERR_SHAPE;
+ltn_status ltn_attn_decode_steps(const void* q, const void* k, const void* v, void* o,
+                                 float* kv, const float* decay,
+                                 int Bt, int H, int S, int D, ltn_dtype dtype, void* stream) {
+    const bool empty = (Bt == 0 || H == 0 || S == 0);   // no token is read, the state is not touched
+    if (!decay || (!empty && (!q || !k || !v || !o || !kv))) return LTN_ERR_NULL;
+    if (Bt < 0 || H < 0 || S < 0 || D <= 0) return LTN_ERR_SHAPE;
     if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
     if (D != 64 && D != 128) return LTN_ERR_UNSUPPORTED;
     if ((long long)Bt * H > 0x3fffffffLL) return LTN_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(kv) ||
         (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
-    if (o == q || o == k || o == v || (const void*)kv == q || (const void*)kv == k ||
-        (const void*)kv == v || (const void*)kv == o)
+    if (!empty && (o == q || o == k || o == v || (const void*)kv == q || (const void*)kv == k ||
+                   (const void*)kv == v || (const void*)kv == o))
         return LTN_ERR_UNSUPPORTED;
     const int chains = Bt * H;
-    if (chains == 0) return LTN_OK;
-    const hipError_t e = ltn::launch_decode(q, k, v, o, kv, decay, chains, H, D, dtype == LTN_BF16,
+    if (empty) return LTN_OK;
+    const hipError_t e = ltn::launch_decode(q, k, v, o, kv, decay, chains, H, S, D, dtype == LTN_BF16,
                                             static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+}
+
+ltn_status ltn_attn_decode_step(const void* q, const void* k, const void* v, void* o,
+                                float* kv, const float* decay,
+                                int Bt, int H, int D, ltn_dtype dtype, void* stream) {
+    return ltn_attn_decode_steps(q, k, v, o, kv, decay, Bt, H, 1, D, dtype, stream);
 }
 
 }  // extern "C"

@@ -1,11 +1,12 @@
-// One recurrent decode step of Lightning Attention (arXiv 2307.14995, Sec. 3.3,
-// Algorithm 2, one loop iteration), per (batch, head):
-//     kv <- lambda kv + k^T v   (fp32, in place),   o = q kv   (the updated state)
-// The step reads and writes the D x D fp32 state exactly once: it is bound by HBM
-// bandwidth (about half a FLOP per byte), so the kernel is plain fp32 vector code
-// with 16-byte accesses; one 256-thread workgroup per chain, each thread owns four
-// adjacent state columns of a strided set of rows, and the D partial dot products
-// per column are reduced through LDS.
+// Recurrent decode of Lightning Attention (arXiv 2307.14995, Sec. 3.3, Algorithm 2), per
+// (batch, head), for S >= 1 consecutive tokens in one call:
+//     kv <- lambda kv + k_s^T v_s   (fp32),   o_s = q_s kv   (the updated state),  s = 0..S-1
+// The state is read once, kept in registers over the S iterations and written once, so a
+// call moves 2 D^2 fp32 values per chain whatever S is; with S = 1 (one token per call) the
+// step is bound by HBM bandwidth (about half a FLOP per byte).  Plain fp32 vector code with
+// 16-byte accesses; one 256-thread workgroup per chain, each thread owns four adjacent state
+// columns of a strided set of rows, and the D partial dot products per column are reduced
+// through LDS.
 #include "ltn_kernels.h"
 
 namespace ltn {
@@ -27,7 +28,8 @@ __device__ __forceinline__ unsigned short f32_to_bf16_bits(float f) {   // round
 template <int D, bool BF16>
 __global__ __launch_bounds__(kThreads)
 void decode_kernel(const void* __restrict__ q, const void* __restrict__ k, const void* __restrict__ v,
-                   void* __restrict__ o, float* __restrict__ kv, const float* __restrict__ decay, int H) {
+                   void* __restrict__ o, float* __restrict__ kv, const float* __restrict__ decay, int H,
+                   int steps) {
     constexpr int TX = D / 4;             // threads across one state row (float4 each)
     constexpr int TY = kThreads / TX;     // rows in flight per sweep
     constexpr int IT = D / TY;            // sweeps
@@ -37,66 +39,69 @@ void decode_kernel(const void* __restrict__ q, const void* __restrict__ k, const
     const int chain = blockIdx.x;
     const int tid = threadIdx.x;
     const float lam = decay[chain % H];
-    if (tid < D) {
-        const size_t e = (size_t)chain * D + tid;
-        if (BF16) {
-            qs[tid] = bf16_bits_to_f32(((const unsigned short*)q)[e]);
-            ks[tid] = bf16_bits_to_f32(((const unsigned short*)k)[e]);
-            vs[tid] = bf16_bits_to_f32(((const unsigned short*)v)[e]);
-        } else {
-            qs[tid] = ((const float*)q)[e];
-            ks[tid] = ((const float*)k)[e];
-            vs[tid] = ((const float*)v)[e];
-        }
-    }
-    __syncthreads();
-
     const int tx = tid % TX, ty = tid / TX;
     float4* S = (float4*)(kv + (size_t)chain * D * D);
-    const float4 vv = *(const float4*)(&vs[4 * tx]);
-    float4 acc = {0.f, 0.f, 0.f, 0.f};
     float4 s[IT];
 #pragma unroll
     for (int it = 0; it < IT; ++it) s[it] = S[(size_t)(ty + TY * it) * TX + tx];
+
+    for (int step = 0; step < steps; ++step) {
+        if (tid < D) {
+            const size_t e = ((size_t)chain * steps + step) * D + tid;
+            if (BF16) {
+                qs[tid] = bf16_bits_to_f32(((const unsigned short*)q)[e]);
+                ks[tid] = bf16_bits_to_f32(((const unsigned short*)k)[e]);
+                vs[tid] = bf16_bits_to_f32(((const unsigned short*)v)[e]);
+            } else {
+                qs[tid] = ((const float*)q)[e];
+                ks[tid] = ((const float*)k)[e];
+                vs[tid] = ((const float*)v)[e];
+            }
+        }
+        __syncthreads();
+        const float4 vv = *(const float4*)(&vs[4 * tx]);
+        float4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int it = 0; it < IT; ++it) {
-        const int i = ty + TY * it;
-        const float ki = ks[i], qi = qs[i];
-        float4 n;
-        n.x = fmaf(lam, s[it].x, ki * vv.x);
-        n.y = fmaf(lam, s[it].y, ki * vv.y);
-        n.z = fmaf(lam, s[it].z, ki * vv.z);
-        n.w = fmaf(lam, s[it].w, ki * vv.w);
-        S[(size_t)i * TX + tx] = n;
-        acc.x = fmaf(qi, n.x, acc.x);
-        acc.y = fmaf(qi, n.y, acc.y);
-        acc.z = fmaf(qi, n.z, acc.z);
-        acc.w = fmaf(qi, n.w, acc.w);
-    }
-    part[ty][tx] = acc;
-    __syncthreads();
-    if (tid < D) {
-        const int cx = tid / 4, comp = tid % 4;
-        float sum = 0.f;
+        for (int it = 0; it < IT; ++it) {
+            const int i = ty + TY * it;
+            const float ki = ks[i], qi = qs[i];
+            s[it].x = fmaf(lam, s[it].x, ki * vv.x);
+            s[it].y = fmaf(lam, s[it].y, ki * vv.y);
+            s[it].z = fmaf(lam, s[it].z, ki * vv.z);
+            s[it].w = fmaf(lam, s[it].w, ki * vv.w);
+            acc.x = fmaf(qi, s[it].x, acc.x);
+            acc.y = fmaf(qi, s[it].y, acc.y);
+            acc.z = fmaf(qi, s[it].z, acc.z);
+            acc.w = fmaf(qi, s[it].w, acc.w);
+        }
+        part[ty][tx] = acc;
+        __syncthreads();                  // also: everyone is done with qs/ks/vs of this step
+        if (tid < D) {
+            const int cx = tid / 4, comp = tid % 4;
+            float sum = 0.f;
 #pragma unroll
-        for (int y = 0; y < TY; ++y) sum += ((const float*)&part[y][cx])[comp];
-        const size_t e = (size_t)chain * D + tid;
-        if (BF16) ((unsigned short*)o)[e] = f32_to_bf16_bits(sum);
-        else ((float*)o)[e] = sum;
+            for (int y = 0; y < TY; ++y) sum += ((const float*)&part[y][cx])[comp];
+            const size_t e = ((size_t)chain * steps + step) * D + tid;
+            if (BF16) ((unsigned short*)o)[e] = f32_to_bf16_bits(sum);
+            else ((float*)o)[e] = sum;
+        }
+        // the next step's first barrier separates these reads of `part` from its next writes
     }
+#pragma unroll
+    for (int it = 0; it < IT; ++it) S[(size_t)(ty + TY * it) * TX + tx] = s[it];
 }
 
 }  // namespace
 
 hipError_t launch_decode(const void* q, const void* k, const void* v, void* o, float* kv,
-                         const float* decay, int chains, int H, int D, int is_bf16,
+                         const float* decay, int chains, int H, int steps, int D, int is_bf16,
                          hipStream_t stream) {
-    if (chains <= 0) return hipSuccess;
+    if (chains <= 0 || steps <= 0) return hipSuccess;
     const dim3 grid((unsigned)chains), block(kThreads);
-    if (D == 128 && is_bf16) hipLaunchKernelGGL((decode_kernel<128, true>), grid, block, 0, stream, q, k, v, o, kv, decay, H);
-    else if (D == 128) hipLaunchKernelGGL((decode_kernel<128, false>), grid, block, 0, stream, q, k, v, o, kv, decay, H);
-    else if (D == 64 && is_bf16) hipLaunchKernelGGL((decode_kernel<64, true>), grid, block, 0, stream, q, k, v, o, kv, decay, H);
-    else if (D == 64) hipLaunchKernelGGL((decode_kernel<64, false>), grid, block, 0, stream, q, k, v, o, kv, decay, H);
+    if (D == 128 && is_bf16) hipLaunchKernelGGL((decode_kernel<128, true>), grid, block, 0, stream, q, k, v, o, kv, decay, H, steps);
+    else if (D == 128) hipLaunchKernelGGL((decode_kernel<128, false>), grid, block, 0, stream, q, k, v, o, kv, decay, H, steps);
+    else if (D == 64 && is_bf16) hipLaunchKernelGGL((decode_kernel<64, true>), grid, block, 0, stream, q, k, v, o, kv, decay, H, steps);
+    else if (D == 64) hipLaunchKernelGGL((decode_kernel<64, false>), grid, block, 0, stream, q, k, v, o, kv, decay, H, steps);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -62,9 +62,10 @@ hipError_t launch_segment_scan(float* states, const float* kv_in, float* kv_out,
                                int D, hipStream_t stream);
 // kv[c] (or zeros if null) -> kv_out[c], n floats.
 hipError_t launch_state_copy(const float* kv_in, float* kv_out, size_t n, hipStream_t stream);
-// One decode step, see ltn_attn_decode_step.
+// `steps` consecutive decode steps per chain (q, k, v, o: [chains, steps, D]), see
+// ltn_attn_decode_steps.
 hipError_t launch_decode(const void* q, const void* k, const void* v, void* o, float* kv,
-                         const float* decay, int chains, int H, int D, int is_bf16,
+                         const float* decay, int chains, int H, int steps, int D, int is_bf16,
                          hipStream_t stream);
 
 // Gated SimpleRMSNorm on `rows` rows of D features (see ltn_gate.hip).  is_bwd = 0:

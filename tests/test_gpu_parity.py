@@ -207,6 +207,36 @@ def test_decode_steps_continue_prefix(dtype, D):
     check("kv", kv, kv_ref, tol)
 
 
+@pytest.mark.parametrize("dtype,D", [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 128), (torch.float32, 64)])
+@pytest.mark.parametrize("S", [1, 5, 17])
+def test_decode_several_tokens_per_call(dtype, D, S):
+    """S iterations of Algorithm 2 in one call: rows of a forward that continues the state,
+    and bit for bit what S single-token calls give."""
+    Bt, H = 2, 5
+    decay = decays(H)["mix"]
+    g = torch.Generator().manual_seed(77 + S)
+    kv0 = torch.randn(Bt, H, D, D, generator=g) * 0.2
+    q, k, v = synth.make_qkv(Bt, H, S, D, dtype, 63 + S)
+    dd, = gpu(decay)
+    kv = kv0.to(dev())
+    o = ltn.ltn_attn_decode_steps(*gpu(q, k, v), kv, dd)
+    o_ref, kv_ref = orc.fwd_recurrent(q, k, v, decay, kv_in=kv0, return_state=True)
+    tol = TOL[dtype]
+    check("o", o, o_ref, tol, per_slice=(S >= 5))
+    check("kv", kv, kv_ref, tol)
+    kv1 = kv0.to(dev())
+    qd, kd, vd = gpu(q, k, v)
+    for s_ in range(S):
+        o1 = ltn.ltn_attn_decode_step(qd[:, :, s_].contiguous(), kd[:, :, s_].contiguous(),
+                                      vd[:, :, s_].contiguous(), kv1, dd)
+        assert torch.equal(o1, o[:, :, s_])
+    assert torch.equal(kv1, kv)
+    # S = 0: nothing happens
+    empty = qd[:, :, :0].contiguous()
+    assert ltn.ltn_attn_decode_steps(empty, empty, empty, kv1, dd).shape == (Bt, H, 0, D)
+    assert torch.equal(kv1, kv)
+
+
 def test_decode_time_does_not_depend_on_position():
     """Sec. 4 / Fig. 4: per-token cost of the recurrent form is constant in sequence position."""
     Bt, H, D = 16, 32, 128
