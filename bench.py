@@ -50,8 +50,10 @@ def algorithmic_bytes_per_token_head(D: int, esize: int):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    # defaults: the first ~100 steps after an idle GPU run 4-8 % slower (clocks ramp up); 100 warm-up
+    # and 400 timed steps are about 0.4 s of GPU time
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="cfg3_7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", action="store_true")
