@@ -41,6 +41,11 @@
 //   * wave role and strip are compile-time constants of the code each wave runs, so
 //     causal tile skipping costs no branches inside a block.
 // Only non-negative powers of lambda are formed.
+//
+// Two variations of the same workgroup: the gated epilogue (full-width slices: the token
+// mixer's y = SRMSNorm(o) (.) u of Eq. 3 applied to the fp32 output rows before they are
+// stored) and the state-only sweep of the sequence-parallel form (a chain cut into
+// segments: only the state waves work, and only the segment's end state is written).
 #include "ltn_kernels.h"
 
 namespace ltn {

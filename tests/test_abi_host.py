@@ -125,6 +125,69 @@ def test_decode_argument_errors(lib):
     assert call(Bt=0) == OK
 
 
+def test_decode_steps_argument_errors(lib):
+    f = lib.ltn_attn_decode_steps
+
+    def call(q=P, k=P + 0x1000, v=P + 0x2000, o=P + 0x3000, kv=P + 0x10000, decay=P + 0x4000,
+             Bt=2, H=2, S=4, D=128, dtype=1):
+        return f(q, k, v, o, kv, decay, Bt, H, S, D, dtype, None)
+
+    assert call(kv=None) == E_NULL
+    assert call(S=-1) == E_SHAPE
+    assert call(D=96) == E_UNSUP
+    assert call(q=P + 2) == E_ALIGN
+    assert call(o=P + 0x2000) == E_UNSUP                   # o aliases v
+    assert call(S=0) == OK
+    assert call(S=0, q=None, k=None, v=None, o=None) == OK # nothing to read: pointers may be NULL
+
+
+def test_fwd_gated_argument_errors(lib):
+    f = lib.ltn_attn_fwd_gated
+    cf = ctypes.c_float
+
+    def call(q=P, k=P + 0x1000, v=P + 0x2000, u=P + 0x3000, o=P + 0x5000, y=P + 0x6000, decay=P + 0x4000,
+             kv_in=None, kv_out=None, eps=1e-6, Bt=1, H=2, N=256, D=64, block=0, dtype=1):
+        return f(q, k, v, u, o, y, decay, kv_in, kv_out, cf(eps), Bt, H, N, D, block, dtype, None, 0, None)
+
+    assert call(u=None) == E_NULL
+    assert call(y=None) == E_NULL
+    assert call(eps=-1.0) == E_SHAPE
+    assert call(eps=float("nan")) == E_SHAPE
+    assert call(D=96) == E_UNSUP
+    assert call(y=P + 0x3000) == E_UNSUP                   # y aliases the gate
+    assert call(y=P + 0x5000) == E_UNSUP                   # y aliases o
+    assert call(u=P + 0x3008) == E_ALIGN
+    assert call(N=0) == OK
+    assert call(Bt=0, q=None, k=None, v=None, u=None, o=None, y=None) == OK
+
+
+def test_gate_argument_errors(lib):
+    cf = ctypes.c_float
+    fw, bw = lib.ltn_gate_fwd, lib.ltn_gate_bwd
+    assert fw(None, P + 0x1000, P + 0x2000, cf(0.0), 16, 128, 1, None) == E_NULL
+    assert fw(P, P + 0x1000, P + 0x2000, cf(0.0), -1, 128, 1, None) == E_SHAPE
+    assert fw(P, P + 0x1000, P + 0x2000, cf(-0.5), 16, 128, 1, None) == E_SHAPE
+    assert fw(P, P + 0x1000, P + 0x2000, cf(0.0), 16, 96, 1, None) == E_UNSUP
+    assert fw(P, P + 0x1000, P + 0x2000, cf(0.0), 16, 128, 5, None) == E_UNSUP
+    assert fw(P, P + 0x1000, P, cf(0.0), 16, 128, 1, None) == E_UNSUP              # y aliases x
+    assert fw(P, P + 0x1004, P + 0x2000, cf(0.0), 16, 128, 1, None) == E_ALIGN
+    assert fw(None, None, None, cf(0.0), 0, 128, 1, None) == OK                     # no rows
+    assert bw(P, P + 0x1000, None, P + 0x3000, P + 0x4000, cf(0.0), 16, 128, 1, None) == E_NULL
+    assert bw(P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x3000, cf(0.0), 16, 128, 1, None) == E_UNSUP  # d_x aliases d_u
+    assert bw(P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x4000, cf(0.0), 16, 64, 7, None) == E_UNSUP
+
+
+def test_workspace_query(lib):
+    import torch
+    D = 128
+    # few long chains: one fp32 state per (pass, chain, segment); 8 segments of 1024 tokens here
+    assert ltn.ltn_attn_workspace_bytes(1, 2, 8192, D, 0, torch.bfloat16, 0) == 1 * 2 * 8 * D * D * 4
+    assert ltn.ltn_attn_workspace_bytes(1, 2, 8192, D, 0, torch.bfloat16, 1) == 3 * 2 * 8 * D * D * 4
+    assert ltn.ltn_attn_workspace_bytes(1, 2, 8192, D, 0, torch.float32, 0) == 0     # bf16 kernels only
+    assert ltn.ltn_attn_workspace_bytes(1, 32, 4096, D, 0, torch.bfloat16, 0) == 0   # segments would be too short
+    assert ltn.ltn_attn_workspace_bytes(0, 2, 8192, D, 0, torch.bfloat16, 0) == 0
+
+
 def test_binding_rejects_cpu_tensors():
     import torch
     x = torch.zeros(1, 1, 4, 64)
