@@ -476,3 +476,40 @@ def test_segmented_call_needs_its_workspace():
     assert rc == 2, ltn.ltn_status_str(rc)               # LTN_ERR_SHAPE: workspace too small
     rc = lib.ltn_attn_fwd(p(q), p(k), p(v), p(o), p(dd), None, None, Bt, H, N, D, 0, 1, None, need, None)
     assert rc == 1, ltn.ltn_status_str(rc)               # LTN_ERR_NULL: bytes needed, no pointer
+
+
+# --------------------------------------------------------------------------- seeded sweep of odd shapes
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        D = int(rng.choice([64, 128]))
+        Bt, H = int(rng.integers(1, 4)), int(rng.integers(1, 10))
+        N = int(rng.choice([rng.integers(1, 64), rng.integers(64, 400), rng.integers(400, 1500)]))
+        dv = int(rng.choice([D, D // 2] + ([D // 4] if D == 128 else [])))
+        segs = int(rng.choice([1, 1, 2, 3, 7]))
+        cases.append((i, Bt, H, N, D, dv, segs))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(16, 2024), ids=lambda c: "B%dH%dN%dD%ddv%dseg%d" % c[1:])
+def test_bf16_seeded_shape_sweep(case):
+    """Forward (with an initial state, returning the final one) and backward on seeded odd
+    shapes, value-column split and segment count forced, against the oracle."""
+    i, Bt, H, N, D, dv, segs = case
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 700 + i)
+    g = synth.make_do(Bt, H, N, D, torch.bfloat16, 700 + i)
+    kv0 = torch.randn(Bt, H, D, D, generator=torch.Generator().manual_seed(i)) * 0.1
+    decay = torch.rand(H, generator=torch.Generator().manual_seed(1000 + i))
+    decay[0] = 1.0
+    ref, kv_ref = orc.fwd_recurrent(q, k, v, decay, kv_in=kv0, return_state=True)
+    refs = orc.bwd_recurrent(q, k, v, g, decay)
+    with force_dv(dv), force_segs(segs):
+        o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), kv_in=kv0.to(dev()), return_state=True)
+        outs = ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay))
+    check("O", o, ref, 1e-2)
+    check("kv", kv, kv_ref, 1e-2)
+    for n, x, r in zip(("dQ", "dK", "dV"), outs, refs):
+        check(n, x, r, 1e-2)
