@@ -257,6 +257,23 @@ def extended_report(ltn, synth, torch, dev):
                           "fused_training_GBs": round(6 * unit / (t_trn * 1e-3) / 1e9, 1)}),
               file=sys.stderr, flush=True)
         del q, k, v, u, g, o, y, dx, du
+    # the paper's quadratic tiling (App. B Algorithm 3) against the state recurrence, forward only
+    Bt, H = 4, 32
+    dd = synth.decay_bench_rule(H).to(dev)
+    for N in (128, 256, 512, 1024, 2048, 4096, 8192):
+        q, k, v = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
+                   for _ in range(3))
+        o = torch.empty_like(q)
+        t_rec = time_call(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o), n=20, warm=5)
+        t_til = time_call(lambda: ltn.ltn_attn_fwd_tiled(q, k, v, dd, out=o), n=5 if N >= 4096 else 20, warm=2)
+        T = N // 64
+        tile_pairs = Bt * H * T * (T + 1) // 2
+        print(json.dumps({"workload": "tiled_vs_recurrence", "Bt": Bt, "H": H, "N": N,
+                          "recurrence_ms": round(t_rec, 4), "tiled_ms": round(t_til, 4),
+                          "tiled_over_recurrence": round(t_til / t_rec, 2),
+                          "tiled_TFLOPs_full_tiles": round(tile_pairs * 4 * 64 * 64 * D / (t_til * 1e-3) / 1e12, 1)}),
+              file=sys.stderr, flush=True)
+        del q, k, v, o
     c = synth.DECODE
     Bt, H = c["Bt"], c["H"]
     kv = torch.zeros(Bt, H, D, D, device=dev)

@@ -128,6 +128,18 @@ ltn_status ltn_gate_bwd(const void* x, const void* u, const void* d_y, void* d_x
                         long long rows, int D, ltn_dtype dtype, void* stream);
 
 /*
+ * The same forward output by the paper's own evaluation order (App. B, Algorithm 3): every
+ * block of 64 queries loops over all key/value blocks up to its own, with the decay mask
+ * tile generated on chip.  Quadratic in N; kept as a comparison kernel (where on the N axis
+ * it loses to the state recurrence of ltn_attn_fwd is part of the report), zero initial
+ * state, no state output, bf16 only (LTN_ERR_UNSUPPORTED otherwise).
+ *
+ *   q, k, v in : device, [Bt,H,N,D] bf16      o out: device, [Bt,H,N,D] bf16
+ */
+ltn_status ltn_attn_fwd_tiled(const void* q, const void* k, const void* v, void* o, const float* decay,
+                              int Bt, int H, long long N, int D, ltn_dtype dtype, void* stream);
+
+/*
  * Backward pass: gradients of the definition above (App. B Algorithm 4 read
  * with its misprints corrected: dK = dA^T Q, dQ accumulates dA K).  With
  * A = (Q K^T)(.)M and dA = (dO V^T)(.)M:  dQ = dA K, dK = dA^T Q, dV = A^T dO.

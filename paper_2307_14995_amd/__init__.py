@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     ltn_attn_decode_steps,
     ltn_attn_fwd,
     ltn_attn_fwd_gated,
+    ltn_attn_fwd_tiled,
     ltn_gate_bwd,
     ltn_gate_fwd,
     ltn_attn_pick_block,
@@ -20,7 +21,7 @@ from .binding import (  # noqa: F401
 )
 
 __all__ = [
-    "LtnError", "library_path", "load_library", "ltn_attn_fwd", "ltn_attn_fwd_gated", "ltn_gate_fwd", "ltn_gate_bwd", "ltn_attn_bwd",
+    "LtnError", "library_path", "load_library", "ltn_attn_fwd", "ltn_attn_fwd_gated", "ltn_attn_fwd_tiled", "ltn_gate_fwd", "ltn_gate_bwd", "ltn_attn_bwd",
     "ltn_attn_decode_step", "ltn_attn_decode_steps", "ltn_attn_pick_block", "ltn_attn_workspace_bytes",
     "ltn_attn_check_decay", "ltn_status_str",
 ]

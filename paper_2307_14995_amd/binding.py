@@ -17,7 +17,7 @@ _lib = None
 
 LTN_F32, LTN_BF16 = 0, 1
 SYMBOLS = (
-    "ltn_attn_fwd", "ltn_attn_fwd_gated", "ltn_gate_fwd", "ltn_gate_bwd",
+    "ltn_attn_fwd", "ltn_attn_fwd_gated", "ltn_attn_fwd_tiled", "ltn_gate_fwd", "ltn_gate_bwd",
     "ltn_attn_bwd", "ltn_attn_decode_step", "ltn_attn_decode_steps", "ltn_attn_pick_block",
     "ltn_attn_workspace_bytes", "ltn_attn_check_decay", "ltn_status_str",
 )
@@ -50,6 +50,8 @@ def load_library():
     cf = ctypes.c_float
     lib.ltn_attn_fwd_gated.argtypes = [vp, vp, vp, vp, vp, vp, fp, fp, fp, cf, ci, ci, cl, ci, ci, ci, vp, sz, vp]
     lib.ltn_attn_fwd_gated.restype = ci
+    lib.ltn_attn_fwd_tiled.argtypes = [vp, vp, vp, vp, fp, ci, ci, cl, ci, ci, vp]
+    lib.ltn_attn_fwd_tiled.restype = ci
     lib.ltn_gate_fwd.argtypes = [vp, vp, vp, cf, cl, ci, ci, vp]
     lib.ltn_gate_fwd.restype = ci
     lib.ltn_gate_bwd.argtypes = [vp, vp, vp, vp, vp, cf, cl, ci, ci, vp]
@@ -288,4 +290,23 @@ def ltn_attn_decode_steps(q, k, v, kv, decay, out=None):
                                        Bt, H, S, D, _dtype_code(q.dtype), _stream(q.device))
     if rc != 0:
         raise LtnError(rc, "ltn_attn_decode_steps")
+    return o
+
+
+def ltn_attn_fwd_tiled(q, k, v, decay, out=None):
+    """The forward output by the quadratic tile loop of App. B Algorithm 3 (comparison kernel, bf16)."""
+    lib = load_library()
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (decay, "decay")):
+        _dev(t, n)
+    if q.shape != k.shape or q.shape != v.shape or q.dim() != 4 or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must be [Bt,H,N,D] tensors of one shape and dtype")
+    Bt, H, N, D = q.shape
+    if decay.dtype != torch.float32 or decay.numel() != H:
+        raise ValueError("decay must be fp32 [H]")
+    o = torch.empty_like(q) if out is None else _dev(out, "out")
+    with torch.cuda.device(q.device):
+        rc = lib.ltn_attn_fwd_tiled(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(decay), Bt, H, N, D,
+                                    _dtype_code(q.dtype), _stream(q.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_fwd_tiled")
     return o

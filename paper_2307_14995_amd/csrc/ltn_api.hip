@@ -236,6 +236,22 @@ ltn_status ltn_attn_fwd_gated(const void* q, const void* k, const void* v, const
                       workspace, workspace_bytes, stream, true);
 }
 
+ltn_status ltn_attn_fwd_tiled(const void* q, const void* k, const void* v, void* o, const float* decay,
+                              int Bt, int H, long long N, int D, ltn_dtype dtype, void* stream) {
+    const bool empty = (Bt == 0 || H == 0 || N == 0);
+    if (!decay || (!empty && (!q || !k || !v || !o))) return LTN_ERR_NULL;
+    if (Bt < 0 || H < 0 || N < 0 || D <= 0) return LTN_ERR_SHAPE;
+    if (dtype != LTN_BF16 || (D != 64 && D != 128)) return LTN_ERR_UNSUPPORTED;
+    if ((long long)Bt * H > 0x3fffffffLL) return LTN_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) ||
+        (reinterpret_cast<uintptr_t>(decay) & 3u))
+        return LTN_ERR_ALIGN;
+    if (!empty && (o == q || o == k || o == v)) return LTN_ERR_UNSUPPORTED;
+    if (empty) return LTN_OK;
+    return ltn::launch_tiled_fwd_bf16(q, k, v, o, decay, Bt * H, H, N, D, static_cast<hipStream_t>(stream)) ==
+                   hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+}
+
 static ltn_status gate_common(const void* x, const void* u, const void* d_y, void* o0, void* o1, float eps,
                               long long rows, int D, ltn_dtype dtype, void* stream, bool bwd) {
     if (rows < 0 || D <= 0) return LTN_ERR_SHAPE;

@@ -51,6 +51,10 @@ struct PassBatch {
 // bf16 MFMA kernel, block length 64.  D in {64,128}; dv = value columns per workgroup
 // (D, D/2 or, for D = 128, D/4).
 hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream);
+// Forward by the quadratic tiling of App. B Algorithm 3 (comparison kernel), bf16, zero
+// initial state, D in {64,128}.
+hipError_t launch_tiled_fwd_bf16(const void* q, const void* k, const void* v, void* o, const float* decay,
+                                 int chains, int H, long long N, int D, hipStream_t stream);
 // fp32 kernel.  D in {64,128}, block in {16,32,64}, D*block <= 4096.
 hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStream_t stream);
 // Turns the segment-local end states L[pass][chain][g] in `states` (as written by a

@@ -161,6 +161,21 @@ def test_fwd_gated_argument_errors(lib):
     assert call(Bt=0, q=None, k=None, v=None, u=None, o=None, y=None) == OK
 
 
+def test_fwd_tiled_argument_errors(lib):
+    f = lib.ltn_attn_fwd_tiled
+
+    def call(q=P, k=P + 0x1000, v=P + 0x2000, o=P + 0x3000, decay=P + 0x4000, Bt=1, H=2, N=256, D=128, dtype=1):
+        return f(q, k, v, o, decay, Bt, H, N, D, dtype, None)
+
+    assert call(o=None) == E_NULL
+    assert call(N=-1) == E_SHAPE
+    assert call(dtype=0) == E_UNSUP                        # bf16 only
+    assert call(D=96) == E_UNSUP
+    assert call(k=P + 0x1002) == E_ALIGN
+    assert call(o=P + 0x1000) == E_UNSUP                   # o aliases k
+    assert call(N=0) == OK
+
+
 def test_gate_argument_errors(lib):
     cf = ctypes.c_float
     fw, bw = lib.ltn_gate_fwd, lib.ltn_gate_bwd

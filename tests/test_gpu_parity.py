@@ -513,3 +513,30 @@ def test_bf16_seeded_shape_sweep(case):
     check("kv", kv, kv_ref, 1e-2)
     for n, x, r in zip(("dQ", "dK", "dV"), outs, refs):
         check(n, x, r, 1e-2)
+
+
+# --------------------------------------------------------------------------- the paper's tiling as a kernel
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("N", [1, 63, 64, 65, 200, 517])
+def test_bf16_tiled_forward(D, N):
+    """App. B Algorithm 3 evaluated on the GPU: the definition's O, by the quadratic tile loop."""
+    Bt, H = 1, 3
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 800 + N)
+    for name, decay in decays(H).items():
+        o = ltn.ltn_attn_fwd_tiled(*gpu(q, k, v, decay))
+        check(f"O[{name}]", o, orc.fwd_quadratic(q, k, v, decay), 1e-2)
+    # the oracle's own Algorithm 3 (64 x 64 tiles) is the same numbers
+    assert orc.rel_l2(orc.fwd_tiled(q, k, v, decays(H)["bench"], 64, 64),
+                      orc.fwd_quadratic(q, k, v, decays(H)["bench"])) < 1e-12
+
+
+def test_bf16_tiled_forward_many_chains_long():
+    Bt, H, N, D = 2, 8, 1500, 128           # 16 chains (XCD-grouped), 24 query blocks each
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 87)
+    decay = synth.decay_bench_rule(H)
+    o = ltn.ltn_attn_fwd_tiled(*gpu(q, k, v, decay))
+    check("O", o, orc.fwd_recurrent(q, k, v, decay), 1e-2)
+    with pytest.raises(ltn.LtnError):
+        ltn.ltn_attn_fwd_tiled(*gpu(q.float(), k.float(), v.float(), decay))     # bf16 only
