@@ -183,16 +183,16 @@ ltn_status ltn_attn_decode_steps(const void* q, const void* k, const void* v, vo
 /* Block length the library uses for (D, dtype) when `block` is 0; 0 if unsupported. */
 int ltn_attn_pick_block(int D, ltn_dtype dtype);
 
-/* Scratch bytes ltn_attn_fwd / ltn_attn_fwd_gated (is_bwd = 0) or ltn_attn_bwd
- * (is_bwd = 1) needs for these arguments.  A smaller workspace makes the call fail
- * with LTN_ERR_SHAPE; a NULL one with LTN_ERR_NULL when bytes are needed.  It is 0
- * except when few chains meet a long sequence: then every chain is cut into segments
- * that run in parallel (the recurrence of Sec. 3.3 is linear in the state, so the
- * segments' end states can be computed from zero and combined by a scan), and the
- * workspace holds one fp32 D x D state per (pass, chain, segment).  Contents are
- * scratch: undefined before and after the call. */
+/* Scratch bytes a call needs for these arguments: call = 0 for ltn_attn_fwd, 1 for
+ * ltn_attn_bwd, 2 for ltn_attn_fwd_gated.  A smaller workspace makes the call fail with
+ * LTN_ERR_SHAPE; a NULL one with LTN_ERR_NULL when bytes are needed.  It is 0 except
+ * when few chains meet a long sequence: then every chain is cut into segments that run
+ * in parallel (the recurrence of Sec. 3.3 is linear in the state, so the segments' end
+ * states can be computed from zero and combined by a scan), and the workspace holds one
+ * fp32 D x D state per (pass, chain, segment).  Contents are scratch: undefined before
+ * and after the call. */
 size_t ltn_attn_workspace_bytes(int Bt, int H, long long N, int D, int block,
-                                ltn_dtype dtype, int is_bwd);
+                                ltn_dtype dtype, int call);
 
 /* Host-side validation of a HOST copy of the decay array: LTN_OK if every value
  * is in [0, 1], LTN_ERR_DECAY otherwise (Eq. 2 gives values in (0, 1]; the last

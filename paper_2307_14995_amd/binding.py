@@ -82,8 +82,9 @@ def ltn_attn_pick_block(D: int, dtype: torch.dtype) -> int:
     return int(load_library().ltn_attn_pick_block(int(D), _dtype_code(dtype)))
 
 
-def ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, is_bwd) -> int:
-    return int(load_library().ltn_attn_workspace_bytes(Bt, H, N, D, block, _dtype_code(dtype), int(is_bwd)))
+def ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, call) -> int:
+    """call: 0 = ltn_attn_fwd, 1 = ltn_attn_bwd, 2 = ltn_attn_fwd_gated."""
+    return int(load_library().ltn_attn_workspace_bytes(Bt, H, N, D, block, _dtype_code(dtype), int(call)))
 
 
 def ltn_attn_check_decay(decay) -> int:
@@ -171,7 +172,7 @@ def ltn_attn_fwd_gated(q, k, v, u, decay, eps=0.0, kv_in=None, return_state=Fals
     if kv_out is None and return_state:
         kv_out = torch.empty((Bt, H, D, D), dtype=torch.float32, device=q.device)
     code = _dtype_code(q.dtype)
-    ws_bytes = int(lib.ltn_attn_workspace_bytes(Bt, H, N, D, block, code, 0))
+    ws_bytes = int(lib.ltn_attn_workspace_bytes(Bt, H, N, D, block, code, 2))
     ws = _workspace(ws_bytes, q.device)
     with torch.cuda.device(q.device):
         rc = lib.ltn_attn_fwd_gated(_ptr(q), _ptr(k), _ptr(v), _ptr(u), _ptr(o), _ptr(y), _ptr(decay),

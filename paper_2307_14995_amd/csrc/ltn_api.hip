@@ -54,13 +54,15 @@ ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype 
 // units, and never otherwise.  bf16 kernels only.
 // LTN_ATTN_SEGS (debug, used by the parity tests) forces a segment count.
 struct SegPlan { int segs; long long seg_len; };
+constexpr long long kMinSegsFullWidth = 4;   // measured: 2 segments lose to one workgroup per chain
 
-SegPlan pick_segments(long long chain_passes, long long N, ltn_dtype dtype) {
+SegPlan pick_segments(long long chain_passes, long long N, ltn_dtype dtype, bool full_width = false) {
     SegPlan plan = {1, 0};
     if (dtype != LTN_BF16 || chain_passes <= 0 || N <= 64) return plan;
     long long want = 256 / chain_passes;
     if (want > N / 1024) want = N / 1024;
-    if (want < 8) want = 1;
+    // a pass that must keep full-width slices has no column split to fall back on
+    if (want < (full_width ? kMinSegsFullWidth : 8)) want = 1;
     if (const char* e = std::getenv("LTN_ATTN_SEGS")) {
         const long long v = std::atoll(e);
         if (v >= 1 && v <= 4096) want = v;
@@ -75,12 +77,15 @@ SegPlan pick_segments(long long chain_passes, long long N, ltn_dtype dtype) {
     return plan;
 }
 
-ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void* workspace, hipStream_t stream) {
+// full_width: the pass carries the gated epilogue, which needs complete output rows in one
+// workgroup (slices of all D value columns).
+ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void* workspace, hipStream_t stream,
+                      bool full_width = false) {
     const long long chain_passes = (long long)pb.chains * pb.count;
-    const SegPlan plan = pick_segments(chain_passes, pb.N, dtype);
+    const SegPlan plan = pick_segments(chain_passes, pb.N, dtype, full_width);
     pb.segs = 1;
     if (plan.segs == 1) {
-        const int dv = pick_dv(chain_passes, D, dtype);
+        const int dv = full_width ? D : pick_dv(chain_passes, D, dtype);
         const hipError_t e = (dtype == LTN_BF16) ? ltn::launch_pass_bf16(pb, D, dv, stream)
                                                  : ltn::launch_pass_f32(pb, D, dv, blk, stream);
         return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
@@ -98,6 +103,8 @@ ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void*
     sweep.need_last = kv_out != nullptr;
     for (int i = 0; i < pb.count; ++i) {
         sweep.p[i].out = nullptr;
+        sweep.p[i].gate = nullptr;
+        sweep.p[i].gated_out = nullptr;
         sweep.p[i].state_in = nullptr;
         sweep.p[i].state_out = states + i * per_pass;
     }
@@ -112,7 +119,7 @@ ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void*
         main.p[i].state_in = states + i * per_pass;
         main.p[i].state_out = nullptr;
     }
-    const int dv = pick_dv(chain_passes * plan.segs, D, dtype);
+    const int dv = full_width ? D : pick_dv(chain_passes * plan.segs, D, dtype);
     return ltn::launch_pass_bf16(main, D, dv, stream) == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
 }
 
@@ -127,12 +134,12 @@ int ltn_attn_pick_block(int D, ltn_dtype dtype) {
     return 0;
 }
 
-size_t ltn_attn_workspace_bytes(int Bt, int H, long long N, int D, int block, ltn_dtype dtype, int is_bwd) {
+size_t ltn_attn_workspace_bytes(int Bt, int H, long long N, int D, int block, ltn_dtype dtype, int call) {
     (void)block;
-    if (Bt <= 0 || H <= 0 || N <= 0 || (D != 64 && D != 128)) return 0;
+    if (Bt <= 0 || H <= 0 || N <= 0 || (D != 64 && D != 128) || call < 0 || call > 2) return 0;
     const long long chains = (long long)Bt * H;
-    const int count = is_bwd ? 3 : 1;
-    const SegPlan plan = pick_segments(chains * count, N, dtype);
+    const int count = (call == 1) ? 3 : 1;
+    const SegPlan plan = pick_segments(chains * count, N, dtype, call == 2);
     if (plan.segs == 1) return 0;
     return (size_t)count * (size_t)chains * (size_t)plan.segs * D * D * sizeof(float);   // one fp32 state per segment
 }
@@ -169,7 +176,7 @@ static ltn_status fwd_common(const void* q, const void* k, const void* v, const 
     const ltn_status cs = check_common(Bt, H, N, D, block, dtype, &blk);
     if (cs != LTN_OK) return cs;
     if (gated && !(eps >= 0.0f)) return LTN_ERR_SHAPE;
-    if (workspace_bytes < ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, 0)) return LTN_ERR_SHAPE;
+    if (workspace_bytes < ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, gated ? 2 : 0)) return LTN_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(u) || !aligned16(y) ||
         !aligned16(kv_in) || !aligned16(kv_out) || !aligned16(workspace) ||
         (reinterpret_cast<uintptr_t>(decay) & 3u))
@@ -202,11 +209,12 @@ static ltn_status fwd_common(const void* q, const void* k, const void* v, const 
     pb.N = N;
     pb.p[0] = ltn::PassArgs{q, k, v, o, kv_in, kv_out, 0, gated ? u : nullptr, gated ? y : nullptr, eps};
     if (!gated) return run_passes(pb, D, blk, dtype, workspace, st);
-    // The fused epilogue needs complete output rows in one workgroup, i.e. full-width
-    // slices and one workgroup per chain.  With few chains that leaves compute units idle;
-    // when the caller wants the attention output stored anyway (training), the plain
-    // forward at its usual split followed by the gate kernel on the stored output is then
-    // the faster way to the same result (measured on MI355X: below about 192 chains).
+    // The fused epilogue needs complete output rows in one workgroup, i.e. full-width slices
+    // (one workgroup per chain, or per chain segment).  With few chains that can leave
+    // compute units idle; when the caller wants the attention output stored anyway
+    // (training), the plain forward at its usual split followed by the gate kernel on the
+    // stored output is then the faster way to the same result (measured on MI355X: below
+    // about 192 chains).
     if (o && dtype == LTN_BF16 && chains < 192) {
         pb.p[0].gate = nullptr;
         pb.p[0].gated_out = nullptr;
@@ -215,9 +223,7 @@ static ltn_status fwd_common(const void* q, const void* k, const void* v, const 
         return ltn::launch_gate(o, u, nullptr, y, nullptr, eps, chains * N, D, 1, 0, st) == hipSuccess
                    ? LTN_OK : LTN_ERR_LAUNCH;
     }
-    const hipError_t e = (dtype == LTN_BF16) ? ltn::launch_pass_bf16(pb, D, D, st)
-                                             : ltn::launch_pass_f32(pb, D, D, blk, st);
-    return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+    return run_passes(pb, D, blk, dtype, workspace, st, true);
 }
 
 ltn_status ltn_attn_fwd(const void* q, const void* k, const void* v, void* o,

@@ -201,6 +201,10 @@ def test_workspace_query(lib):
     assert ltn.ltn_attn_workspace_bytes(1, 2, 8192, D, 0, torch.float32, 0) == 0     # bf16 kernels only
     assert ltn.ltn_attn_workspace_bytes(1, 32, 4096, D, 0, torch.bfloat16, 0) == 0   # segments would be too short
     assert ltn.ltn_attn_workspace_bytes(0, 2, 8192, D, 0, torch.bfloat16, 0) == 0
+    # the gated forward keeps full-width slices, so it cuts chains sooner (from 4 segments on)
+    assert ltn.ltn_attn_workspace_bytes(1, 32, 4096, D, 0, torch.bfloat16, 2) == 32 * 4 * D * D * 4
+    assert ltn.ltn_attn_workspace_bytes(4, 32, 8192, D, 0, torch.bfloat16, 2) == 0
+    assert ltn.ltn_attn_workspace_bytes(1, 2, 8192, D, 0, torch.bfloat16, 3) == 0     # no such call
 
 
 def test_binding_rejects_cpu_tensors():

@@ -139,6 +139,39 @@ def test_bf16_forward_gated_many_chains_fused_with_o():
     assert torch.equal(y2, y)                # same kernel, same bits
 
 
+@pytest.mark.parametrize("segs,N", [(3, 517), (5, 1000)])
+def test_bf16_forward_gated_segmented(segs, N, monkeypatch):
+    """The fused epilogue on chains cut into segments (forced), with an initial state."""
+    monkeypatch.setenv("LTN_ATTN_SEGS", str(segs))
+    Bt, H, D = 1, 3, 128
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 460 + N)
+    u = synth.make_gate(Bt, H, N, D, torch.bfloat16, 460 + N)
+    kv0 = torch.randn(Bt, H, D, D, generator=torch.Generator().manual_seed(N)) * 0.1
+    decay = mixed_decay(H)
+    assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 2) > 0
+    o_ref, y_ref = orc.fwd_gated(q, k, v, u, decay, eps=1e-6, kv_in=kv0)
+    _, kv_ref = orc.fwd_recurrent(q, k, v, decay, kv_in=kv0, return_state=True)
+    _, y, kv = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6, kv_in=kv0.to(dev()),
+                                      return_state=True, store_o=False)
+    check("Y", y, y_ref, 1e-2)
+    check("kv", kv, kv_ref, 1e-2)
+
+
+def test_bf16_forward_gated_few_long_chains_by_default():
+    Bt, H, N, D = 1, 4, 4096 + 50, 128       # 4 chains: cut 4 ways by the library's own rule
+    assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 2) == 4 * Bt * H * D * D * 4
+    assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 0) == 0
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 49)
+    u = synth.make_gate(Bt, H, N, D, torch.bfloat16, 49)
+    decay = synth.decay_bench_rule(H)
+    o_ref, y_ref = orc.fwd_gated(q, k, v, u, decay, eps=1e-6)
+    o, y = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6)      # training form: plain forward + gate kernel
+    _, y2 = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6, store_o=False)   # fused, segmented
+    check("O", o, o_ref, 1e-2)
+    check("Y", y, y_ref, 1e-2)
+    check("Y (fused)", y2, y_ref, 1e-2)
+
+
 def test_training_chain_through_the_gate():
     """fwd_gated (stores O) -> gate_bwd -> attn_bwd equals the oracle's chain rule."""
     Bt, H, N, D = 2, 3, 160, 128
