@@ -188,7 +188,16 @@ def cpu_baseline(w, q, k, v, d_o, decay):
     orc.bwd_recurrent(qs, ks, vs, gs, ds)
     dt = time.perf_counter() - t0
     token_heads = bs * hs * w.N
+    # one chain on one thread, scaled to the layer: the per-core figure
+    orc.set_num_threads(1)
+    one = (slice(0, 1), slice(0, 1))
+    t1 = time.perf_counter()
+    orc.fwd_recurrent(q[one], k[one], v[one], decay[:1])
+    orc.bwd_recurrent(q[one], k[one], v[one], d_o[one], decay[:1])
+    dt1 = time.perf_counter() - t1
+    orc.set_num_threads(cores)
     return {
+        "single_thread_value": round(w.N / dt1 / w.H, 1),
         "value": round(token_heads / dt / w.H, 1),
         "unit": "tokens/s",
         "cores": cores,
@@ -202,6 +211,7 @@ def cpu_baseline(w, q, k, v, d_o, decay):
 def extended_report(ltn, synth, torch, dev):
     """Other workloads (not the bench line): printed to stderr as JSON lines."""
     def time_call(fn, n=10, warm=3):
+        """Mean ms per call over n back-to-back calls (HIP events on the launch stream)."""
         for _ in range(warm):
             fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -212,9 +222,37 @@ def extended_report(ltn, synth, torch, dev):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
+    def time_stats(fn, n=20, warm=5):
+        """(median, min) ms per call, one event pair per call."""
+        for _ in range(warm):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        for i in range(n):
+            ev[i].record()
+            fn()
+        ev[n].record()
+        torch.cuda.synchronize()
+        ts = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))
+        return ts[n // 2], ts[0]
+
+    # what this machine gives: a plain 1 GiB device copy and a large bf16 GEMM (library calls, only
+    # to put the published peaks of 8 TB/s and 2.5 PFLOP/s into perspective)
+    src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    t_copy = time_call(lambda: dst.copy_(src), n=10, warm=3)
+    del src, dst
+    a = torch.randn(8192, 8192, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    b = torch.randn(8192, 8192, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    t_gemm = time_call(lambda: torch.matmul(a, b), n=10, warm=3)
+    del a, b
+    print(json.dumps({"workload": "machine", "copy_1GiB_GBs": round(2 * (1 << 30) / (t_copy * 1e-3) / 1e9, 1),
+                      "bf16_gemm_8192_TFLOPs": round(2 * 8192 ** 3 / (t_gemm * 1e-3) / 1e12, 1)}),
+          file=sys.stderr, flush=True)
+
     shapes = [("cfg2_385m", 8, 8, 2048), ("cfg_1b", 8, 16, 2048), ("cfg3_7b", 4, 32, 8192)]
     shapes += [(f"long_N{n}", 1, 32, n) for n in synth.LONG_CONTEXT_N]
     D = 128
+    long_times = []
     for name, Bt, H, N in shapes:
         q, k, v = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
                    for _ in range(3))
@@ -222,16 +260,49 @@ def extended_report(ltn, synth, torch, dev):
         dd = synth.decay_bench_rule(H).to(dev)
         o = torch.empty_like(q)
         gr = tuple(torch.empty_like(q) for _ in range(3))
-        f = time_call(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o))
-        b = time_call(lambda: ltn.ltn_attn_bwd(q, k, v, g, dd, out=gr))
+        f, fmin = time_stats(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o))
+        b, bmin = time_stats(lambda: ltn.ltn_attn_bwd(q, k, v, g, dd, out=gr))
         th = Bt * H * N
-        print(json.dumps({"workload": name, "Bt": Bt, "H": H, "N": N, "fwd_ms": round(f, 4), "bwd_ms": round(b, 4),
-                          "tokens_per_s": round(Bt * N / ((f + b) * 1e-3), 1),
-                          "fwd_GBs": round(4 * D * 2 * th / (f * 1e-3) / 1e9, 1),
-                          "bwd_GBs": round(7 * D * 2 * th / (b * 1e-3) / 1e9, 1),
-                          "F_alg_TFLOPs": round((14 * D * D + 7 * 65 * D) * th / ((f + b) * 1e-3) / 1e12, 1)}),
-              file=sys.stderr, flush=True)
+        line = {"workload": name, "Bt": Bt, "H": H, "N": N, "fwd_ms": round(f, 4), "bwd_ms": round(b, 4),
+                "fwd_min_ms": round(fmin, 4), "bwd_min_ms": round(bmin, 4),
+                "tokens_per_s": round(Bt * N / ((f + b) * 1e-3), 1),
+                "fwd_GBs": round(4 * D * 2 * th / (f * 1e-3) / 1e9, 1),
+                "bwd_GBs": round(7 * D * 2 * th / (b * 1e-3) / 1e9, 1),
+                "F_alg_TFLOPs": round((14 * D * D + 7 * 65 * D) * th / ((f + b) * 1e-3) / 1e12, 1)}
+        if name == "cfg2_385m":
+            # its 8 tensors (268 MB) about fit the 256 MB memory-side cache: also time it cold, rotating
+            # through 8 sets of buffers so that no call finds its operands cached
+            sets = [tuple(torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).to(torch.bfloat16)
+                          for _ in range(8)) for _ in range(8)]
+            it = [0]
+
+            def cold_fwd():
+                x = sets[it[0] % 8]; it[0] += 1
+                ltn.ltn_attn_fwd(x[0], x[1], x[2], dd, out=x[4])
+
+            def cold_bwd():
+                x = sets[it[0] % 8]; it[0] += 1
+                ltn.ltn_attn_bwd(x[0], x[1], x[2], x[3], dd, out=(x[5], x[6], x[7]))
+            line["fwd_cold_ms"] = round(time_stats(cold_fwd, n=24, warm=8)[0], 4)
+            line["bwd_cold_ms"] = round(time_stats(cold_bwd, n=24, warm=8)[0], 4)
+            del sets
+        print(json.dumps(line), file=sys.stderr, flush=True)
+        if name.startswith("long_"):
+            long_times.append((N, f + b))
         del q, k, v, g, o, gr
+    # time linear in N (long context): log-log slope and doubling ratios of fwd+bwd
+    import math
+    xs = [math.log(n) for n, _ in long_times]
+    ys = [math.log(t) for _, t in long_times]
+    mx, my = sum(xs) / len(xs), sum(ys) / len(ys)
+    slope = sum((x - mx) * (y - my) for x, y in zip(xs, ys)) / sum((x - mx) ** 2 for x in xs)
+    big = [(n, t) for n, t in long_times if n >= 8192]
+    slope_big = math.log(big[-1][1] / big[0][1]) / math.log(big[-1][0] / big[0][0])
+    print(json.dumps({"workload": "long_context_linearity", "loglog_slope_all_N": round(slope, 3),
+                      "loglog_slope_N_ge_8192": round(slope_big, 3),
+                      "doubling_ratios": {str(b_[0]): round(b_[1] / a_[1], 3)
+                                          for a_, b_ in zip(long_times, long_times[1:])}}),
+          file=sys.stderr, flush=True)
     # token mixer epilogue (gated SimpleRMSNorm): fused into the forward vs. forward + gate kernel
     for name, Bt, H, N in (("cfg3_7b", 4, 32, 8192), ("256chains", 8, 32, 4096)):
         q, k, v = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
@@ -276,9 +347,11 @@ def extended_report(ltn, synth, torch, dev):
         del q, k, v, o
     c = synth.DECODE
     Bt, H = c["Bt"], c["H"]
-    kv = torch.zeros(Bt, H, D, D, device=dev)
-    q1, k1, v1 = (torch.randn(Bt, H, D, device=dev).to(torch.bfloat16) for _ in range(3))
     dd = synth.decay_bench_rule(H).to(dev)
+    qp, kp, vp = (torch.randn(Bt, H, c["prefix"], D, device=dev).div_(D ** 0.5).to(torch.bfloat16) for _ in range(3))
+    _, kv = ltn.ltn_attn_fwd(qp, kp, vp, dd, return_state=True)      # state after a 1024-token prefix
+    del qp, kp, vp
+    q1, k1, v1 = (torch.randn(Bt, H, D, device=dev).div_(D ** 0.5).to(torch.bfloat16) for _ in range(3))
     o1 = torch.empty_like(q1)
     t = time_call(lambda: ltn.ltn_attn_decode_step(q1, k1, v1, kv, dd, out=o1), n=512, warm=20)
     print(json.dumps({"workload": "decode_cfg5", "Bt": Bt, "H": H, "us_per_step": round(t * 1e3, 2),

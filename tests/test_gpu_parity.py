@@ -540,3 +540,33 @@ def test_bf16_tiled_forward_many_chains_long():
     check("O", o, orc.fwd_recurrent(q, k, v, decay), 1e-2)
     with pytest.raises(ltn.LtnError):
         ltn.ltn_attn_fwd_tiled(*gpu(q.float(), k.float(), v.float(), decay))     # bf16 only
+
+
+# --------------------------------------------------------------------------- cost linear in N
+
+
+def test_time_is_linear_in_sequence_length():
+    """Long-context workload (Bt=1, H=32, D=128): forward + backward time doubles with N."""
+    import statistics
+    H, D = 32, 128
+    decay = synth.decay_bench_rule(H).to(dev())
+    times = {}
+    for N in (16384, 32768, 65536):
+        q, k, v, g = (torch.randn(1, H, N, D, device=dev()).mul_(0.1).to(torch.bfloat16) for _ in range(4))
+        o = torch.empty_like(q)
+        gr = tuple(torch.empty_like(q) for _ in range(3))
+
+        def step():
+            ltn.ltn_attn_fwd(q, k, v, decay, out=o)
+            ltn.ltn_attn_bwd(q, k, v, g, decay, out=gr)
+        for _ in range(10):
+            step()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(21)]
+        for i in range(20):
+            ev[i].record()
+            step()
+        ev[20].record()
+        torch.cuda.synchronize()
+        times[N] = statistics.median(ev[i].elapsed_time(ev[i + 1]) for i in range(20))
+    assert 1.8 < times[32768] / times[16384] < 2.2, times
+    assert 1.8 < times[65536] / times[32768] < 2.2, times
