@@ -6,15 +6,20 @@
 //   S_i+1 = lambda^len S_i + sum_c lambda^(len-1-c) b_c^T c_c
 //
 // (arXiv 2307.14995, Sec. 3.2.1 / Eq. 1; Sec. 3.3 Algorithm 2 in block form.)
-// One 256-thread workgroup per (chain, value-column slice); tiles and the fp32
-// state live in LDS.  This path exists for fp32 callers and the fp32 parity
-// configuration; the throughput path is the bf16 kernel.
+// One 256-thread workgroup per (chain, value-column slice).  Tiles live in LDS; every
+// product is register-tiled (a thread owns a small rectangle of the result and walks the
+// contraction with 16-byte LDS reads), the state rectangle of a thread stays in its
+// registers for the whole sequence and is mirrored to LDS once per block for the
+// A_i S_i product.  This path exists for fp32 callers and the fp32 parity configuration;
+// the throughput path is the bf16 kernel.
 #include "ltn_kernels.h"
 
 namespace ltn {
 namespace {
 
 constexpr int kThreads = 256;
+
+__device__ __forceinline__ float4 ld4(const float* p) { return *(const float4*)p; }
 
 // GATED (full-width slices, one pass): the block's output rows are complete, so the token
 // mixer's epilogue (Sec. 3.1.2 Eq. 3 with the SimpleRMSNorm of Sec. 3.1.3 per head),
@@ -23,15 +28,16 @@ template <int D, int DV, int B, bool GATED>
 __global__ __launch_bounds__(kThreads)
 void pass_f32_kernel(const PassBatch pb, const int nsplit) {
     static_assert(!GATED || DV == D, "the gated epilogue needs complete output rows");
-    constexpr int DP = D + 1;     // padded pitches: conflict-free column walks
+    static_assert(B % 16 == 0 && D % 64 == 0 && DV % 32 == 0 && DV <= D, "tile shapes");
+    constexpr int DP = D + 4;     // row pitch of A and B tiles: 16-byte aligned rows, shifted banks
     constexpr int BP = B + 1;
-    __shared__ float As[B * DP];
-    __shared__ float Bs[B * DP];
-    __shared__ float Cs[B * DV];
+    __shared__ __attribute__((aligned(16))) float As[B * DP];
+    __shared__ __attribute__((aligned(16))) float Bs[B * DP];
+    __shared__ __attribute__((aligned(16))) float Cs[B * DV];
     __shared__ float Ps[B * BP];
-    __shared__ float St[D * DV];
+    __shared__ __attribute__((aligned(16))) float St[D * DV];
     __shared__ float pw[B + 1];   // lambda^0 .. lambda^B
-    __shared__ float Os[GATED ? B * DV : 1];
+    __shared__ __attribute__((aligned(16))) float Os[GATED ? B * DV : 4];
     __shared__ float rstd[GATED ? B : 1];
 
     const int tid = threadIdx.x;
@@ -52,56 +58,135 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
     const float* Up = GATED ? (const float*)P.gate + chain_off : nullptr;
     float* Yp = GATED ? (float*)P.gated_out + chain_off : nullptr;
 
+    // thread rectangles
+    //   scores: rows sy*SR.., columns sx*SR.. of the B x B tile          (16 x 16 threads)
+    //   output: rows oy + OY*m, columns 4*ox..+3 of the B x DV tile      (OY x DV/4 threads)
+    //   state : rows uy*UR.., columns ux*UC.. of the D x DV state        (16 x 16 threads)
+    constexpr int SR = B / 16;
+    const int sy = tid >> 4, sx = tid & 15;
+    constexpr int OX = DV / 4, OY = kThreads / OX, OM = (B + OY - 1) / OY;
+    const int ox = tid % OX, oy = tid / OX;
+    constexpr int UR = D / 16, UC = DV / 16;
+    static_assert(UR % 4 == 0 && UC % 2 == 0, "vector reads of the state rectangle");
+    const int uy = tid >> 4, ux = tid & 15;
+
     for (int n = tid; n <= B; n += kThreads) pw[n] = decay_pow(lam, n);
-    for (int e = tid; e < D * DV; e += kThreads) {
-        const int i = e / DV, j = e % DV;
-        St[e] = P.state_in ? P.state_in[(size_t)chain * D * D + (size_t)i * D + split * DV + j] : 0.0f;
-    }
+    float st[UR][UC];             // this thread's rectangle of the running state
+#pragma unroll
+    for (int a = 0; a < UR; ++a)
+#pragma unroll
+        for (int b = 0; b < UC; ++b) {
+            const int i = uy * UR + a, j = ux * UC + b;
+            st[a][b] = P.state_in ? P.state_in[(size_t)chain * D * D + (size_t)i * D + split * DV + j] : 0.0f;
+            St[i * DV + j] = st[a][b];
+        }
     __syncthreads();
 
     for (long long t0 = 0; t0 < N; t0 += B) {
         const int len = (N - t0 < B) ? (int)(N - t0) : B;
-        // ---- load tiles (rows past the end are zero)
-        for (int e = tid; e < B * D; e += kThreads) {
-            const int r = e / D, i = e % D;
+        // ---- load tiles with 16-byte accesses (rows past the end are zero)
+        for (int e = tid; e < B * (D / 4); e += kThreads) {
+            const int r = e / (D / 4), i4 = e % (D / 4);
             const long long t = t0 + r;
             const size_t gr = (size_t)(rev ? (N - 1 - t) : t);
             const bool ok = r < len;
-            As[r * DP + i] = ok ? Ap[gr * D + i] : 0.0f;
-            Bs[r * DP + i] = ok ? Bp[gr * D + i] : 0.0f;
+            const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+            *(float4*)&As[r * DP + 4 * i4] = ok ? ld4(Ap + gr * D + 4 * i4) : z;
+            *(float4*)&Bs[r * DP + 4 * i4] = ok ? ld4(Bp + gr * D + 4 * i4) : z;
         }
-        for (int e = tid; e < B * DV; e += kThreads) {
-            const int r = e / DV, j = e % DV;
+        for (int e = tid; e < B * (DV / 4); e += kThreads) {
+            const int r = e / (DV / 4), j4 = e % (DV / 4);
             const long long t = t0 + r;
             const size_t gr = (size_t)(rev ? (N - 1 - t) : t);
-            Cs[e] = (r < len) ? Cp[gr * D + j] : 0.0f;
+            *(float4*)&Cs[r * DV + 4 * j4] = (r < len) ? ld4(Cp + gr * D + 4 * j4) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
         __syncthreads();
-        // ---- masked scores
-        for (int e = tid; e < B * B; e += kThreads) {
-            const int r = e / B, c = e % B;
-            float acc = 0.0f;
-            if (c <= r) {
-#pragma unroll 8
-                for (int i = 0; i < D; ++i) acc = fmaf(As[r * DP + i], Bs[c * DP + i], acc);
-                acc *= pw[r - c];
+
+        // ---- masked scores: an SR x SR rectangle per thread, skipped when above the diagonal
+        {
+            const int r0 = sy * SR, c0 = sx * SR;
+            float acc[SR][SR];
+#pragma unroll
+            for (int a = 0; a < SR; ++a)
+#pragma unroll
+                for (int b = 0; b < SR; ++b) acc[a][b] = 0.0f;
+            if (c0 <= r0 + SR - 1) {
+                for (int i = 0; i < D; i += 4) {
+                    float4 av[SR], bv[SR];
+#pragma unroll
+                    for (int a = 0; a < SR; ++a) av[a] = ld4(&As[(r0 + a) * DP + i]);
+#pragma unroll
+                    for (int b = 0; b < SR; ++b) bv[b] = ld4(&Bs[(c0 + b) * DP + i]);
+#pragma unroll
+                    for (int a = 0; a < SR; ++a)
+#pragma unroll
+                        for (int b = 0; b < SR; ++b) {
+                            acc[a][b] = fmaf(av[a].x, bv[b].x, acc[a][b]);
+                            acc[a][b] = fmaf(av[a].y, bv[b].y, acc[a][b]);
+                            acc[a][b] = fmaf(av[a].z, bv[b].z, acc[a][b]);
+                            acc[a][b] = fmaf(av[a].w, bv[b].w, acc[a][b]);
+                        }
+                }
             }
-            Ps[r * BP + c] = acc;
+#pragma unroll
+            for (int a = 0; a < SR; ++a)
+#pragma unroll
+                for (int b = 0; b < SR; ++b) {
+                    const int r = r0 + a, c = c0 + b;
+                    Ps[r * BP + c] = (c <= r) ? acc[a][b] * pw[r - c] : 0.0f;
+                }
         }
         __syncthreads();
-        // ---- outputs
-        for (int e = tid; e < B * DV; e += kThreads) {
-            const int r = e / DV, j = e % DV;
-            float intra = 0.0f, inter = 0.0f;
-            for (int c = 0; c <= r; ++c) intra = fmaf(Ps[r * BP + c], Cs[c * DV + j], intra);
-#pragma unroll 8
-            for (int i = 0; i < D; ++i) inter = fmaf(As[r * DP + i], St[i * DV + j], inter);
-            const float o = fmaf(pw[r + 1], inter, intra);
-            if (GATED) Os[e] = o;
-            if (r < len && Op) {
-                const long long t = t0 + r;
-                const size_t gr = (size_t)(rev ? (N - 1 - t) : t);
-                Op[gr * D + j] = o;
+
+        // ---- outputs: rows oy + OY*m, four value columns per thread
+        {
+            float4 intra[OM], inter[OM];
+#pragma unroll
+            for (int m = 0; m < OM; ++m) {
+                intra[m] = make_float4(0.f, 0.f, 0.f, 0.f);
+                inter[m] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            for (int c = 0; c < len; ++c) {                       // P C (P is zero above the diagonal)
+                const float4 cv = ld4(&Cs[c * DV + 4 * ox]);
+#pragma unroll
+                for (int m = 0; m < OM; ++m) {
+                    const int r = oy + OY * m;
+                    const float p = (r < B) ? Ps[r * BP + c] : 0.0f;
+                    intra[m].x = fmaf(p, cv.x, intra[m].x);
+                    intra[m].y = fmaf(p, cv.y, intra[m].y);
+                    intra[m].z = fmaf(p, cv.z, intra[m].z);
+                    intra[m].w = fmaf(p, cv.w, intra[m].w);
+                }
+            }
+            for (int i = 0; i < D; i += 4) {                      // A S
+                const float4 s0 = ld4(&St[(i + 0) * DV + 4 * ox]);
+                const float4 s1 = ld4(&St[(i + 1) * DV + 4 * ox]);
+                const float4 s2 = ld4(&St[(i + 2) * DV + 4 * ox]);
+                const float4 s3 = ld4(&St[(i + 3) * DV + 4 * ox]);
+#pragma unroll
+                for (int m = 0; m < OM; ++m) {
+                    const int r = oy + OY * m;
+                    const float4 a = (r < B) ? ld4(&As[r * DP + i]) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    inter[m].x = fmaf(a.x, s0.x, fmaf(a.y, s1.x, fmaf(a.z, s2.x, fmaf(a.w, s3.x, inter[m].x))));
+                    inter[m].y = fmaf(a.x, s0.y, fmaf(a.y, s1.y, fmaf(a.z, s2.y, fmaf(a.w, s3.y, inter[m].y))));
+                    inter[m].z = fmaf(a.x, s0.z, fmaf(a.y, s1.z, fmaf(a.z, s2.z, fmaf(a.w, s3.z, inter[m].z))));
+                    inter[m].w = fmaf(a.x, s0.w, fmaf(a.y, s1.w, fmaf(a.z, s2.w, fmaf(a.w, s3.w, inter[m].w))));
+                }
+            }
+#pragma unroll
+            for (int m = 0; m < OM; ++m) {
+                const int r = oy + OY * m;
+                if (r < B) {
+                    const float q = pw[r + 1];
+                    const float4 o = make_float4(fmaf(q, inter[m].x, intra[m].x), fmaf(q, inter[m].y, intra[m].y),
+                                                 fmaf(q, inter[m].z, intra[m].z), fmaf(q, inter[m].w, intra[m].w));
+                    if (GATED) *(float4*)&Os[r * DV + 4 * ox] = o;
+                    if (r < len && Op) {
+                        const long long t = t0 + r;
+                        const size_t gr = (size_t)(rev ? (N - 1 - t) : t);
+                        *(float4*)(Op + gr * D + 4 * ox) = o;
+                    }
+                }
             }
         }
         __syncthreads();
@@ -115,28 +200,59 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
                 rstd[tid] = 1.0f / sqrtf(ss * (1.0f / D) + P.eps);
             }
             __syncthreads();
-            for (int e = tid; e < len * DV; e += kThreads) {
-                const int r = e / DV, j = e % DV;
+            for (int e = tid; e < len * (DV / 4); e += kThreads) {
+                const int r = e / (DV / 4), j4 = e % (DV / 4);
                 const long long t = t0 + r;
                 const size_t gr = (size_t)(rev ? (N - 1 - t) : t);
-                Yp[gr * D + j] = Os[e] * rstd[r] * Up[gr * D + j];
+                const float4 o = ld4(&Os[r * DV + 4 * j4]);
+                const float4 u = ld4(Up + gr * D + 4 * j4);
+                const float s = rstd[r];
+                *(float4*)(Yp + gr * D + 4 * j4) = make_float4(o.x * s * u.x, o.y * s * u.y, o.z * s * u.z, o.w * s * u.w);
             }
         }
-        // ---- state update (each thread owns its state entries: no hazard inside the step)
-        for (int e = tid; e < D * DV; e += kThreads) {
-            const int i = e / DV, j = e % DV;
-            float acc = 0.0f;
-            for (int c = 0; c < len; ++c) acc = fmaf(pw[len - 1 - c] * Bs[c * DP + i], Cs[c * DV + j], acc);
-            St[e] = fmaf(pw[len], St[e], acc);
+
+        // ---- state update on the thread's own rectangle (registers), mirrored to LDS
+        {
+            const float decay_all = pw[len];
+#pragma unroll
+            for (int a = 0; a < UR; ++a)
+#pragma unroll
+                for (int b = 0; b < UC; ++b) st[a][b] *= decay_all;
+            for (int c = 0; c < len; ++c) {
+                const float w = pw[len - 1 - c];
+                float bv[UR], cv[UC];
+#pragma unroll
+                for (int a = 0; a < UR; a += 4) {
+                    const float4 x = ld4(&Bs[c * DP + uy * UR + a]);
+                    bv[a] = x.x * w; bv[a + 1] = x.y * w; bv[a + 2] = x.z * w; bv[a + 3] = x.w * w;
+                }
+#pragma unroll
+                for (int b = 0; b < UC; b += 2) {
+                    const float2 x = *(const float2*)&Cs[c * DV + ux * UC + b];
+                    cv[b] = x.x; cv[b + 1] = x.y;
+                }
+#pragma unroll
+                for (int a = 0; a < UR; ++a)
+#pragma unroll
+                    for (int b = 0; b < UC; ++b) st[a][b] = fmaf(bv[a], cv[b], st[a][b]);
+            }
+            // every thread has read the old LDS copy (outputs above, before the last barrier)
+#pragma unroll
+            for (int a = 0; a < UR; ++a)
+#pragma unroll
+                for (int b = 0; b < UC; ++b) St[(uy * UR + a) * DV + ux * UC + b] = st[a][b];
         }
         __syncthreads();
     }
 
     if (P.state_out) {
-        for (int e = tid; e < D * DV; e += kThreads) {
-            const int i = e / DV, j = e % DV;
-            P.state_out[(size_t)chain * D * D + (size_t)i * D + split * DV + j] = St[e];
-        }
+#pragma unroll
+        for (int a = 0; a < UR; ++a)
+#pragma unroll
+            for (int b = 0; b < UC; ++b) {
+                const int i = uy * UR + a, j = ux * UC + b;
+                P.state_out[(size_t)chain * D * D + (size_t)i * D + split * DV + j] = st[a][b];
+            }
     }
 }
 
