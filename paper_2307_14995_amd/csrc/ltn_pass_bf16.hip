@@ -69,20 +69,38 @@ struct Cfg {
     static_assert(PASS_TOTAL <= 163840, "LDS per workgroup");
 };
 
+// lambda^n for 0 <= n <= 64 without one fp64 powering loop per constant: every lane powers
+// once (lambda^lane, and lambda^64), the rest are cross-lane reads.  Same values as
+// decay_pow(lam, n), bit for bit.  All 64 lanes must call get() together.
+struct DecayTable {
+    float mine, p64;
+    __device__ __forceinline__ void init(float lam, int lane) {
+        mine = decay_pow(lam, lane);
+        p64 = decay_pow(lam, 64);
+    }
+    __device__ __forceinline__ float get(int n) const {
+        const float v = __shfl(mine, n & 63, 64);
+        return n >= 64 ? p64 : v;
+    }
+};
+
 // Per-lane decay constants of an output wave (non-negative exponents only).
 template <int W>
 struct OutConsts {
     float qscale, mdiag[4], moff[4], lam16, lam32;
     __device__ __forceinline__ void init(float lam, int g, int i16) {
-        qscale = decay_pow(lam, 16 * W + i16 + 1);      // lambda^(r+1), r = row in block
+        DecayTable tb;
+        tb.init(lam, 16 * g + i16);
+        qscale = tb.get(16 * W + i16 + 1);               // lambda^(r+1), r = row in block
         const int d0 = i16 - 4 * g;                      // (row - key) in a diagonal tile at j = 0
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            mdiag[j] = (d0 - j >= 0) ? decay_pow(lam, d0 - j) : 0.0f;
-            moff[j] = decay_pow(lam, 16 + d0 - j);       // 16 + d0 - j >= 1
+            const float md = tb.get(d0 - j >= 0 ? d0 - j : 0);
+            mdiag[j] = (d0 - j >= 0) ? md : 0.0f;
+            moff[j] = tb.get(16 + d0 - j);               // 16 + d0 - j >= 1
         }
-        lam16 = decay_pow(lam, 16);
-        lam32 = decay_pow(lam, 32);
+        lam16 = tb.get(16);
+        lam32 = tb.get(32);
     }
 };
 
@@ -258,14 +276,18 @@ struct StateConsts {
     int btr[D / 64];     // transpose read of B^T: token row 4g + s/4, columns dk0 + 16mt + 4(s%4)
     int ctr[DV / 16];    // transpose read of C:   token row 4g + s/4, columns c0 + 16nt + 4(s%4)
     int pub[D / 64];     // 8-byte write into a state copy: row i16, columns dk0 + 16mt + 4g
-    __device__ __forceinline__ void set_block_len(float lam, int len, int g) {
-        lamB = decay_pow(lam, len);
+    __device__ __forceinline__ void set_block_len(float lam, int len, int lane) {   // whole wave together
+        const int g = lane >> 4;
+        DecayTable tb;
+        tb.init(lam, lane);
+        lamB = tb.get(len);
 #pragma unroll
         for (int p = 0; p < 2; ++p)
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int tok = 32 * p + 16 * (j >> 2) + 4 * g + (j & 3);
-                ksc[p][j] = (tok < len) ? decay_pow(lam, len - 1 - tok) : 0.0f;
+                const float v = tb.get(tok < len ? len - 1 - tok : 0);
+                ksc[p][j] = (tok < len) ? v : 0.0f;
             }
     }
     __device__ __forceinline__ void init_offsets(int g, int i16, int dk0, int c0) {
@@ -406,7 +428,7 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
     const int g = lane >> 4, i16 = lane & 15;
     const int dk0 = u * (D / 4);
     StateConsts<D, DV, DV> k;
-    k.set_block_len(ch.lam, kBlock, g);
+    k.set_block_len(ch.lam, kBlock, lane);
     k.init_offsets(g, i16, dk0, 0);
 
     // running state, fp32
@@ -461,7 +483,7 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
         fetch(blk + C::PST - 1, fs);
         if (!more) {
             if (!ch.state_out) break;                // the last update only feeds the returned state
-            if (ch.last_valid != kBlock) k.set_block_len(ch.lam, ch.last_valid, g);
+            if (ch.last_valid != kBlock) k.set_block_len(ch.lam, ch.last_valid, lane);
         }
         const char* tb = smem + stage * C::PSTAGE + C::F::BYTES;
         state_update<D, DV, DV>(st, tb, tb + C::F::BYTES, k);
