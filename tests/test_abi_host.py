@@ -226,3 +226,14 @@ def test_product_path_does_not_import_the_oracle():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2307_14995_amd" not in text and "libltn_attn" not in text, f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU measurement: any other --gpus value exits with a message, before
+    anything touches a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
