@@ -570,3 +570,24 @@ def test_time_is_linear_in_sequence_length():
         times[N] = statistics.median(ev[i].elapsed_time(ev[i + 1]) for i in range(20))
     assert 1.8 < times[32768] / times[16384] < 2.2, times
     assert 1.8 < times[65536] / times[32768] < 2.2, times
+
+
+def test_work_goes_to_the_callers_stream():
+    """The library enqueues on the stream it is handed (here torch's current stream) and does
+    not synchronise: results on a side stream match the default-stream results bit for bit."""
+    Bt, H, N, D = 2, 4, 300, 128
+    q, k, v = gpu(*synth.make_qkv(Bt, H, N, D, torch.bfloat16, 97))
+    g, = gpu(synth.make_do(Bt, H, N, D, torch.bfloat16, 97))
+    dd, = gpu(synth.decay_bench_rule(H))
+    o_ref = ltn.ltn_attn_fwd(q, k, v, dd)
+    g_ref = ltn.ltn_attn_bwd(q, k, v, g, dd)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        o = ltn.ltn_attn_fwd(q, k, v, dd)
+        grads = ltn.ltn_attn_bwd(q, k, v, g, dd)
+    side.synchronize()
+    assert torch.equal(o, o_ref)
+    for a, b in zip(grads, g_ref):
+        assert torch.equal(a, b)
