@@ -111,6 +111,7 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
 #pragma unroll
                 for (int b = 0; b < SR; ++b) acc[a][b] = 0.0f;
             if (c0 <= r0 + SR - 1) {
+#pragma unroll 4
                 for (int i = 0; i < D; i += 4) {
                     float4 av[SR], bv[SR];
 #pragma unroll
@@ -146,6 +147,7 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
                 intra[m] = make_float4(0.f, 0.f, 0.f, 0.f);
                 inter[m] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
+#pragma unroll 4
             for (int c = 0; c < len; ++c) {                       // P C (P is zero above the diagonal)
                 const float4 cv = ld4(&Cs[c * DV + 4 * ox]);
 #pragma unroll
@@ -158,6 +160,7 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
                     intra[m].w = fmaf(p, cv.w, intra[m].w);
                 }
             }
+#pragma unroll 4
             for (int i = 0; i < D; i += 4) {                      // A S
                 const float4 s0 = ld4(&St[(i + 0) * DV + 4 * ox]);
                 const float4 s1 = ld4(&St[(i + 1) * DV + 4 * ox]);
@@ -218,6 +221,7 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
             for (int a = 0; a < UR; ++a)
 #pragma unroll
                 for (int b = 0; b < UC; ++b) st[a][b] *= decay_all;
+#pragma unroll 4
             for (int c = 0; c < len; ++c) {
                 const float w = pw[len - 1 - c];
                 float bv[UR], cv[UC];
