@@ -32,6 +32,11 @@
  *       y = x / sqrt(|x|^2 / D + eps) (.) u      (eps = 0 is the printed formula)
  *   and its derivative with respect to x and u.
  *
+ *   Input side (Sec. 3.1.2 Eq. 2: swish on the query/key projections; Sec. 3.1.1
+ *   Eq. 1: LRPE-d, the phase exp(i theta (t-s)) on the score), near the end of
+ *   this file together with the variants of Algorithm 2 and of the gradients
+ *   for a query/key width different from the value width, which LRPE-d needs.
+ *
  * Parity pins live in tests/test_oracle_pins.py (brute force, closed forms,
  * cumulative-sum special case, finite differences, Algorithm 1 == Algorithm 2
  * identity of App. C, block-form re-association).  Nothing is "parity unpinned".
@@ -543,6 +548,226 @@ void ltn_oracle_gate_bwd(const double* x, const double* u, const double* dy, dou
             const double n = xr[i] / rms;
             du[r * d + i] = gr[i] * n;
             dx[r * d + i] = (gr[i] * ur[i] - n * mean) / rms;
+        }
+    }
+}
+
+/* ========================================================================
+ * Query/key feature width Dk different from the value width Dv.
+ * The definition (Sec. 3.2.1) and Algorithm 2 (Sec. 3.3) never use that the two
+ * widths agree: q_t, k_s in R^Dk meet only in their dot product, the state
+ * kv is [Dk x Dv].  LRPE-d (below) needs Dk = 2 Dv.  Layouts: q,k [Bt,H,N,Dk];
+ * v,o [Bt,H,N,Dv]; states [Bt,H,Dk,Dv].
+ * ====================================================================== */
+
+/* Algorithm 2 (Sec. 3.3), token by token. */
+void ltn_oracle_fwd_recurrent_dkdv(const double* q, const double* k, const double* v,
+                                   const double* decay, const double* kv_in,
+                                   int Bt, int H, i64 N, int Dk, int Dv,
+                                   double* o, double* kv_out) {
+    const i64 chains = (i64)Bt * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        const double* Q = q + c * N * Dk;
+        const double* K = k + c * N * Dk;
+        const double* V = v + c * N * Dv;
+        double* O = o + c * N * Dv;
+        const size_t sz = sizeof(double) * (size_t)Dk * Dv;
+        double* kv = (double*)malloc(sz);
+        if (kv_in) memcpy(kv, kv_in + c * Dk * Dv, sz);
+        else memset(kv, 0, sz);
+        for (i64 t = 0; t < N; ++t) {
+            for (int i = 0; i < Dk; ++i)
+                for (int j = 0; j < Dv; ++j)
+                    kv[i * Dv + j] = lam * kv[i * Dv + j] + K[t * Dk + i] * V[t * Dv + j];
+            for (int j = 0; j < Dv; ++j) {
+                double acc = 0.0;
+                for (int i = 0; i < Dk; ++i) acc += Q[t * Dk + i] * kv[i * Dv + j];
+                O[t * Dv + j] = acc;
+            }
+        }
+        if (kv_out) memcpy(kv_out + c * Dk * Dv, kv, sz);
+        free(kv);
+    }
+}
+
+/* Gradients in recurrent form (derivative of the definition):
+ *   forward sweep:  kv_t as above,            dq_t = kv_t dO_t^T        (Dk)
+ *   reverse sweep:  dkv = lambda dkv + q_t^T dO_t  ([Dk x Dv]),
+ *                   dk_t = dkv v_t^T (Dk),    dv_t = k_t dkv (Dv)             */
+void ltn_oracle_bwd_recurrent_dkdv(const double* q, const double* k, const double* v,
+                                   const double* d_o, const double* decay,
+                                   int Bt, int H, i64 N, int Dk, int Dv,
+                                   double* dq, double* dk, double* dv) {
+    const i64 chains = (i64)Bt * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        const double* Q = q + c * N * Dk;
+        const double* K = k + c * N * Dk;
+        const double* V = v + c * N * Dv;
+        const double* G = d_o + c * N * Dv;
+        double* DQ = dq + c * N * Dk;
+        double* DK = dk + c * N * Dk;
+        double* DV = dv + c * N * Dv;
+        double* kv = (double*)calloc((size_t)Dk * Dv, sizeof(double));
+        for (i64 t = 0; t < N; ++t) {
+            for (int i = 0; i < Dk; ++i)
+                for (int j = 0; j < Dv; ++j)
+                    kv[i * Dv + j] = lam * kv[i * Dv + j] + K[t * Dk + i] * V[t * Dv + j];
+            for (int i = 0; i < Dk; ++i) {
+                double acc = 0.0;
+                for (int j = 0; j < Dv; ++j) acc += G[t * Dv + j] * kv[i * Dv + j];
+                DQ[t * Dk + i] = acc;
+            }
+        }
+        memset(kv, 0, sizeof(double) * (size_t)Dk * Dv); /* now the suffix state dkv */
+        for (i64 t = N - 1; t >= 0; --t) {
+            for (int i = 0; i < Dk; ++i)
+                for (int j = 0; j < Dv; ++j)
+                    kv[i * Dv + j] = lam * kv[i * Dv + j] + Q[t * Dk + i] * G[t * Dv + j];
+            for (int i = 0; i < Dk; ++i) {
+                double acc = 0.0;
+                for (int j = 0; j < Dv; ++j) acc += V[t * Dv + j] * kv[i * Dv + j];
+                DK[t * Dk + i] = acc;
+            }
+            for (int j = 0; j < Dv; ++j) {
+                double acc = 0.0;
+                for (int i = 0; i < Dk; ++i) acc += K[t * Dk + i] * kv[i * Dv + j];
+                DV[t * Dv + j] = acc;
+            }
+        }
+        free(kv);
+    }
+}
+
+/* One iteration of Algorithm 2 on a caller-held [Dk x Dv] state. */
+void ltn_oracle_decode_step_dkdv(const double* q, const double* k, const double* v,
+                                 const double* decay, int Bt, int H, int Dk, int Dv,
+                                 double* kv, double* o) {
+    const i64 chains = (i64)Bt * H;
+#pragma omp parallel for schedule(static)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        double* S = kv + c * Dk * Dv;
+        for (int i = 0; i < Dk; ++i)
+            for (int j = 0; j < Dv; ++j)
+                S[i * Dv + j] = lam * S[i * Dv + j] + k[c * Dk + i] * v[c * Dv + j];
+        for (int j = 0; j < Dv; ++j) {
+            double acc = 0.0;
+            for (int i = 0; i < Dk; ++i) acc += q[c * Dk + i] * S[i * Dv + j];
+            o[c * Dv + j] = acc;
+        }
+    }
+}
+
+/* ========================================================================
+ * Input side of the token mixer: the activation of Eq. 2 (Q = phi(X W_q),
+ * K = phi(X W_k) with phi = swish, Sec. 3.1.2) and the position encoding of
+ * Eq. 1, LRPE-d (Sec. 3.1.1):
+ *     a[t,s] = q_t^T k_s lambda^(t-s) exp(i theta (t-s))
+ * The paper prints the complex form only.  Reading taken here: theta is a real
+ * learnable vector per head, one angle per feature ([H, D]); the phase acts
+ * feature by feature and the score is the real part,
+ *     a[t,s] = lambda^(t-s) sum_d q_t[d] k_s[d] cos(theta_d (t - s)).
+ * ====================================================================== */
+
+/* The definition with the real part of Eq. 1 as the score, quadratic in N. */
+void ltn_oracle_lrpe_fwd_quadratic(const double* q, const double* k, const double* v,
+                                   const double* decay, const double* theta,
+                                   int Bt, int H, i64 N, int D, double* o) {
+    const i64 chains = (i64)Bt * H;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (i64 c = 0; c < chains; ++c) {
+        const double lam = decay[c % H];
+        const double* th = theta + (c % H) * D;
+        const double* Q = q + c * N * D;
+        const double* K = k + c * N * D;
+        const double* V = v + c * N * D;
+        double* O = o + c * N * D;
+        for (i64 t = 0; t < N; ++t) {
+            for (int j = 0; j < D; ++j) O[t * D + j] = 0.0;
+            for (i64 s = 0; s <= t; ++s) {
+                double dot = 0.0;
+                for (int i = 0; i < D; ++i)
+                    dot += Q[t * D + i] * K[s * D + i] * cos(th[i] * (double)(t - s));
+                const double a = dot * decay_pow(lam, t - s);
+                for (int j = 0; j < D; ++j) O[t * D + j] += a * V[s * D + j];
+            }
+        }
+    }
+}
+
+static double swish(double x) { return x / (1.0 + exp(-x)); }
+/* d/dx [x sigma(x)] = sigma(x) (1 + x (1 - sigma(x))) */
+static double swish_grad(double x) {
+    const double s = 1.0 / (1.0 + exp(-x));
+    return s * (1.0 + x * (1.0 - s));
+}
+
+/* What the linear-cost evaluation feeds to the attention: Eq. 1 "can be decomposed
+ * with respect to s and t separately" (Sec. 3.1.1) because
+ * cos(theta (t-s)) = cos(theta t) cos(theta s) + sin(theta t) sin(theta s).  For a
+ * token at absolute position p = pos0 + (row index) and z = phi(x) (act != 0) or x:
+ *     y = [ z (.) cos(theta p) | z (.) sin(theta p) ]      (width 2D)
+ * applied to queries and keys alike; their dot product is then the real-part
+ * score above.  theta == NULL: no position encoding, y = z (width D). */
+void ltn_oracle_prologue_fwd(const double* x, const double* theta, int act,
+                             int Bt, int H, i64 N, int D, i64 pos0, double* y) {
+    const i64 chains = (i64)Bt * H;
+    const int W = theta ? 2 * D : D;
+#pragma omp parallel for schedule(static)
+    for (i64 c = 0; c < chains; ++c) {
+        const double* th = theta ? theta + (c % H) * D : NULL;
+        for (i64 t = 0; t < N; ++t) {
+            const double* xr = x + (c * N + t) * D;
+            double* yr = y + (c * N + t) * W;
+            const double p = (double)(pos0 + t);
+            for (int i = 0; i < D; ++i) {
+                const double z = act ? swish(xr[i]) : xr[i];
+                if (th) {
+                    yr[i] = z * cos(th[i] * p);
+                    yr[D + i] = z * sin(th[i] * p);
+                } else {
+                    yr[i] = z;
+                }
+            }
+        }
+    }
+}
+
+/* Derivative of the map above, given dy (width 2D, or D without theta):
+ *     dz = dy_c cos(theta p) + dy_s sin(theta p),      dx = dz phi'(x)
+ *     dtheta[h,d] = sum over batch and tokens of  p z (dy_s cos(theta p) - dy_c sin(theta p))
+ * dtheta ([H, D]) may be NULL.  Parallel over heads so that the sum has a fixed order. */
+void ltn_oracle_prologue_bwd(const double* x, const double* theta, const double* dy, int act,
+                             int Bt, int H, i64 N, int D, i64 pos0,
+                             double* dx, double* dtheta) {
+    const int W = theta ? 2 * D : D;
+#pragma omp parallel for schedule(static)
+    for (int h = 0; h < H; ++h) {
+        const double* th = theta ? theta + (i64)h * D : NULL;
+        if (dtheta) for (int i = 0; i < D; ++i) dtheta[(i64)h * D + i] = 0.0;
+        for (int b = 0; b < Bt; ++b) {
+            const i64 c = (i64)b * H + h;
+            for (i64 t = 0; t < N; ++t) {
+                const double* xr = x + (c * N + t) * D;
+                const double* gr = dy + (c * N + t) * W;
+                double* dxr = dx + (c * N + t) * D;
+                const double p = (double)(pos0 + t);
+                for (int i = 0; i < D; ++i) {
+                    const double z = act ? swish(xr[i]) : xr[i];
+                    const double dphi = act ? swish_grad(xr[i]) : 1.0;
+                    if (th) {
+                        const double cs = cos(th[i] * p), sn = sin(th[i] * p);
+                        dxr[i] = (gr[i] * cs + gr[D + i] * sn) * dphi;
+                        if (dtheta) dtheta[(i64)h * D + i] += p * z * (gr[D + i] * cs - gr[i] * sn);
+                    } else {
+                        dxr[i] = gr[i] * dphi;
+                    }
+                }
+            }
         }
     }
 }
