@@ -180,6 +180,88 @@ ltn_status ltn_attn_decode_steps(const void* q, const void* k, const void* v, vo
                                  float* kv, const float* decay,
                                  int Bt, int H, int S, int D, ltn_dtype dtype, void* stream);
 
+/*
+ * Input side of the token mixer, applied to queries and to keys (one call per tensor):
+ * the activation of Sec. 3.1.2 Eq. 2 (Q = phi(X W_q), K = phi(X W_k), phi = swish,
+ * z = x / (1 + exp(-x))) and the position encoding of Sec. 3.1.1 Eq. 1 (LRPE-d),
+ *
+ *     a[t,s] = q_t^T k_s lambda^(t-s) exp(i theta (t-s)).
+ *
+ * The paper prints the complex form only; this library reads it with one real learnable
+ * angle per head and feature, theta[h,d], acting feature by feature, and the real part as
+ * the score: a[t,s] = lambda^(t-s) sum_d q_t[d] k_s[d] cos(theta[h,d] (t-s)).  It "can be
+ * decomposed with respect to s and t separately" (Sec. 3.1.1): with p the absolute position
+ * of a token,
+ *
+ *     y[b,h,t,:] = [ z (.) cos(theta_h p) | z (.) sin(theta_h p) ],     p = pos0 + t,
+ *
+ * for queries and keys alike gives y_q(t) . y_k(s) = that score without the decay, so the
+ * attention entry points for Dk = 2 Dv below finish the job.  Only differences of positions
+ * matter; pos0 lets a later chunk (chunked prefill, decode) continue an earlier one.
+ *
+ *   x      in : device, [Bt,H,N,D] dtype
+ *   theta  in : device, [H,D] fp32, or NULL: no position encoding, y = z with D features
+ *   y      out: device, [Bt,H,N,2D] dtype ([Bt,H,N,D] when theta is NULL)
+ *   act       : nonzero applies swish, 0 passes x through (z = x)
+ *   pos0      : absolute position of token 0, 0 <= pos0, pos0 + N <= 2^40
+ * D in {64, 128}.  The angle theta p is formed and reduced in fp64, everything else in fp32;
+ * outputs are rounded once to `dtype`.
+ */
+ltn_status ltn_prologue_fwd(const void* x, const float* theta, void* y, int act,
+                            int Bt, int H, long long N, int D, long long pos0,
+                            ltn_dtype dtype, void* stream);
+
+/*
+ * Derivative of ltn_prologue_fwd for one tensor:
+ *     dz = dy_c (.) cos + dy_s (.) sin,   dx = dz (.) phi'(x),
+ *     d_theta[h,d] = sum over b and t of  p z (dy_s cos - dy_c sin)
+ * (the caller adds the d_theta of the query call and of the key call: theta is shared).
+ *
+ *   x, theta, act, pos0 : as given to the forward
+ *   d_y     in : device, [Bt,H,N,2D] dtype ([Bt,H,N,D] when theta is NULL)
+ *   d_x     out: device, [Bt,H,N,D] dtype
+ *   d_theta out: device, [H,D] fp32, overwritten; NULL skips it (and must be NULL when
+ *                theta is NULL)
+ *   workspace  : device scratch of ltn_prologue_workspace_bytes(...) bytes, needed only
+ *                when d_theta is wanted (the sum is taken in a fixed order, in fp64, through
+ *                per-workgroup partial sums: reproducible, no atomics)
+ */
+ltn_status ltn_prologue_bwd(const void* x, const float* theta, const void* d_y, void* d_x,
+                            float* d_theta, int act,
+                            int Bt, int H, long long N, int D, long long pos0, ltn_dtype dtype,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+size_t ltn_prologue_workspace_bytes(int Bt, int H, long long N, int D);
+
+/*
+ * Forward, gradients and decode with query/key width Dk different from the value width
+ * Dv -- what the attention sees behind the LRPE-d expansion above (Dk = 2 Dv).  Same
+ * definition, same conventions and the same kernels as ltn_attn_fwd / ltn_attn_bwd /
+ * ltn_attn_decode_steps (Sec. 3.2.1; Sec. 3.3 Algorithm 2 never uses that the widths agree):
+ *
+ *   q, k, dq, dk : [Bt,H,N,Dk]        v, o, d_o, dv : [Bt,H,N,Dv]
+ *   kv_in, kv_out, kv : fp32 [Bt,H,Dk,Dv]  (row = key feature, column = value feature)
+ *   decode: q, k [Bt,H,S,Dk];  v, o [Bt,H,S,Dv]
+ *
+ * Supported: (Dk, Dv) in {(256,128), (128,64)}; equal widths go through the entry points
+ * above (LTN_ERR_UNSUPPORTED here).  block: 0 = library's choice; bf16 64; fp32 16, or 32
+ * when Dk = 128.  No workspace is needed: long sequences are not cut into segments here.
+ */
+ltn_status ltn_attn_fwd_dkdv(const void* q, const void* k, const void* v, void* o,
+                             const float* decay, const float* kv_in, float* kv_out,
+                             int Bt, int H, long long N, int Dk, int Dv, int block,
+                             ltn_dtype dtype, void* stream);
+
+ltn_status ltn_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
+                             void* dq, void* dk, void* dv, const float* decay,
+                             int Bt, int H, long long N, int Dk, int Dv, int block,
+                             ltn_dtype dtype, void* stream);
+
+ltn_status ltn_attn_decode_steps_dkdv(const void* q, const void* k, const void* v, void* o,
+                                      float* kv, const float* decay,
+                                      int Bt, int H, int S, int Dk, int Dv,
+                                      ltn_dtype dtype, void* stream);
+
 /* Block length the library uses for (D, dtype) when `block` is 0; 0 if unsupported. */
 int ltn_attn_pick_block(int D, ltn_dtype dtype);
 

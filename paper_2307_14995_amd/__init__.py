@@ -18,10 +18,17 @@ from .binding import (  # noqa: F401
     ltn_attn_pick_block,
     ltn_attn_workspace_bytes,
     ltn_status_str,
+    ltn_prologue_fwd,
+    ltn_prologue_bwd,
+    ltn_prologue_workspace_bytes,
+    ltn_attn_fwd_dkdv,
+    ltn_attn_bwd_dkdv,
+    ltn_attn_decode_steps_dkdv,
 )
 
 __all__ = [
     "LtnError", "library_path", "load_library", "ltn_attn_fwd", "ltn_attn_fwd_gated", "ltn_attn_fwd_tiled", "ltn_gate_fwd", "ltn_gate_bwd", "ltn_attn_bwd",
     "ltn_attn_decode_step", "ltn_attn_decode_steps", "ltn_attn_pick_block", "ltn_attn_workspace_bytes",
-    "ltn_attn_check_decay", "ltn_status_str",
+    "ltn_attn_check_decay", "ltn_status_str", "ltn_prologue_fwd", "ltn_prologue_bwd", "ltn_prologue_workspace_bytes",
+    "ltn_attn_fwd_dkdv", "ltn_attn_bwd_dkdv", "ltn_attn_decode_steps_dkdv",
 ]

@@ -20,6 +20,8 @@ SYMBOLS = (
     "ltn_attn_fwd", "ltn_attn_fwd_gated", "ltn_attn_fwd_tiled", "ltn_gate_fwd", "ltn_gate_bwd",
     "ltn_attn_bwd", "ltn_attn_decode_step", "ltn_attn_decode_steps", "ltn_attn_pick_block",
     "ltn_attn_workspace_bytes", "ltn_attn_check_decay", "ltn_status_str",
+    "ltn_prologue_fwd", "ltn_prologue_bwd", "ltn_prologue_workspace_bytes",
+    "ltn_attn_fwd_dkdv", "ltn_attn_bwd_dkdv", "ltn_attn_decode_steps_dkdv",
 )
 
 
@@ -70,6 +72,18 @@ def load_library():
     lib.ltn_attn_check_decay.restype = ci
     lib.ltn_status_str.argtypes = [ci]
     lib.ltn_status_str.restype = ctypes.c_char_p
+    lib.ltn_prologue_fwd.argtypes = [vp, fp, vp, ci, ci, ci, cl, ci, cl, ci, vp]
+    lib.ltn_prologue_fwd.restype = ci
+    lib.ltn_prologue_bwd.argtypes = [vp, fp, vp, vp, fp, ci, ci, ci, cl, ci, cl, ci, vp, sz, vp]
+    lib.ltn_prologue_bwd.restype = ci
+    lib.ltn_prologue_workspace_bytes.argtypes = [ci, ci, cl, ci]
+    lib.ltn_prologue_workspace_bytes.restype = sz
+    lib.ltn_attn_fwd_dkdv.argtypes = [vp, vp, vp, vp, fp, fp, fp, ci, ci, cl, ci, ci, ci, ci, vp]
+    lib.ltn_attn_fwd_dkdv.restype = ci
+    lib.ltn_attn_bwd_dkdv.argtypes = [vp, vp, vp, vp, vp, vp, vp, fp, ci, ci, cl, ci, ci, ci, ci, vp]
+    lib.ltn_attn_bwd_dkdv.restype = ci
+    lib.ltn_attn_decode_steps_dkdv.argtypes = [vp, vp, vp, vp, fp, fp, ci, ci, ci, ci, ci, ci, vp]
+    lib.ltn_attn_decode_steps_dkdv.restype = ci
     _lib = lib
     return lib
 
@@ -310,4 +324,124 @@ def ltn_attn_fwd_tiled(q, k, v, decay, out=None):
                                     _dtype_code(q.dtype), _stream(q.device))
     if rc != 0:
         raise LtnError(rc, "ltn_attn_fwd_tiled")
+    return o
+
+
+def ltn_prologue_workspace_bytes(Bt, H, N, D) -> int:
+    return int(load_library().ltn_prologue_workspace_bytes(int(Bt), int(H), int(N), int(D)))
+
+
+def _check_theta(theta, H, D):
+    if theta is None:
+        return
+    _dev(theta, "theta")
+    if theta.dtype != torch.float32 or tuple(theta.shape) != (H, D):
+        raise ValueError("theta must be fp32 [H,D]")
+
+
+def ltn_prologue_fwd(x, theta=None, act=True, pos0=0, out=None):
+    """y = [z cos(theta p) | z sin(theta p)] with z = swish(x) (act) or x, p = pos0 + token; theta None: y = z."""
+    lib = load_library()
+    _dev(x, "x")
+    if x.dim() != 4:
+        raise ValueError("x must be [Bt,H,N,D]")
+    Bt, H, N, D = x.shape
+    _check_theta(theta, H, D)
+    W = D if theta is None else 2 * D
+    y = torch.empty((Bt, H, N, W), dtype=x.dtype, device=x.device) if out is None else _dev(out, "out")
+    if tuple(y.shape) != (Bt, H, N, W) or y.dtype != x.dtype:
+        raise ValueError("out must be [Bt,H,N,2D] (or [Bt,H,N,D] without theta) in x's dtype")
+    with torch.cuda.device(x.device):
+        rc = lib.ltn_prologue_fwd(_ptr(x), _ptr(theta), _ptr(y), int(bool(act)), Bt, H, N, D, int(pos0),
+                                  _dtype_code(x.dtype), _stream(x.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_prologue_fwd")
+    return y
+
+
+def ltn_prologue_bwd(x, d_y, theta=None, act=True, pos0=0, want_dtheta=True):
+    """(d_x, d_theta) of ltn_prologue_fwd for one tensor; d_theta is None without theta or when not wanted."""
+    lib = load_library()
+    _dev(x, "x")
+    _dev(d_y, "d_y")
+    if x.dim() != 4:
+        raise ValueError("x must be [Bt,H,N,D]")
+    Bt, H, N, D = x.shape
+    _check_theta(theta, H, D)
+    W = D if theta is None else 2 * D
+    if tuple(d_y.shape) != (Bt, H, N, W) or d_y.dtype != x.dtype:
+        raise ValueError("d_y must be [Bt,H,N,2D] (or [Bt,H,N,D] without theta) in x's dtype")
+    dx = torch.empty_like(x)
+    dth = torch.empty((H, D), dtype=torch.float32, device=x.device) if (theta is not None and want_dtheta) else None
+    ws_bytes = int(lib.ltn_prologue_workspace_bytes(Bt, H, N, D)) if dth is not None else 0
+    ws = _workspace(ws_bytes, x.device)
+    with torch.cuda.device(x.device):
+        rc = lib.ltn_prologue_bwd(_ptr(x), _ptr(theta), _ptr(d_y), _ptr(dx), _ptr(dth), int(bool(act)),
+                                  Bt, H, N, D, int(pos0), _dtype_code(x.dtype), _ptr(ws), ws_bytes, _stream(x.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_prologue_bwd")
+    return dx, dth
+
+
+def _check_dkdv(q, k, v, decay):
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (decay, "decay")):
+        _dev(t, n)
+    if q.dim() != 4 or q.shape != k.shape or v.dim() != 4 or v.shape[:3] != q.shape[:3]:
+        raise ValueError("q, k must be [Bt,H,N,Dk] and v [Bt,H,N,Dv]")
+    if not (q.dtype == k.dtype == v.dtype):
+        raise ValueError("q, k, v must share a dtype")
+    Bt, H, N, Dk = q.shape
+    if decay.dtype != torch.float32 or decay.numel() != H:
+        raise ValueError("decay must be fp32 [H]")
+    return Bt, H, N, Dk, v.shape[3]
+
+
+def ltn_attn_fwd_dkdv(q, k, v, decay, kv_in=None, return_state=False, block=0, out=None, kv_out=None):
+    """The forward with q, k of width Dk and v, o of width Dv (state fp32 [Bt,H,Dk,Dv])."""
+    lib = load_library()
+    Bt, H, N, Dk, Dv = _check_dkdv(q, k, v, decay)
+    o = torch.empty_like(v) if out is None else _dev(out, "out")
+    if kv_in is not None:
+        _dev(kv_in, "kv_in")
+        if kv_in.dtype != torch.float32 or tuple(kv_in.shape) != (Bt, H, Dk, Dv):
+            raise ValueError("kv_in must be fp32 [Bt,H,Dk,Dv]")
+    if kv_out is None and return_state:
+        kv_out = torch.empty((Bt, H, Dk, Dv), dtype=torch.float32, device=q.device)
+    with torch.cuda.device(q.device):
+        rc = lib.ltn_attn_fwd_dkdv(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(decay), _ptr(kv_in), _ptr(kv_out),
+                                   Bt, H, N, Dk, Dv, int(block), _dtype_code(q.dtype), _stream(q.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_fwd_dkdv")
+    return (o, kv_out) if (return_state or kv_out is not None) else o
+
+
+def ltn_attn_bwd_dkdv(q, k, v, d_o, decay, block=0):
+    """(dQ, dK, dV) for q, k of width Dk and v, d_o of width Dv."""
+    lib = load_library()
+    Bt, H, N, Dk, Dv = _check_dkdv(q, k, v, decay)
+    _dev(d_o, "d_o")
+    if d_o.shape != v.shape or d_o.dtype != v.dtype:
+        raise ValueError("d_o must have v's shape and dtype")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    with torch.cuda.device(q.device):
+        rc = lib.ltn_attn_bwd_dkdv(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(decay),
+                                   Bt, H, N, Dk, Dv, int(block), _dtype_code(q.dtype), _stream(q.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_bwd_dkdv")
+    return dq, dk, dv
+
+
+def ltn_attn_decode_steps_dkdv(q, k, v, kv, decay, out=None):
+    """S decode steps: q, k [Bt,H,S,Dk]; v [Bt,H,S,Dv]; kv fp32 [Bt,H,Dk,Dv] updated in place; returns o."""
+    lib = load_library()
+    Bt, H, S, Dk, Dv = _check_dkdv(q, k, v, decay)
+    _dev(kv, "kv")
+    if kv.dtype != torch.float32 or tuple(kv.shape) != (Bt, H, Dk, Dv):
+        raise ValueError("kv must be fp32 [Bt,H,Dk,Dv]")
+    o = torch.empty_like(v) if out is None else _dev(out, "out")
+    with torch.cuda.device(q.device):
+        rc = lib.ltn_attn_decode_steps_dkdv(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(kv), _ptr(decay),
+                                            Bt, H, S, Dk, Dv, _dtype_code(q.dtype), _stream(q.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_decode_steps_dkdv")
     return o

@@ -29,6 +29,14 @@ int pick_dv(long long chain_passes, int D, ltn_dtype dtype) {
     return hi;
 }
 
+// The same rule for a pass whose value side has DC columns and whose kernels exist for
+// slices of lo .. hi columns (powers of two).
+int pick_dv_range(long long chain_passes, int DC, int lo, int hi) {
+    for (int dv = lo; dv <= hi; dv *= 2)
+        if (chain_passes * (DC / dv) <= 256) return dv;
+    return hi;
+}
+
 ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype dtype, int* blk_out) {
     if (Bt < 0 || H < 0 || N < 0 || D <= 0 || block < 0) return LTN_ERR_SHAPE;
     if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
@@ -343,7 +351,7 @@ ltn_status ltn_attn_decode_steps(const void* q, const void* k, const void* v, vo
         return LTN_ERR_UNSUPPORTED;
     const int chains = Bt * H;
     if (empty) return LTN_OK;
-    const hipError_t e = ltn::launch_decode(q, k, v, o, kv, decay, chains, H, S, D, dtype == LTN_BF16,
+    const hipError_t e = ltn::launch_decode(q, k, v, o, kv, decay, chains, H, S, D, D, dtype == LTN_BF16,
                                             static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
 }
@@ -352,6 +360,197 @@ ltn_status ltn_attn_decode_step(const void* q, const void* k, const void* v, voi
                                 float* kv, const float* decay,
                                 int Bt, int H, int D, ltn_dtype dtype, void* stream) {
     return ltn_attn_decode_steps(q, k, v, o, kv, decay, Bt, H, 1, D, dtype, stream);
+}
+
+// ---------------------------------------------------------------------------------------
+// Query/key width Dk = 2 Dv (behind the LRPE-d expansion) and the input side itself.
+// ---------------------------------------------------------------------------------------
+
+static ltn_status check_dkdv(int Bt, int H, long long N, int Dk, int Dv, int block, ltn_dtype dtype, int* blk_out) {
+    if (Bt < 0 || H < 0 || N < 0 || Dk <= 0 || Dv <= 0 || block < 0) return LTN_ERR_SHAPE;
+    if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
+    if (!((Dk == 256 && Dv == 128) || (Dk == 128 && Dv == 64))) return LTN_ERR_UNSUPPORTED;
+    int blk = block;
+    if (dtype == LTN_BF16) {
+        if (blk == 0) blk = 64;
+        if (blk != 64) return LTN_ERR_UNSUPPORTED;
+    } else {
+        if (blk == 0) blk = Dk == 256 ? 16 : 32;
+        if (blk != 16 && !(blk == 32 && Dk == 128)) return LTN_ERR_UNSUPPORTED;
+    }
+    if ((long long)Bt * H > 0x3fffffffLL) return LTN_ERR_SHAPE;
+    *blk_out = blk;
+    return LTN_OK;
+}
+
+// One launch of `pb` (passes of one shape): a, b with DA features, c and out with DC.
+static ltn_status run_dkdv(const ltn::PassBatch& pb, int DA, int DC, int blk, ltn_dtype dtype, hipStream_t st) {
+    const long long chain_passes = (long long)pb.chains * pb.count;
+    hipError_t e;
+    if (dtype == LTN_BF16) {
+        // slices the kernels exist for: 32..64 behind a 256-wide query/key side (its state
+        // copies fill the LDS beyond that) and behind a 64-wide one, 32..min(DC,128) otherwise
+        const int hi = (DA == 256 || DA == 64) ? 64 : (DC < 128 ? DC : 128);
+        e = ltn::launch_pass_bf16(pb, DA, pick_dv_range(chain_passes, DC, 32, hi), st, DC);
+    } else {
+        const int lo = 64, hi = (DA == 256) ? 64 : (DC < 128 ? DC : 128);
+        e = ltn::launch_pass_f32(pb, DA, pick_dv_range(chain_passes, DC, lo, hi), blk, st, DC);
+    }
+    return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+}
+
+ltn_status ltn_attn_fwd_dkdv(const void* q, const void* k, const void* v, void* o,
+                             const float* decay, const float* kv_in, float* kv_out,
+                             int Bt, int H, long long N, int Dk, int Dv, int block, ltn_dtype dtype,
+                             void* stream) {
+    const bool empty = (Bt == 0 || H == 0 || N == 0);
+    if (!decay || (!empty && (!q || !k || !v || !o))) return LTN_ERR_NULL;
+    int blk = 0;
+    const ltn_status cs = check_dkdv(Bt, H, N, Dk, Dv, block, dtype, &blk);
+    if (cs != LTN_OK) return cs;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(kv_in) ||
+        !aligned16(kv_out) || (reinterpret_cast<uintptr_t>(decay) & 3u))
+        return LTN_ERR_ALIGN;
+    if (!empty && (o == q || o == k || o == v || (const void*)kv_out == q || (const void*)kv_out == k ||
+                   (const void*)kv_out == v || (const void*)kv_out == o))
+        return LTN_ERR_UNSUPPORTED;
+    const long long chains = (long long)Bt * H;
+    if (chains == 0) return LTN_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (N == 0) {
+        if (!kv_out) return LTN_OK;
+        return ltn::launch_state_copy(kv_in, kv_out, (size_t)chains * Dk * Dv, st) == hipSuccess
+                   ? LTN_OK : LTN_ERR_LAUNCH;
+    }
+    ltn::PassBatch pb = {};
+    pb.segs = 1;
+    pb.count = 1;
+    pb.decay = decay;
+    pb.chains = (int)chains;
+    pb.H = H;
+    pb.N = N;
+    pb.p[0] = ltn::PassArgs{q, k, v, o, kv_in, kv_out, 0};
+    return run_dkdv(pb, Dk, Dv, blk, dtype, st);
+}
+
+ltn_status ltn_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
+                             void* dq, void* dk, void* dv, const float* decay,
+                             int Bt, int H, long long N, int Dk, int Dv, int block, ltn_dtype dtype,
+                             void* stream) {
+    const bool empty = (Bt == 0 || H == 0 || N == 0);
+    if (!decay || (!empty && (!q || !k || !v || !d_o || !dq || !dk || !dv))) return LTN_ERR_NULL;
+    int blk = 0;
+    const ltn_status cs = check_dkdv(Bt, H, N, Dk, Dv, block, dtype, &blk);
+    if (cs != LTN_OK) return cs;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) ||
+        !aligned16(dk) || !aligned16(dv) || (reinterpret_cast<uintptr_t>(decay) & 3u))
+        return LTN_ERR_ALIGN;
+    const void* ins[4] = {q, k, v, d_o};
+    const void* outs[3] = {dq, dk, dv};
+    for (int a = 0; a < 3 && !empty; ++a) {
+        for (int b = 0; b < 4; ++b)
+            if (outs[a] == ins[b]) return LTN_ERR_UNSUPPORTED;
+        for (int b = a + 1; b < 3; ++b)
+            if (outs[a] == outs[b]) return LTN_ERR_UNSUPPORTED;
+    }
+    const long long chains = (long long)Bt * H;
+    if (chains == 0 || N == 0) return LTN_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // The same three passes as ltn_attn_bwd; they come in two shapes, hence two launches:
+    //   dV = pass(K, Q, dO), last token -> first:  Dk-wide a, b;  Dv-wide c, out
+    //   dK = pass(V, dO, Q) (last -> first), dQ = pass(dO, V, K):  Dv-wide a, b;  Dk-wide c, out
+    ltn::PassBatch pb = {};
+    pb.segs = 1;
+    pb.decay = decay;
+    pb.chains = (int)chains;
+    pb.H = H;
+    pb.N = N;
+    pb.count = 1;
+    pb.p[0] = ltn::PassArgs{k, q, d_o, dv, nullptr, nullptr, 1};
+    const ltn_status s1 = run_dkdv(pb, Dk, Dv, blk, dtype, st);
+    if (s1 != LTN_OK) return s1;
+    pb.count = 2;
+    pb.p[0] = ltn::PassArgs{v, d_o, q, dk, nullptr, nullptr, 1};
+    pb.p[1] = ltn::PassArgs{d_o, v, k, dq, nullptr, nullptr, 0};
+    return run_dkdv(pb, Dv, Dk, blk, dtype, st);
+}
+
+ltn_status ltn_attn_decode_steps_dkdv(const void* q, const void* k, const void* v, void* o,
+                                      float* kv, const float* decay,
+                                      int Bt, int H, int S, int Dk, int Dv, ltn_dtype dtype, void* stream) {
+    const bool empty = (Bt == 0 || H == 0 || S == 0);
+    if (!decay || (!empty && (!q || !k || !v || !o || !kv))) return LTN_ERR_NULL;
+    if (Bt < 0 || H < 0 || S < 0 || Dk <= 0 || Dv <= 0) return LTN_ERR_SHAPE;
+    if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
+    if (!((Dk == 256 && Dv == 128) || (Dk == 128 && Dv == 64))) return LTN_ERR_UNSUPPORTED;
+    if ((long long)Bt * H > 0x3fffffffLL) return LTN_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(kv) ||
+        (reinterpret_cast<uintptr_t>(decay) & 3u))
+        return LTN_ERR_ALIGN;
+    if (!empty && (o == q || o == k || o == v || (const void*)kv == q || (const void*)kv == k ||
+                   (const void*)kv == v || (const void*)kv == o))
+        return LTN_ERR_UNSUPPORTED;
+    if (empty) return LTN_OK;
+    const hipError_t e = ltn::launch_decode(q, k, v, o, kv, decay, Bt * H, H, S, Dk, Dv, dtype == LTN_BF16,
+                                            static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+}
+
+size_t ltn_prologue_workspace_bytes(int Bt, int H, long long N, int D) {
+    if (Bt <= 0 || H <= 0 || N <= 0 || D <= 0) return 0;
+    return (size_t)ltn::prologue_partial_count(N) * (size_t)H * (size_t)D * sizeof(double);
+}
+
+static ltn_status prologue_common(const void* x, const float* theta, const void* d_y, void* out, float* d_theta,
+                                  int act, int Bt, int H, long long N, int D, long long pos0, ltn_dtype dtype,
+                                  void* workspace, size_t workspace_bytes, void* stream, bool bwd) {
+    if (Bt < 0 || H < 0 || N < 0 || D <= 0 || pos0 < 0) return LTN_ERR_SHAPE;
+    if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
+    if (D != 64 && D != 128) return LTN_ERR_UNSUPPORTED;
+    if ((long long)Bt * H > 0x3fffffffLL || pos0 + N > (1LL << 40)) return LTN_ERR_SHAPE;
+    const bool empty = (Bt == 0 || H == 0 || N == 0);
+    if (d_theta && !theta) return LTN_ERR_NULL;
+    if (!empty && (!x || !out || (bwd && !d_y))) return LTN_ERR_NULL;
+    const bool want_dtheta = bwd && theta && d_theta;
+    if (want_dtheta && !empty) {
+        if (workspace_bytes < ltn_prologue_workspace_bytes(Bt, H, N, D)) return LTN_ERR_SHAPE;
+        if (!workspace) return LTN_ERR_NULL;
+    }
+    if (!aligned16(x) || !aligned16(d_y) || !aligned16(out) || !aligned16(workspace) ||
+        (reinterpret_cast<uintptr_t>(theta) & 3u) || (reinterpret_cast<uintptr_t>(d_theta) & 3u))
+        return LTN_ERR_ALIGN;
+    if (!empty) {
+        const void* ins[3] = {x, d_y, theta};
+        const void* outs[2] = {out, d_theta};
+        for (int a = 0; a < 2; ++a) {
+            if (!outs[a]) continue;
+            for (int b = 0; b < 3; ++b)
+                if (outs[a] == ins[b]) return LTN_ERR_UNSUPPORTED;
+        }
+        if (out == (const void*)d_theta) return LTN_ERR_UNSUPPORTED;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (empty) {
+        // no token contributes: the angle gradient is zero
+        if (want_dtheta && H > 0)
+            return ltn::launch_state_copy(nullptr, d_theta, (size_t)H * D, st) == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+        return LTN_OK;
+    }
+    const hipError_t e = ltn::launch_prologue(x, theta, d_y, out, d_theta, static_cast<double*>(workspace), act != 0,
+                                              Bt, H, N, D, pos0, dtype == LTN_BF16, bwd, st);
+    return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+}
+
+ltn_status ltn_prologue_fwd(const void* x, const float* theta, void* y, int act,
+                            int Bt, int H, long long N, int D, long long pos0, ltn_dtype dtype, void* stream) {
+    return prologue_common(x, theta, nullptr, y, nullptr, act, Bt, H, N, D, pos0, dtype, nullptr, 0, stream, false);
+}
+
+ltn_status ltn_prologue_bwd(const void* x, const float* theta, const void* d_y, void* d_x, float* d_theta, int act,
+                            int Bt, int H, long long N, int D, long long pos0, ltn_dtype dtype,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    return prologue_common(x, theta, d_y, d_x, d_theta, act, Bt, H, N, D, pos0, dtype, workspace, workspace_bytes,
+                           stream, true);
 }
 
 }  // extern "C"

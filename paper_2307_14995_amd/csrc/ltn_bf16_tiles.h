@@ -64,13 +64,14 @@ template <int COLS>
 struct Swz {
     static constexpr int RB = COLS * 2;        // bytes per row
     static constexpr int CPR = RB / 16;        // chunks per row
-    static constexpr int RPB = 256 / RB;       // rows per 256 bytes (one pass over the banks)
+    static constexpr int RPB = RB >= 256 ? 1 : 256 / RB;   // rows per 256 bytes (one pass over the banks)
+    static constexpr int KC = CPR < 16 ? CPR : 16;         // chunk positions the key permutes (a bank pass)
     static constexpr int BYTES = kBlock * RB;  // a 64-row tile
     static constexpr int NI = BYTES / 1024;    // wave-wide direct loads per tile
-    static_assert(COLS == 128 || COLS == 64 || COLS == 32, "tile widths");
+    static_assert(COLS == 256 || COLS == 128 || COLS == 64 || COLS == 32, "tile widths");
     __device__ static __forceinline__ int key(int r) {
         const int q = r / RPB;             // index of the row's 256-byte group member
-        return ((q % (CPR / 2)) << 1) | ((q / (CPR / 2)) & 1);
+        return ((q % (KC / 2)) << 1) | ((q / (KC / 2)) & 1);
     }
     __device__ static __forceinline__ int off(int r, int c) { return r * RB + ((c ^ key(r)) << 4); }
 };

@@ -50,13 +50,17 @@ struct PassBatch {
 
 // bf16 MFMA kernel, block length 64.  D in {64,128}; dv = value columns per workgroup
 // (D, D/2 or, for D = 128, D/4).
-hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream);
+// DC (0: = D): features per token of c and out when they differ from those of a and b
+// (the LRPE-d expansion of Eq. 1 doubles the query/key width): a, b [chains, N, D];
+// c, out [chains, N, DC]; states [chains, D, DC]; dv slices DC.  Plain pass, one segment.
+// (D, DC) in {(256,128), (128,256), (128,64), (64,128)}.
+hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream, int DC = 0);
 // Forward by the quadratic tiling of App. B Algorithm 3 (comparison kernel), bf16, zero
 // initial state, D in {64,128}.
 hipError_t launch_tiled_fwd_bf16(const void* q, const void* k, const void* v, void* o, const float* decay,
                                  int chains, int H, long long N, int D, hipStream_t stream);
 // fp32 kernel.  D in {64,128}, block in {16,32,64}, D*block <= 4096.
-hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStream_t stream);
+hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStream_t stream, int DC = 0);
 // Turns the segment-local end states L[pass][chain][g] in `states` (as written by a
 // state_only launch) into the states at each segment's start, in place:
 //   S[0] = kv_in (pass 0 only) or 0,   S[g+1] = lambda^len(g) S[g] + L[g],
@@ -66,11 +70,21 @@ hipError_t launch_segment_scan(float* states, const float* kv_in, float* kv_out,
                                int D, hipStream_t stream);
 // kv[c] (or zeros if null) -> kv_out[c], n floats.
 hipError_t launch_state_copy(const float* kv_in, float* kv_out, size_t n, hipStream_t stream);
-// `steps` consecutive decode steps per chain (q, k, v, o: [chains, steps, D]), see
-// ltn_attn_decode_steps.
+// `steps` consecutive decode steps per chain (q, k: [chains, steps, DK]; v, o: [chains,
+// steps, DV]; kv: [chains, DK, DV]), see ltn_attn_decode_steps.  (DK, DV) in {(128,128),
+// (64,64), (256,128), (128,64)}.
 hipError_t launch_decode(const void* q, const void* k, const void* v, void* o, float* kv,
-                         const float* decay, int chains, int H, int steps, int D, int is_bf16,
+                         const float* decay, int chains, int H, int steps, int DK, int DV, int is_bf16,
                          hipStream_t stream);
+
+// Input side of the token mixer for queries and keys (see ltn_prologue.hip): swish (Eq. 2)
+// and the LRPE-d expansion of Eq. 1.  is_bwd = 0: y from x.  is_bwd = 1: dx from (x, dy)
+// and, with theta and dtheta given, dtheta[H, D] through `partials` (device scratch of
+// prologue_partial_count(N) * H * D doubles).
+long long prologue_partial_count(long long N);
+hipError_t launch_prologue(const void* x, const float* theta, const void* dy, void* out, float* dtheta,
+                           double* partials, int act, int Bt, int H, long long N, int D, long long pos0,
+                           int is_bf16, int is_bwd, hipStream_t stream);
 
 // Gated SimpleRMSNorm on `rows` rows of D features (see ltn_gate.hip).  is_bwd = 0:
 // o0 = y (dy, o1 unused); is_bwd = 1: o0 = dx, o1 = du.

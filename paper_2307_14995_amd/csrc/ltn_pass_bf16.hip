@@ -3,7 +3,9 @@
 // Building block: the decayed linear-attention pass (arXiv 2307.14995, Sec. 3.2.1 with
 // the decay mask of Eq. 1; recurrence of Sec. 3.3, Algorithm 2, taken 64 tokens at a
 // time).  For each chain (batch, head) and a slice of DV value columns, per block i of
-// 64 tokens, with S_i the running [D x DV] state:
+// 64 tokens, with S_i the running [D x DV] state (A, B have D features; C and the output
+// have DC, equal to D except around the LRPE-d expansion of Eq. 1, where queries and keys
+// are twice as wide as values):
 //
 //     P    = (A_i B_i^T) (.) M,       M[r,c] = lambda^(r-c) for r >= c else 0
 //     O_i  = P C_i + diag(lambda^(r+1)) A_i S_i
@@ -61,13 +63,36 @@ struct Cfg {
     using F = Swz<D>;                          // full-width tiles and state copies [DV][D]
     using V = Swz<DV>;                         // DV-wide C tile of the pass body
     static constexpr int SBYTES = DV * F::RB;  // one bf16 state copy
-    // pass body: ring of PST stages {A tile, B tile, C tile}, then two state copies
-    static constexpr int PSTAGE = 2 * F::BYTES + V::BYTES;
+    // pass body: ring of PST stages {A tile, B tile, C tile}, then two state copies.
+    // AREG (256 query/key features, the LRPE-d expansion of Eq. 1): two 32 KB tiles per
+    // stage would leave room for one stage only, so the A tile stays out of LDS -- every
+    // output wave fetches its own 16 rows of A straight into registers, two blocks ahead --
+    // and a stage is {B tile, C tile}.
+    static constexpr bool AREG = D == 256;
+    static constexpr int BOFF = AREG ? 0 : F::BYTES;        // B tile inside a stage
+    static constexpr int COFF = BOFF + F::BYTES;            // C tile inside a stage
+    static constexpr int PSTAGE = COFF + V::BYTES;
     static constexpr int PST = (4 * PSTAGE + 2 * SBYTES <= 163840) ? 4 : ((3 * PSTAGE + 2 * SBYTES <= 163840) ? 3 : 2);
     static constexpr int P_SB = PST * PSTAGE;
     static constexpr int PASS_TOTAL = P_SB + 2 * SBYTES;
     static_assert(PASS_TOTAL <= 163840, "LDS per workgroup");
 };
+
+// Register prefetch loads of the AREG output waves are issued from inline assembly and
+// waited for with explicit vmcnt counts: left to the compiler, loads that rotate through
+// register sets two blocks ahead make its wait-count bookkeeping wait for every load right
+// after issuing it.  The destination is an in/out operand and every load is unconditional,
+// so a register set is one variable updated in place and the compiler has no reason to copy
+// it (a copy made between issue and wait would read stale data).
+__device__ __forceinline__ void gload16(u32x4& r, const char* p) {
+    asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(r) : "v"(p) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm8(u32x4 (&r)[8]) {
+    asm volatile("s_waitcnt vmcnt(%8)"
+                 : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])
+                 : "n"(N) : "memory");
+}
 
 // lambda^n for 0 <= n <= 64 without one fp64 powering loop per constant: every lane powers
 // once (lambda^lane, and lambda^64), the rest are cross-lane reads.  Same values as
@@ -375,7 +400,7 @@ struct Chain {            // what every wave of the workgroup knows about its pr
 // state-only sweep of the sequence-parallel form (no outputs: only the segment's end state).
 enum { kPlain = 0, kGated = 1, kStateOnly = 2 };
 
-template <int D, int DV, int W, int MODE>
+template <int D, int DV, int DC, int W, int MODE>
 __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, int lane) {
     using C = Cfg<D, DV>;
     constexpr bool GATED = MODE == kGated;
@@ -385,7 +410,7 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, in
         return;
     }
     constexpr int KS = C::KS;
-    constexpr long long ROW = D * 2;
+    constexpr long long ROW = DC * 2;      // the output's row (and U's, Y's)
     const int g = lane >> 4, i16 = lane & 15;
     OutConsts<W> k;
     k.init(ch.lam, g, i16);
@@ -410,7 +435,7 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, in
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) Af[ks].u = *(const u32x4*)(st + (16 * W) * C::F::RB + ro.row[ks]);
         const long long bo = (long long)blk * step;
-        output_pass<D, DV, W, DV, GATED>(st + C::F::BYTES, st + 2 * C::F::BYTES,
+        output_pass<D, DV, W, DV, GATED>(st + C::BOFF, st + C::COFF,
                                          smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
                                          po ? po + bo : nullptr, more || row_ok,
                                          GATED ? pu + bo : nullptr, GATED ? py + bo : nullptr, ch.eps);
@@ -419,12 +444,83 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, in
     }
 }
 
-template <int D, int DV, int MODE>
+// Output wave of the AREG layout: as pass_output_wave, but the A fragments of its 16 rows
+// come straight from global memory into three rotating register sets, two blocks ahead.
+template <int D, int DV, int DC, int W>
+__device__ __forceinline__ void areg_output_wave(const Chain& ch, char* smem, int lane) {
+    using C = Cfg<D, DV>;
+    constexpr int KS = C::KS, NT = C::NT;
+    static_assert(KS == 8, "register sets of eight fragments");
+    constexpr long long AROW = D * 2, ROW = DC * 2;
+    const int g = lane >> 4, i16 = lane & 15;
+    OutConsts<W> k;
+    k.init(ch.lam, g, i16);
+    ReadOffs<D, DV, DV> ro;
+    ro.init(g, i16, 0);
+
+    const long long r0 = ch.rev ? (ch.N - 1 - (16 * W + i16)) : (long long)(16 * W + i16);
+    const long long astep = ch.rev ? -(long long)kBlock * AROW : (long long)kBlock * AROW;
+    const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
+    const char* pa = ch.a + r0 * AROW + (8 * g) * 2;
+    char* po = ch.out + r0 * ROW + (8 * g) * 2;
+    auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
+
+    struct Set { u32x4 f[KS]; };
+    auto load_a = [&](Set& s, int b) {
+        b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block (ignored)
+        const bool ok = (16 * W + i16) < valid_of(b);
+        const char* p = pa + (long long)b * astep;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) gload16(s.f[ks], ok ? p + ks * 64 : (const char*)kZeros);
+    };
+    // Set(blk) was issued two blocks ago; since then this wave issued the NT/2 stores of
+    // each of two blocks and the KS loads of set(blk+1).
+    constexpr int kAfter = NT + KS;
+    static_assert(kAfter <= 63, "vmcnt field");
+
+    auto do_block = [&](int blk, int stage, Set& cur_set, Set& incoming) {
+        const bool more = blk + 1 < ch.T;
+        const bool row_ok = (16 * W + i16) < valid_of(blk);
+        wait_vm8<kAfter>(cur_set.f);
+        Frag Af[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) Af[ks].u = cur_set.f[ks];
+        load_a(incoming, blk + 2);
+        const char* st = smem + stage * C::PSTAGE;
+        output_pass<D, DV, W, DV>(st + C::BOFF, st + C::COFF, smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
+                                  po + (long long)blk * step, more || row_ok);
+        if (more) __syncthreads();
+    };
+
+    Set s0, s1, s2;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) s0.f[ks] = s1.f[ks] = s2.f[ks] = u32x4{0, 0, 0, 0};
+    load_a(s0, 0);
+    load_a(s1, 1);
+    wait_vm8<0>(s0.f);                     // blocks 0 and 1 are retired here, so the
+    wait_vm8<0>(s1.f);                     // steady-state count is safe for them too
+    __syncthreads();                       // block 0 tiles and the initial state copy are in LDS
+
+    int stage = 0;
+    auto next = [&]() { stage = (stage + 1 == C::PST) ? 0 : stage + 1; };
+    for (int blk = 0; blk < ch.T; blk += 3) {
+        do_block(blk, stage, s0, s2); next();
+        if (blk + 1 < ch.T) { do_block(blk + 1, stage, s1, s0); next(); }
+        if (blk + 2 < ch.T) { do_block(blk + 2, stage, s2, s1); next(); }
+    }
+    // the last two prefetches were never consumed: retire them before the registers die
+    wait_vm8<0>(s0.f);
+    wait_vm8<0>(s1.f);
+    wait_vm8<0>(s2.f);
+}
+
+template <int D, int DV, int DC, int MODE>
 __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, unsigned lds0, int lane, int u) {
     using C = Cfg<D, DV>;
     constexpr int MT = C::MT, NT = C::NT;
-    constexpr bool SO = MODE == kStateOnly;          // no A tile, no published state copies
-    constexpr long long ROW = D * 2;
+    constexpr bool SO = MODE == kStateOnly;          // no published state copies
+    constexpr bool NOA = SO || C::AREG;              // the A tile is not this wave's business
+    constexpr long long ROW = D * 2, CROW = DC * 2;
     const int g = lane >> 4, i16 = lane & 15;
     const int dk0 = u * (D / 4);
     StateConsts<D, DV, DV> k;
@@ -440,7 +536,7 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
             if (ch.state_in) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    st[mt][nt][j] = ch.state_in[(size_t)(dk0 + 16 * mt + 4 * g + j) * D + 16 * nt + i16];
+                    st[mt][nt][j] = ch.state_in[(size_t)(dk0 + 16 * mt + 4 * g + j) * DC + 16 * nt + i16];
             } else {
                 st[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
@@ -448,24 +544,25 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
 
     // tile pipeline: block b lives in ring stage b % PST
     const long long rs = ch.rev ? -ROW : ROW;        // byte stride between consecutive block rows
-    const long long step = kBlock * rs;
+    const long long crs = ch.rev ? -CROW : CROW;
+    const long long step = kBlock * rs, cstep = kBlock * crs;
     const char* pa0 = ch.a + (ch.rev ? (ch.N - 1) * ROW : 0);
     const char* pb0 = ch.b + (ch.rev ? (ch.N - 1) * ROW : 0);
-    const char* pc0 = ch.c + (ch.rev ? (ch.N - 1) * ROW : 0);
+    const char* pc0 = ch.c + (ch.rev ? (ch.N - 1) * CROW : 0);
     TileDma<D> db;                                   // A and B tiles: same shape, same offsets
     TileDma<DV> dc;
     db.init(u, lane, rs);
-    dc.init(u, lane, rs);
-    constexpr int kLoads = (SO ? 1 : 2) * TileDma<D>::PER_WAVE + TileDma<DV>::PER_WAVE;   // per block, per wave
+    dc.init(u, lane, crs);
+    constexpr int kLoads = (NOA ? 1 : 2) * TileDma<D>::PER_WAVE + TileDma<DV>::PER_WAVE;   // per block, per wave
     static_assert((C::PST - 2) * kLoads <= 63, "vmcnt field");
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
     auto fetch = [&](int b, int stage) {
         b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block into a free stage
         const int valid = valid_of(b);
         const unsigned lds = lds0 + (unsigned)(stage * C::PSTAGE);
-        if constexpr (!SO) db.issue(pa0 + (long long)b * step, lds, u, valid);
-        db.issue(pb0 + (long long)b * step, lds + C::F::BYTES, u, valid);
-        dc.issue(pc0 + (long long)b * step, lds + 2 * C::F::BYTES, u, valid);
+        if constexpr (!NOA) db.issue(pa0 + (long long)b * step, lds, u, valid);
+        db.issue(pb0 + (long long)b * step, lds + C::BOFF, u, valid);
+        dc.issue(pc0 + (long long)b * cstep, lds + C::COFF, u, valid);
     };
 
     // prologue: blocks 0 .. PST-2 in flight, block 0 landed; initial state copy published
@@ -485,8 +582,8 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
             if (!ch.state_out) break;                // the last update only feeds the returned state
             if (ch.last_valid != kBlock) k.set_block_len(ch.lam, ch.last_valid, lane);
         }
-        const char* tb = smem + stage * C::PSTAGE + C::F::BYTES;
-        state_update<D, DV, DV>(st, tb, tb + C::F::BYTES, k);
+        const char* tb = smem + stage * C::PSTAGE;
+        state_update<D, DV, DV>(st, tb + C::BOFF, tb + C::COFF, k);
         if (more) {
             if constexpr (!SO) publish_state<D, DV, DV>(st, smem + C::P_SB + ((blk + 1) & 1) * C::SBYTES, k);
             wait_dma<(C::PST - 2) * kLoads>();       // block blk+1 has landed (this wave's part)
@@ -503,11 +600,11 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    ch.state_out[(size_t)(dk0 + 16 * mt + 4 * g + j) * D + 16 * nt + i16] = st[mt][nt][j];
+                    ch.state_out[(size_t)(dk0 + 16 * mt + 4 * g + j) * DC + 16 * nt + i16] = st[mt][nt][j];
     }
 }
 
-template <int D, int DV, int MODE>
+template <int D, int DV, int DC, int MODE>
 __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int wg, char* smem, unsigned lds0,
                                           int wave, int lane) {
     constexpr bool GATED = MODE == kGated;
@@ -529,55 +626,81 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
     const long long row0 = P.rev ? (pb.N - seg_start - n) : seg_start;
 
     Chain ch;
-    const size_t chain_off = ((size_t)chain * (size_t)pb.N + (size_t)row0) * D * 2;
+    const size_t first_row = (size_t)chain * (size_t)pb.N + (size_t)row0;
+    const size_t ab_off = first_row * D * 2;            // A, B: D features per token
+    const size_t chain_off = first_row * DC * 2;        // C, out (U, Y): DC features per token
     const size_t col_off = (size_t)split * DV * 2;
-    ch.a = (const char*)P.a + chain_off;
-    ch.b = (const char*)P.b + chain_off;
+    ch.a = (const char*)P.a + ab_off;
+    ch.b = (const char*)P.b + ab_off;
     ch.c = (const char*)P.c + chain_off + col_off;
     ch.out = P.out ? (char*)P.out + chain_off + col_off : nullptr;
     ch.gate = GATED ? (const char*)P.gate + chain_off : nullptr;
     ch.y = GATED ? (char*)P.gated_out + chain_off : nullptr;
     ch.eps = P.eps;
-    ch.state_in = P.state_in ? P.state_in + (size_t)vchain * D * D + (size_t)split * DV : nullptr;
-    ch.state_out = P.state_out ? P.state_out + (size_t)vchain * D * D + (size_t)split * DV : nullptr;
+    ch.state_in = P.state_in ? P.state_in + (size_t)vchain * D * DC + (size_t)split * DV : nullptr;
+    ch.state_out = P.state_out ? P.state_out + (size_t)vchain * D * DC + (size_t)split * DV : nullptr;
     ch.N = n;
     ch.T = (int)((n + kBlock - 1) / kBlock);
     ch.last_valid = (int)(n - (long long)(ch.T - 1) * kBlock);
     ch.rev = P.rev;
     ch.lam = pb.decay[chain % pb.H];
 
-    switch (wave) {
-        case 0: pass_output_wave<D, DV, 0, MODE>(ch, smem, lane); break;
-        case 1: pass_output_wave<D, DV, 1, MODE>(ch, smem, lane); break;
-        case 2: pass_output_wave<D, DV, 2, MODE>(ch, smem, lane); break;
-        case 3: pass_output_wave<D, DV, 3, MODE>(ch, smem, lane); break;
-        default: pass_state_wave<D, DV, MODE>(ch, smem, lds0, lane, wave - 4); break;
+    if constexpr (Cfg<D, DV>::AREG) {
+        static_assert(MODE == kPlain, "the register-fed layout has the plain pass only");
+        switch (wave) {
+            case 0: areg_output_wave<D, DV, DC, 0>(ch, smem, lane); break;
+            case 1: areg_output_wave<D, DV, DC, 1>(ch, smem, lane); break;
+            case 2: areg_output_wave<D, DV, DC, 2>(ch, smem, lane); break;
+            case 3: areg_output_wave<D, DV, DC, 3>(ch, smem, lane); break;
+            default: pass_state_wave<D, DV, DC, MODE>(ch, smem, lds0, lane, wave - 4); break;
+        }
+    } else {
+        switch (wave) {
+            case 0: pass_output_wave<D, DV, DC, 0, MODE>(ch, smem, lane); break;
+            case 1: pass_output_wave<D, DV, DC, 1, MODE>(ch, smem, lane); break;
+            case 2: pass_output_wave<D, DV, DC, 2, MODE>(ch, smem, lane); break;
+            case 3: pass_output_wave<D, DV, DC, 3, MODE>(ch, smem, lane); break;
+            default: pass_state_wave<D, DV, DC, MODE>(ch, smem, lds0, lane, wave - 4); break;
+        }
     }
 }
 
 // =============================================================== kernels
 
-template <int D, int DV, int MODE>
+template <int D, int DV, int MODE, int DC = D>
 __global__ __launch_bounds__(kThreads)
 void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
     __shared__ __attribute__((aligned(1024))) char smem[Cfg<D, DV>::PASS_TOTAL];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: role dispatch is a uniform branch
-    pass_body<D, DV, MODE>(pb, nsplit, blockIdx.x, smem, lds_address(smem), wave, tid & 63);
+    pass_body<D, DV, DC, MODE>(pb, nsplit, blockIdx.x, smem, lds_address(smem), wave, tid & 63);
 }
 
-template <int D, int DV, int MODE = kPlain>
+template <int D, int DV, int MODE = kPlain, int DC = D>
 hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
-    const int nsplit = D / DV;
+    static_assert(DV <= DC && DC % DV == 0, "value-column slices tile the C operand");
+    static_assert(DC == D || MODE == kPlain, "unequal widths: plain pass only");
+    const int nsplit = DC / DV;
     const long long wgs = (long long)pb.chains * pb.segs * pb.count * nsplit;
     if (wgs <= 0 || wgs > 0x7fffffffLL || pb.segs < 1) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((pass_bf16_kernel<D, DV, MODE>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
+    if (DC != D && pb.segs != 1) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((pass_bf16_kernel<D, DV, MODE, DC>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream) {
+hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream, int DC) {
+    if (DC != 0 && DC != D) {              // queries/keys and values of different widths (plain pass only)
+        if (pb.p[0].gate || pb.state_only) return hipErrorInvalidValue;
+#define LTN_BF16_DC(d, v, c) if (D == d && dv == v && DC == c) return launch_t<d, v, kPlain, c>(pb, stream)
+        LTN_BF16_DC(256, 64, 128); LTN_BF16_DC(256, 32, 128);
+        LTN_BF16_DC(128, 128, 256); LTN_BF16_DC(128, 64, 256); LTN_BF16_DC(128, 32, 256);
+        LTN_BF16_DC(128, 64, 64); LTN_BF16_DC(128, 32, 64);
+        LTN_BF16_DC(64, 64, 128); LTN_BF16_DC(64, 32, 128);
+#undef LTN_BF16_DC
+        return hipErrorInvalidValue;
+    }
     if (pb.p[0].gate) {                    // gated epilogue: one pass, complete output rows
         if (pb.count != 1 || dv != D || !pb.p[0].gated_out || pb.state_only) return hipErrorInvalidValue;
         if (D == 128) return launch_t<128, 128, kGated>(pb, stream);

@@ -24,11 +24,14 @@ __device__ __forceinline__ float4 ld4(const float* p) { return *(const float4*)p
 // GATED (full-width slices, one pass): the block's output rows are complete, so the token
 // mixer's epilogue (Sec. 3.1.2 Eq. 3 with the SimpleRMSNorm of Sec. 3.1.3 per head),
 // y = o / sqrt(mean(o^2) + eps) (.) u, is applied to them from an LDS copy.
-template <int D, int DV, int B, bool GATED>
+// A and B have D features per token; C and the output have DC (equal to D except around
+// the LRPE-d expansion of Eq. 1, where queries and keys are twice as wide as values); the
+// state is [D x DC].
+template <int D, int DV, int B, bool GATED, int DC = D>
 __global__ __launch_bounds__(kThreads)
 void pass_f32_kernel(const PassBatch pb, const int nsplit) {
-    static_assert(!GATED || DV == D, "the gated epilogue needs complete output rows");
-    static_assert(B % 16 == 0 && D % 64 == 0 && DV % 32 == 0 && DV <= D, "tile shapes");
+    static_assert(!GATED || (DV == D && DC == D), "the gated epilogue needs complete output rows");
+    static_assert(B % 16 == 0 && D % 64 == 0 && DV % 32 == 0 && DV <= DC && DC % DV == 0, "tile shapes");
     constexpr int DP = D + 4;     // row pitch of A and B tiles: 16-byte aligned rows, shifted banks
     constexpr int BP = B + 1;
     __shared__ __attribute__((aligned(16))) float As[B * DP];
@@ -50,9 +53,10 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
     const long long N = pb.N;
     const float lam = pb.decay[chain % pb.H];
 
-    const size_t chain_off = (size_t)chain * (size_t)N * D;
-    const float* Ap = (const float*)P.a + chain_off;
-    const float* Bp = (const float*)P.b + chain_off;
+    const size_t ab_off = (size_t)chain * (size_t)N * D;
+    const size_t chain_off = (size_t)chain * (size_t)N * DC;
+    const float* Ap = (const float*)P.a + ab_off;
+    const float* Bp = (const float*)P.b + ab_off;
     const float* Cp = (const float*)P.c + chain_off + (size_t)split * DV;
     float* Op = P.out ? (float*)P.out + chain_off + (size_t)split * DV : nullptr;
     const float* Up = GATED ? (const float*)P.gate + chain_off : nullptr;
@@ -77,7 +81,7 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
 #pragma unroll
         for (int b = 0; b < UC; ++b) {
             const int i = uy * UR + a, j = ux * UC + b;
-            st[a][b] = P.state_in ? P.state_in[(size_t)chain * D * D + (size_t)i * D + split * DV + j] : 0.0f;
+            st[a][b] = P.state_in ? P.state_in[(size_t)chain * D * DC + (size_t)i * DC + split * DV + j] : 0.0f;
             St[i * DV + j] = st[a][b];
         }
     __syncthreads();
@@ -98,7 +102,7 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
             const int r = e / (DV / 4), j4 = e % (DV / 4);
             const long long t = t0 + r;
             const size_t gr = (size_t)(rev ? (N - 1 - t) : t);
-            *(float4*)&Cs[r * DV + 4 * j4] = (r < len) ? ld4(Cp + gr * D + 4 * j4) : make_float4(0.f, 0.f, 0.f, 0.f);
+            *(float4*)&Cs[r * DV + 4 * j4] = (r < len) ? ld4(Cp + gr * DC + 4 * j4) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
         __syncthreads();
 
@@ -187,7 +191,7 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
                     if (r < len && Op) {
                         const long long t = t0 + r;
                         const size_t gr = (size_t)(rev ? (N - 1 - t) : t);
-                        *(float4*)(Op + gr * D + 4 * ox) = o;
+                        *(float4*)(Op + gr * DC + 4 * ox) = o;
                     }
                 }
             }
@@ -255,17 +259,17 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
 #pragma unroll
             for (int b = 0; b < UC; ++b) {
                 const int i = uy * UR + a, j = ux * UC + b;
-                P.state_out[(size_t)chain * D * D + (size_t)i * D + split * DV + j] = st[a][b];
+                P.state_out[(size_t)chain * D * DC + (size_t)i * DC + split * DV + j] = st[a][b];
             }
     }
 }
 
-template <int D, int DV, int B, bool GATED = false>
+template <int D, int DV, int B, bool GATED = false, int DC = D>
 hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
-    const int nsplit = D / DV;
+    const int nsplit = DC / DV;
     const long long wgs = (long long)pb.chains * pb.count * nsplit;
     if (wgs <= 0 || wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((pass_f32_kernel<D, DV, B, GATED>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
+    hipLaunchKernelGGL((pass_f32_kernel<D, DV, B, GATED, DC>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
     return hipGetLastError();
 }
 
@@ -277,7 +281,16 @@ __global__ void state_copy_kernel(const float* __restrict__ in, float* __restric
 
 }  // namespace
 
-hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStream_t stream) {
+hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStream_t stream, int DC) {
+    if (DC != 0 && DC != D) {              // queries/keys and values of different widths (plain pass only)
+        if (pb.p[0].gate) return hipErrorInvalidValue;
+#define LTN_F32_DC(d, v, c, b) if (D == d && dv == v && DC == c && block == b) return launch_t<d, v, b, false, c>(pb, stream)
+        LTN_F32_DC(256, 64, 128, 16); LTN_F32_DC(128, 128, 256, 16); LTN_F32_DC(128, 64, 256, 16);
+        LTN_F32_DC(128, 64, 64, 16); LTN_F32_DC(128, 64, 64, 32);
+        LTN_F32_DC(64, 128, 128, 16); LTN_F32_DC(64, 128, 128, 32); LTN_F32_DC(64, 64, 128, 16); LTN_F32_DC(64, 64, 128, 32);
+#undef LTN_F32_DC
+        return hipErrorInvalidValue;
+    }
     if (pb.p[0].gate) {                    // gated epilogue: one pass, complete output rows
         if (pb.count != 1 || dv != D || !pb.p[0].gated_out) return hipErrorInvalidValue;
 #define LTN_F32_GATED(d, b) if (D == d && block == b) return launch_t<d, d, b, true>(pb, stream)

@@ -64,6 +64,33 @@ def make_gate(Bt: int, H: int, N: int, D: int, dtype: torch.dtype, seed: int) ->
     return _randn((Bt, H, N, D), seed * 16 + 9, 1.0, dtype)
 
 
+def make_qkv_dkdv(Bt: int, H: int, N: int, Dk: int, Dv: int, dtype: torch.dtype, seed: int):
+    """Q, K ~ N(0,1)/sqrt(Dk) of shape [Bt,H,N,Dk] and V ~ N(0,1)/sqrt(Dv) of shape [Bt,H,N,Dv]."""
+    sk, sv = 1.0 / math.sqrt(Dk), 1.0 / math.sqrt(Dv)
+    return (_randn((Bt, H, N, Dk), seed * 16 + 1, sk, dtype),
+            _randn((Bt, H, N, Dk), seed * 16 + 2, sk, dtype),
+            _randn((Bt, H, N, Dv), seed * 16 + 3, sv, dtype))
+
+
+def make_preact(Bt: int, H: int, N: int, D: int, dtype: torch.dtype, seed: int, which: int = 0) -> torch.Tensor:
+    """Pre-activation query (which = 0) or key (which = 1) projections X W ~ N(0,1), shape
+    [Bt,H,N,D]: what the swish of Eq. 2 is applied to (normalised activations times a
+    variance-preserving projection)."""
+    return _randn((Bt, H, N, D), seed * 16 + 10 + which, 1.0, dtype)
+
+
+def make_theta(H: int, D: int, seed: int) -> torch.Tensor:
+    """LRPE-d angles, fp32 [H,D].  The paper only says they are learnable; these follow the
+    usual geometric ladder of rotary encodings, theta_d = 10000^(-d/D), the same for every
+    head up to a seeded +-10 % jitter standing in for what training would have moved."""
+    d = torch.arange(D, dtype=torch.float64)
+    base = torch.pow(torch.tensor(10000.0, dtype=torch.float64), -d / D)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed * 16 + 12)
+    jitter = 1.0 + 0.1 * (2.0 * torch.rand((H, D), generator=g, dtype=torch.float64) - 1.0)
+    return (base[None, :] * jitter).to(torch.float32)
+
+
 def make_step_qkv(Bt: int, H: int, D: int, dtype: torch.dtype, seed: int, step: int):
     """One decode token per (b,h): q, k, v ~ N(0,1)/sqrt(D), shape [Bt,H,D]."""
     s = 1.0 / math.sqrt(D)

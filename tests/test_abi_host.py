@@ -192,6 +192,64 @@ def test_gate_argument_errors(lib):
     assert bw(P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x4000, cf(0.0), 16, 64, 7, None) == E_UNSUP
 
 
+def test_dkdv_argument_errors(lib):
+    def f(q=P, k=P + 0x1000, v=P + 0x2000, o=P + 0x3000, decay=P + 0x4000, kv_in=None, kv_out=None,
+          Bt=1, H=2, N=256, Dk=256, Dv=128, block=0, dtype=1):
+        return lib.ltn_attn_fwd_dkdv(q, k, v, o, decay, kv_in, kv_out, Bt, H, N, Dk, Dv, block, dtype, None)
+    assert f(q=None) == E_NULL and f(o=None) == E_NULL and f(decay=None) == E_NULL
+    assert f(N=-1) == E_SHAPE and f(Dk=0) == E_SHAPE
+    assert f(Dk=128, Dv=128) == E_UNSUP            # equal widths: the plain entry points
+    assert f(Dk=256, Dv=64) == E_UNSUP and f(Dk=64, Dv=128) == E_UNSUP
+    assert f(dtype=7) == E_UNSUP
+    assert f(block=32) == E_UNSUP                  # bf16: 64 only
+    assert f(dtype=0, block=32) == E_UNSUP         # fp32 with 256-wide keys: 16 only
+    assert f(dtype=0, Dk=128, Dv=64, block=64) == E_UNSUP
+    assert f(q=P + 8) == E_ALIGN and f(kv_in=P + 4) == E_ALIGN
+    assert f(o=P) == E_UNSUP                       # output aliases q
+    assert f(q=None, k=None, v=None, o=None, N=0) == OK
+    assert f(Bt=0) == OK
+
+    def b(q=P, k=P + 0x1000, v=P + 0x2000, g=P + 0x3000, dq=P + 0x5000, dk=P + 0x6000, dv=P + 0x7000,
+          decay=P + 0x4000, Bt=1, H=2, N=256, Dk=256, Dv=128, block=0, dtype=1):
+        return lib.ltn_attn_bwd_dkdv(q, k, v, g, dq, dk, dv, decay, Bt, H, N, Dk, Dv, block, dtype, None)
+    assert b(g=None) == E_NULL and b(dk=None) == E_NULL
+    assert b(Dk=128, Dv=128) == E_UNSUP and b(N=-2) == E_SHAPE
+    assert b(dq=P) == E_UNSUP and b(dk=P + 0x7000) == E_UNSUP
+    assert b(dv=P + 0x7008) == E_ALIGN
+    assert b(N=0) == OK
+
+    def d(q=P, k=P + 0x1000, v=P + 0x2000, o=P + 0x3000, kv=P + 0x8000, decay=P + 0x4000,
+          Bt=1, H=2, S=3, Dk=256, Dv=128, dtype=1):
+        return lib.ltn_attn_decode_steps_dkdv(q, k, v, o, kv, decay, Bt, H, S, Dk, Dv, dtype, None)
+    assert d(kv=None) == E_NULL and d(S=-1) == E_SHAPE and d(Dk=128, Dv=128) == E_UNSUP
+    assert d(kv=P + 0x3000) == E_UNSUP and d(o=P + 2) == E_ALIGN
+    assert d(S=0, q=None, k=None, v=None, o=None, kv=None) == OK
+
+
+def test_prologue_argument_errors(lib):
+    def f(x=P, theta=P + 0x4000, y=P + 0x1000, act=1, Bt=1, H=2, N=100, D=128, pos0=0, dtype=1):
+        return lib.ltn_prologue_fwd(x, theta, y, act, Bt, H, N, D, pos0, dtype, None)
+    assert f(x=None) == E_NULL and f(y=None) == E_NULL
+    assert f(N=-1) == E_SHAPE and f(pos0=-1) == E_SHAPE and f(pos0=1 << 41) == E_SHAPE
+    assert f(D=96) == E_UNSUP and f(dtype=3) == E_UNSUP
+    assert f(x=P + 2) == E_ALIGN and f(theta=P + 0x4002) == E_ALIGN
+    assert f(y=P) == E_UNSUP                       # output aliases the input
+    assert f(N=0, x=None, y=None) == OK
+
+    def b(x=P, theta=P + 0x4000, dy=P + 0x1000, dx=P + 0x2000, dth=P + 0x5000, act=1, Bt=1, H=2, N=100, D=128,
+          pos0=0, dtype=1, ws=P + 0x9000, ws_bytes=1 << 20):
+        return lib.ltn_prologue_bwd(x, theta, dy, dx, dth, act, Bt, H, N, D, pos0, dtype, ws, ws_bytes, None)
+    assert b(dy=None) == E_NULL and b(dx=None) == E_NULL
+    assert b(theta=None) == E_NULL                 # an angle gradient without angles
+    assert b(ws=None) == E_NULL and b(ws_bytes=16) == E_SHAPE
+    assert b(dx=P) == E_UNSUP and b(dth=P + 0x1000) == E_UNSUP
+    assert b(dth=P + 0x5002) == E_ALIGN
+    need = lib.ltn_prologue_workspace_bytes(1, 2, 100, 128)
+    assert need == 2 * 2 * 128 * 8                 # two 64-token chunks x H x D doubles
+    assert b(ws_bytes=need - 1) == E_SHAPE
+    assert lib.ltn_prologue_workspace_bytes(1, 2, 0, 128) == 0
+
+
 def test_workspace_query(lib):
     import torch
     D = 128
