@@ -57,6 +57,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg3_7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", action="store_true")
+    ap.add_argument("--sections", default="",
+                    help="with --report: comma-separated subset of machine,shapes,gated,tiled,lrpe,decode")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one untimed 1 GiB device-to-device copy, so that a counter run "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic")
@@ -165,7 +167,7 @@ def main() -> int:
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, q, k, v, d_o, decay)
     if args.report:
-        extended_report(ltn, synth, torch, dev)
+        extended_report(ltn, synth, torch, dev, args.sections)
     print(json.dumps(out), flush=True)
     return 0
 
@@ -208,8 +210,13 @@ def cpu_baseline(w, q, k, v, d_o, decay):
     }
 
 
-def extended_report(ltn, synth, torch, dev):
+def extended_report(ltn, synth, torch, dev, sections=""):
     """Other workloads (not the bench line): printed to stderr as JSON lines."""
+    chosen = {x for x in sections.split(",") if x}
+
+    def want(name):
+        return not chosen or name in chosen
+
     def time_call(fn, n=10, warm=3):
         """Mean ms per call over n back-to-back calls (HIP events on the launch stream)."""
         for _ in range(warm):
@@ -235,136 +242,192 @@ def extended_report(ltn, synth, torch, dev):
         ts = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))
         return ts[n // 2], ts[0]
 
-    # what this machine gives: a plain 1 GiB device copy and a large bf16 GEMM (library calls, only
-    # to put the published peaks of 8 TB/s and 2.5 PFLOP/s into perspective)
-    src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
-    dst = torch.empty_like(src)
-    t_copy = time_call(lambda: dst.copy_(src), n=10, warm=3)
-    del src, dst
-    a = torch.randn(8192, 8192, device=dev, dtype=torch.float32).to(torch.bfloat16)
-    b = torch.randn(8192, 8192, device=dev, dtype=torch.float32).to(torch.bfloat16)
-    t_gemm = time_call(lambda: torch.matmul(a, b), n=10, warm=3)
-    del a, b
-    print(json.dumps({"workload": "machine", "copy_1GiB_GBs": round(2 * (1 << 30) / (t_copy * 1e-3) / 1e9, 1),
-                      "bf16_gemm_8192_TFLOPs": round(2 * 8192 ** 3 / (t_gemm * 1e-3) / 1e12, 1)}),
-          file=sys.stderr, flush=True)
-
-    shapes = [("cfg2_385m", 8, 8, 2048), ("cfg_1b", 8, 16, 2048), ("cfg3_7b", 4, 32, 8192)]
-    shapes += [(f"long_N{n}", 1, 32, n) for n in synth.LONG_CONTEXT_N]
     D = 128
-    long_times = []
-    for name, Bt, H, N in shapes:
-        q, k, v = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
-                   for _ in range(3))
-        g = torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).to(torch.bfloat16)
-        dd = synth.decay_bench_rule(H).to(dev)
-        o = torch.empty_like(q)
-        gr = tuple(torch.empty_like(q) for _ in range(3))
-        f, fmin = time_stats(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o))
-        b, bmin = time_stats(lambda: ltn.ltn_attn_bwd(q, k, v, g, dd, out=gr))
-        th = Bt * H * N
-        line = {"workload": name, "Bt": Bt, "H": H, "N": N, "fwd_ms": round(f, 4), "bwd_ms": round(b, 4),
-                "fwd_min_ms": round(fmin, 4), "bwd_min_ms": round(bmin, 4),
-                "tokens_per_s": round(Bt * N / ((f + b) * 1e-3), 1),
-                "fwd_GBs": round(4 * D * 2 * th / (f * 1e-3) / 1e9, 1),
-                "bwd_GBs": round(7 * D * 2 * th / (b * 1e-3) / 1e9, 1),
-                "F_alg_TFLOPs": round((14 * D * D + 7 * 65 * D) * th / ((f + b) * 1e-3) / 1e12, 1)}
-        if name == "cfg2_385m":
-            # its 8 tensors (268 MB) about fit the 256 MB memory-side cache: also time it cold, rotating
-            # through 8 sets of buffers so that no call finds its operands cached
-            sets = [tuple(torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).to(torch.bfloat16)
-                          for _ in range(8)) for _ in range(8)]
-            it = [0]
 
-            def cold_fwd():
-                x = sets[it[0] % 8]; it[0] += 1
-                ltn.ltn_attn_fwd(x[0], x[1], x[2], dd, out=x[4])
+    def section_machine():
+        # what this machine gives: a plain 1 GiB device copy and a large bf16 GEMM (library calls, only
+        # to put the published peaks of 8 TB/s and 2.5 PFLOP/s into perspective)
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        t_copy = time_call(lambda: dst.copy_(src), n=10, warm=3)
+        del src, dst
+        a = torch.randn(8192, 8192, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        b = torch.randn(8192, 8192, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        t_gemm = time_call(lambda: torch.matmul(a, b), n=10, warm=3)
+        del a, b
+        print(json.dumps({"workload": "machine", "copy_1GiB_GBs": round(2 * (1 << 30) / (t_copy * 1e-3) / 1e9, 1),
+                          "bf16_gemm_8192_TFLOPs": round(2 * 8192 ** 3 / (t_gemm * 1e-3) / 1e12, 1)}),
+              file=sys.stderr, flush=True)
 
-            def cold_bwd():
-                x = sets[it[0] % 8]; it[0] += 1
-                ltn.ltn_attn_bwd(x[0], x[1], x[2], x[3], dd, out=(x[5], x[6], x[7]))
-            line["fwd_cold_ms"] = round(time_stats(cold_fwd, n=24, warm=8)[0], 4)
-            line["bwd_cold_ms"] = round(time_stats(cold_bwd, n=24, warm=8)[0], 4)
-            del sets
-        print(json.dumps(line), file=sys.stderr, flush=True)
-        if name.startswith("long_"):
-            long_times.append((N, f + b))
-        del q, k, v, g, o, gr
-    # time linear in N (long context): log-log slope and doubling ratios of fwd+bwd
-    import math
-    xs = [math.log(n) for n, _ in long_times]
-    ys = [math.log(t) for _, t in long_times]
-    mx, my = sum(xs) / len(xs), sum(ys) / len(ys)
-    slope = sum((x - mx) * (y - my) for x, y in zip(xs, ys)) / sum((x - mx) ** 2 for x in xs)
-    big = [(n, t) for n, t in long_times if n >= 8192]
-    slope_big = math.log(big[-1][1] / big[0][1]) / math.log(big[-1][0] / big[0][0])
-    print(json.dumps({"workload": "long_context_linearity", "loglog_slope_all_N": round(slope, 3),
-                      "loglog_slope_N_ge_8192": round(slope_big, 3),
-                      "doubling_ratios": {str(b_[0]): round(b_[1] / a_[1], 3)
-                                          for a_, b_ in zip(long_times, long_times[1:])}}),
-          file=sys.stderr, flush=True)
-    # token mixer epilogue (gated SimpleRMSNorm): fused into the forward vs. forward + gate kernel
-    for name, Bt, H, N in (("cfg3_7b", 4, 32, 8192), ("256chains", 8, 32, 4096)):
-        q, k, v = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
-                   for _ in range(3))
-        u, g = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(2))
+
+    def section_shapes():
+        shapes = [("cfg2_385m", 8, 8, 2048), ("cfg_1b", 8, 16, 2048), ("cfg3_7b", 4, 32, 8192)]
+        shapes += [(f"long_N{n}", 1, 32, n) for n in synth.LONG_CONTEXT_N]
+        long_times = []
+        for name, Bt, H, N in shapes:
+            q, k, v = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
+                       for _ in range(3))
+            g = torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            dd = synth.decay_bench_rule(H).to(dev)
+            o = torch.empty_like(q)
+            gr = tuple(torch.empty_like(q) for _ in range(3))
+            f, fmin = time_stats(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o))
+            b, bmin = time_stats(lambda: ltn.ltn_attn_bwd(q, k, v, g, dd, out=gr))
+            th = Bt * H * N
+            line = {"workload": name, "Bt": Bt, "H": H, "N": N, "fwd_ms": round(f, 4), "bwd_ms": round(b, 4),
+                    "fwd_min_ms": round(fmin, 4), "bwd_min_ms": round(bmin, 4),
+                    "tokens_per_s": round(Bt * N / ((f + b) * 1e-3), 1),
+                    "fwd_GBs": round(4 * D * 2 * th / (f * 1e-3) / 1e9, 1),
+                    "bwd_GBs": round(7 * D * 2 * th / (b * 1e-3) / 1e9, 1),
+                    "F_alg_TFLOPs": round((14 * D * D + 7 * 65 * D) * th / ((f + b) * 1e-3) / 1e12, 1)}
+            if name == "cfg2_385m":
+                # its 8 tensors (268 MB) about fit the 256 MB memory-side cache: also time it cold, rotating
+                # through 8 sets of buffers so that no call finds its operands cached
+                sets = [tuple(torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).to(torch.bfloat16)
+                              for _ in range(8)) for _ in range(8)]
+                it = [0]
+
+                def cold_fwd():
+                    x = sets[it[0] % 8]; it[0] += 1
+                    ltn.ltn_attn_fwd(x[0], x[1], x[2], dd, out=x[4])
+
+                def cold_bwd():
+                    x = sets[it[0] % 8]; it[0] += 1
+                    ltn.ltn_attn_bwd(x[0], x[1], x[2], x[3], dd, out=(x[5], x[6], x[7]))
+                line["fwd_cold_ms"] = round(time_stats(cold_fwd, n=24, warm=8)[0], 4)
+                line["bwd_cold_ms"] = round(time_stats(cold_bwd, n=24, warm=8)[0], 4)
+                del sets
+            print(json.dumps(line), file=sys.stderr, flush=True)
+            if name.startswith("long_"):
+                long_times.append((N, f + b))
+            del q, k, v, g, o, gr
+        # time linear in N (long context): log-log slope and doubling ratios of fwd+bwd
+        import math
+        xs = [math.log(n) for n, _ in long_times]
+        ys = [math.log(t) for _, t in long_times]
+        mx, my = sum(xs) / len(xs), sum(ys) / len(ys)
+        slope = sum((x - mx) * (y - my) for x, y in zip(xs, ys)) / sum((x - mx) ** 2 for x in xs)
+        big = [(n, t) for n, t in long_times if n >= 8192]
+        slope_big = math.log(big[-1][1] / big[0][1]) / math.log(big[-1][0] / big[0][0])
+        print(json.dumps({"workload": "long_context_linearity", "loglog_slope_all_N": round(slope, 3),
+                          "loglog_slope_N_ge_8192": round(slope_big, 3),
+                          "doubling_ratios": {str(b_[0]): round(b_[1] / a_[1], 3)
+                                              for a_, b_ in zip(long_times, long_times[1:])}}),
+              file=sys.stderr, flush=True)
+
+    def section_gated():
+        # token mixer epilogue (gated SimpleRMSNorm): fused into the forward vs. forward + gate kernel
+        for name, Bt, H, N in (("cfg3_7b", 4, 32, 8192), ("256chains", 8, 32, 4096)):
+            q, k, v = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
+                       for _ in range(3))
+            u, g = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(2))
+            dd = synth.decay_bench_rule(H).to(dev)
+            o, y, dx, du = (torch.empty_like(q) for _ in range(4))
+            th = Bt * H * N
+            unit = D * 2 * th                      # bytes of one tensor
+            t_plain = time_call(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o))
+            t_gate = time_call(lambda: ltn.ltn_gate_fwd(o, u, 1e-6, out=y))
+            t_inf = time_call(lambda: ltn.ltn_attn_fwd_gated(q, k, v, u, dd, eps=1e-6, store_o=False, y_out=y))
+            t_trn = time_call(lambda: ltn.ltn_attn_fwd_gated(q, k, v, u, dd, eps=1e-6, out=o, y_out=y))
+            t_gbwd = time_call(lambda: ltn.ltn_gate_bwd(o, u, g, 1e-6, out=(dx, du)))
+            print(json.dumps({"workload": "gated_" + name, "Bt": Bt, "H": H, "N": N,
+                              "fwd_plain_ms": round(t_plain, 4), "gate_fwd_ms": round(t_gate, 4),
+                              "unfused_ms": round(t_plain + t_gate, 4),
+                              "fused_inference_ms": round(t_inf, 4), "fused_training_ms": round(t_trn, 4),
+                              "gate_bwd_ms": round(t_gbwd, 4),
+                              "gate_fwd_GBs": round(3 * unit / (t_gate * 1e-3) / 1e9, 1),
+                              "gate_bwd_GBs": round(5 * unit / (t_gbwd * 1e-3) / 1e9, 1),
+                              "fused_inference_GBs": round(5 * unit / (t_inf * 1e-3) / 1e9, 1),
+                              "fused_training_GBs": round(6 * unit / (t_trn * 1e-3) / 1e9, 1)}),
+                  file=sys.stderr, flush=True)
+            del q, k, v, u, g, o, y, dx, du
+
+    def section_tiled():
+        # the paper's quadratic tiling (App. B Algorithm 3) against the state recurrence, forward only
+        Bt, H = 4, 32
         dd = synth.decay_bench_rule(H).to(dev)
-        o, y, dx, du = (torch.empty_like(q) for _ in range(4))
-        th = Bt * H * N
-        unit = D * 2 * th                      # bytes of one tensor
-        t_plain = time_call(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o))
-        t_gate = time_call(lambda: ltn.ltn_gate_fwd(o, u, 1e-6, out=y))
-        t_inf = time_call(lambda: ltn.ltn_attn_fwd_gated(q, k, v, u, dd, eps=1e-6, store_o=False, y_out=y))
-        t_trn = time_call(lambda: ltn.ltn_attn_fwd_gated(q, k, v, u, dd, eps=1e-6, out=o, y_out=y))
-        t_gbwd = time_call(lambda: ltn.ltn_gate_bwd(o, u, g, 1e-6, out=(dx, du)))
-        print(json.dumps({"workload": "gated_" + name, "Bt": Bt, "H": H, "N": N,
-                          "fwd_plain_ms": round(t_plain, 4), "gate_fwd_ms": round(t_gate, 4),
-                          "unfused_ms": round(t_plain + t_gate, 4),
-                          "fused_inference_ms": round(t_inf, 4), "fused_training_ms": round(t_trn, 4),
-                          "gate_bwd_ms": round(t_gbwd, 4),
-                          "gate_fwd_GBs": round(3 * unit / (t_gate * 1e-3) / 1e9, 1),
-                          "gate_bwd_GBs": round(5 * unit / (t_gbwd * 1e-3) / 1e9, 1),
-                          "fused_inference_GBs": round(5 * unit / (t_inf * 1e-3) / 1e9, 1),
-                          "fused_training_GBs": round(6 * unit / (t_trn * 1e-3) / 1e9, 1)}),
-              file=sys.stderr, flush=True)
-        del q, k, v, u, g, o, y, dx, du
-    # the paper's quadratic tiling (App. B Algorithm 3) against the state recurrence, forward only
-    Bt, H = 4, 32
-    dd = synth.decay_bench_rule(H).to(dev)
-    for N in (128, 256, 512, 1024, 2048, 4096, 8192):
-        q, k, v = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
-                   for _ in range(3))
-        o = torch.empty_like(q)
-        t_rec = time_call(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o), n=20, warm=5)
-        t_til = time_call(lambda: ltn.ltn_attn_fwd_tiled(q, k, v, dd, out=o), n=5 if N >= 4096 else 20, warm=2)
-        T = N // 64
-        tile_pairs = Bt * H * T * (T + 1) // 2
-        print(json.dumps({"workload": "tiled_vs_recurrence", "Bt": Bt, "H": H, "N": N,
-                          "recurrence_ms": round(t_rec, 4), "tiled_ms": round(t_til, 4),
-                          "tiled_over_recurrence": round(t_til / t_rec, 2),
-                          "tiled_TFLOPs_full_tiles": round(tile_pairs * 4 * 64 * 64 * D / (t_til * 1e-3) / 1e12, 1)}),
-              file=sys.stderr, flush=True)
-        del q, k, v, o
-    c = synth.DECODE
-    Bt, H = c["Bt"], c["H"]
-    dd = synth.decay_bench_rule(H).to(dev)
-    qp, kp, vp = (torch.randn(Bt, H, c["prefix"], D, device=dev).div_(D ** 0.5).to(torch.bfloat16) for _ in range(3))
-    _, kv = ltn.ltn_attn_fwd(qp, kp, vp, dd, return_state=True)      # state after a 1024-token prefix
-    del qp, kp, vp
-    q1, k1, v1 = (torch.randn(Bt, H, D, device=dev).div_(D ** 0.5).to(torch.bfloat16) for _ in range(3))
-    o1 = torch.empty_like(q1)
-    t = time_call(lambda: ltn.ltn_attn_decode_step(q1, k1, v1, kv, dd, out=o1), n=512, warm=20)
-    print(json.dumps({"workload": "decode_cfg5", "Bt": Bt, "H": H, "us_per_step": round(t * 1e3, 2),
-                      "state_GBs": round(2 * Bt * H * D * D * 4 / (t * 1e-3) / 1e9, 1),
-                      "batch_tokens_per_s": round(Bt / (t * 1e-3), 1)}), file=sys.stderr, flush=True)
-    for S in (4, 16):                          # several tokens per call: the state moves once per call
-        qs, ks, vs = (torch.randn(Bt, H, S, D, device=dev).to(torch.bfloat16) for _ in range(3))
-        os_ = torch.empty_like(qs)
-        t = time_call(lambda: ltn.ltn_attn_decode_steps(qs, ks, vs, kv, dd, out=os_), n=256, warm=20)
-        print(json.dumps({"workload": f"decode_cfg5_{S}_tokens_per_call", "Bt": Bt, "H": H, "S": S,
-                          "us_per_call": round(t * 1e3, 2), "us_per_token": round(t * 1e3 / S, 2),
+        for N in (128, 256, 512, 1024, 2048, 4096, 8192):
+            q, k, v = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
+                       for _ in range(3))
+            o = torch.empty_like(q)
+            t_rec = time_call(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o), n=20, warm=5)
+            t_til = time_call(lambda: ltn.ltn_attn_fwd_tiled(q, k, v, dd, out=o), n=5 if N >= 4096 else 20, warm=2)
+            T = N // 64
+            tile_pairs = Bt * H * T * (T + 1) // 2
+            print(json.dumps({"workload": "tiled_vs_recurrence", "Bt": Bt, "H": H, "N": N,
+                              "recurrence_ms": round(t_rec, 4), "tiled_ms": round(t_til, 4),
+                              "tiled_over_recurrence": round(t_til / t_rec, 2),
+                              "tiled_TFLOPs_full_tiles": round(tile_pairs * 4 * 64 * 64 * D / (t_til * 1e-3) / 1e12, 1)}),
+                  file=sys.stderr, flush=True)
+            del q, k, v, o
+
+    def section_lrpe():
+        # first layer: swish + LRPE-d expansion of queries and keys (Eq. 1, Eq. 2), then the attention with
+        # 2D-wide queries and keys; `unit` = bytes of one [Bt,H,N,D] bf16 tensor
+        for name, Bt, H, N in (("cfg3_7b", 4, 32, 8192), ("cfg2_385m", 8, 8, 2048)):
+            xq, xk, g = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
+            v = torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
+            th_ = synth.make_theta(H, D, 1).to(dev)
+            dd = synth.decay_bench_rule(H).to(dev)
+            qe, ke = ltn.ltn_prologue_fwd(xq, th_), ltn.ltn_prologue_fwd(xk, th_)
+            z, o = torch.empty_like(xq), torch.empty_like(v)
+            unit = D * 2 * Bt * H * N
+            t_sw = time_call(lambda: ltn.ltn_prologue_fwd(xq, None, out=z), n=20, warm=5)
+            t_pf = time_call(lambda: ltn.ltn_prologue_fwd(xq, th_, out=qe), n=20, warm=5)
+            t_f = time_call(lambda: ltn.ltn_attn_fwd_dkdv(qe, ke, v, dd, out=o), n=20, warm=5)
+            t_b = time_call(lambda: ltn.ltn_attn_bwd_dkdv(qe, ke, v, g, dd), n=20, warm=5)
+            dqe = torch.randn_like(qe)
+            t_pb = time_call(lambda: ltn.ltn_prologue_bwd(xq, dqe, th_), n=20, warm=5)
+            t_plain_f = time_call(lambda: ltn.ltn_attn_fwd(xq, xk, v, dd, out=o), n=20, warm=5)
+            t_plain_b = time_call(lambda: ltn.ltn_attn_bwd(xq, xk, v, g, dd), n=20, warm=5)
+            print(json.dumps({"workload": "lrpe_first_layer_" + name, "Bt": Bt, "H": H, "N": N, "D": D,
+                              "swish_only_ms": round(t_sw, 4), "swish_only_GBs": round(2 * unit / (t_sw * 1e-3) / 1e9, 1),
+                              "prologue_fwd_ms": round(t_pf, 4), "prologue_fwd_GBs": round(3 * unit / (t_pf * 1e-3) / 1e9, 1),
+                              "prologue_bwd_ms": round(t_pb, 4), "prologue_bwd_GBs": round(4 * unit / (t_pb * 1e-3) / 1e9, 1),
+                              "attn_fwd_ms": round(t_f, 4), "attn_fwd_GBs": round(6 * unit / (t_f * 1e-3) / 1e9, 1),
+                              "attn_bwd_ms": round(t_b, 4), "attn_bwd_GBs_each_tensor_once": round(11 * unit / (t_b * 1e-3) / 1e9, 1),
+                              "layer_fwd_ms": round(2 * t_pf + t_f, 4), "layer_bwd_ms": round(2 * t_pb + t_b, 4),
+                              "plain_attn_fwd_ms": round(t_plain_f, 4), "plain_attn_bwd_ms": round(t_plain_b, 4)}),
+                  file=sys.stderr, flush=True)
+            del xq, xk, g, v, qe, ke, z, o, dqe
+
+    def section_decode():
+        c = synth.DECODE
+        Bt, H = c["Bt"], c["H"]
+        dd = synth.decay_bench_rule(H).to(dev)
+        kv2 = torch.randn(Bt, H, 2 * D, D, device=dev)                   # decode behind the expansion: 256 x 128 states
+        q2, k2 = (torch.randn(Bt, H, 1, 2 * D, device=dev).div_(D ** 0.5).to(torch.bfloat16) for _ in range(2))
+        v2 = torch.randn(Bt, H, 1, D, device=dev).to(torch.bfloat16)
+        o2 = torch.empty_like(v2)
+        t = time_call(lambda: ltn.ltn_attn_decode_steps_dkdv(q2, k2, v2, kv2, dd, out=o2), n=256, warm=20)
+        print(json.dumps({"workload": "decode_cfg5_lrpe_first_layer", "Bt": Bt, "H": H, "Dk": 2 * D, "Dv": D,
+                          "us_per_step": round(t * 1e3, 2),
+                          "state_GBs": round(2 * Bt * H * 2 * D * D * 4 / (t * 1e-3) / 1e9, 1)}), file=sys.stderr, flush=True)
+        del kv2, q2, k2, v2, o2
+        qp, kp, vp = (torch.randn(Bt, H, c["prefix"], D, device=dev).div_(D ** 0.5).to(torch.bfloat16) for _ in range(3))
+        _, kv = ltn.ltn_attn_fwd(qp, kp, vp, dd, return_state=True)      # state after a 1024-token prefix
+        del qp, kp, vp
+        q1, k1, v1 = (torch.randn(Bt, H, D, device=dev).div_(D ** 0.5).to(torch.bfloat16) for _ in range(3))
+        o1 = torch.empty_like(q1)
+        t = time_call(lambda: ltn.ltn_attn_decode_step(q1, k1, v1, kv, dd, out=o1), n=512, warm=20)
+        print(json.dumps({"workload": "decode_cfg5", "Bt": Bt, "H": H, "us_per_step": round(t * 1e3, 2),
                           "state_GBs": round(2 * Bt * H * D * D * 4 / (t * 1e-3) / 1e9, 1),
-                          "batch_tokens_per_s": round(Bt * S / (t * 1e-3), 1)}), file=sys.stderr, flush=True)
+                          "batch_tokens_per_s": round(Bt / (t * 1e-3), 1)}), file=sys.stderr, flush=True)
+        for S in (4, 16):                          # several tokens per call: the state moves once per call
+            qs, ks, vs = (torch.randn(Bt, H, S, D, device=dev).to(torch.bfloat16) for _ in range(3))
+            os_ = torch.empty_like(qs)
+            t = time_call(lambda: ltn.ltn_attn_decode_steps(qs, ks, vs, kv, dd, out=os_), n=256, warm=20)
+            print(json.dumps({"workload": f"decode_cfg5_{S}_tokens_per_call", "Bt": Bt, "H": H, "S": S,
+                              "us_per_call": round(t * 1e3, 2), "us_per_token": round(t * 1e3 / S, 2),
+                              "state_GBs": round(2 * Bt * H * D * D * 4 / (t * 1e-3) / 1e9, 1),
+                              "batch_tokens_per_s": round(Bt * S / (t * 1e-3), 1)}), file=sys.stderr, flush=True)
+
+    for name, fn in (("machine", section_machine), ("shapes", section_shapes), ("gated", section_gated),
+                     ("tiled", section_tiled), ("lrpe", section_lrpe), ("decode", section_decode)):
+        if want(name):
+            fn()
+
+
 
 
 if __name__ == "__main__":
