@@ -34,7 +34,9 @@
  *     non-negative powers of lambda are ever formed, so lambda = 0 and
  *     lambda = 1 are exact and strong decays cannot overflow (the failure mode
  *     Sec. 3.3 describes for the factorised form of Algorithm 1).
- *   - Supported shapes: D in {64, 128}; N >= 0 arbitrary (a short last block
+ *   - Supported shapes: D in {64, 128, 256} for ltn_attn_fwd, ltn_attn_bwd and the
+ *     decode steps (D in {64, 128} for the gated forward, the gate kernels and the
+ *     tiled comparison kernel); N >= 0 arbitrary (a short last block
  *     is handled on chip; the paper's listings assume block | N).
  *     `block` is the intra-block tile length: 0 lets the library choose
  *     (ltn_attn_pick_block); bf16 supports 64; fp32 supports 16, 32 and 64

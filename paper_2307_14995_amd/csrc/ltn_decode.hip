@@ -114,7 +114,7 @@ hipError_t launch_decode(const void* q, const void* k, const void* v, void* o, f
         else hipLaunchKernelGGL((decode_kernel<dk, dv, false>), grid, block, 0, stream, q, k, v, o, kv, decay, H, steps);         \
         return hipGetLastError();                                                                       \
     }
-    LTN_DECODE(128, 128) LTN_DECODE(64, 64) LTN_DECODE(256, 128) LTN_DECODE(128, 64)
+    LTN_DECODE(128, 128) LTN_DECODE(64, 64) LTN_DECODE(256, 256) LTN_DECODE(256, 128) LTN_DECODE(128, 64)
 #undef LTN_DECODE
     return hipErrorInvalidValue;
 }

@@ -713,6 +713,8 @@ hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stre
         if (D == 64 && dv == 64) return launch_t<64, 64, kStateOnly>(pb, stream);
         return hipErrorInvalidValue;
     }
+    if (D == 256 && dv == 64) return launch_t<256, 64>(pb, stream);
+    if (D == 256 && dv == 32) return launch_t<256, 32>(pb, stream);
     if (D == 128 && dv == 128) return launch_t<128, 128>(pb, stream);
     if (D == 128 && dv == 64) return launch_t<128, 64>(pb, stream);
     if (D == 128 && dv == 32) return launch_t<128, 32>(pb, stream);

@@ -304,6 +304,7 @@ hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStr
     LTN_F32_CASE(64, 32, 16); LTN_F32_CASE(64, 32, 32); LTN_F32_CASE(64, 32, 64);
     LTN_F32_CASE(128, 128, 16); LTN_F32_CASE(128, 128, 32);
     LTN_F32_CASE(128, 64, 16); LTN_F32_CASE(128, 64, 32);
+    LTN_F32_CASE(256, 64, 16);
 #undef LTN_F32_CASE
     return hipErrorInvalidValue;
 }

@@ -50,6 +50,9 @@ def test_pick_block_and_workspace(lib):
     assert ltn.ltn_attn_pick_block(64, torch.float32) == 64
     assert ltn.ltn_attn_pick_block(128, torch.float32) == 32
     assert ltn.ltn_attn_pick_block(96, torch.bfloat16) == 0
+    assert ltn.ltn_attn_pick_block(256, torch.bfloat16) == 64
+    assert ltn.ltn_attn_pick_block(256, torch.float32) == 16
+    assert ltn.ltn_attn_workspace_bytes(1, 32, 65536, 256, 0, torch.bfloat16, 0) == 0   # 256-wide heads: no segments
     assert ltn.ltn_attn_workspace_bytes(4, 32, 8192, 128, 0, torch.bfloat16, 1) == 0
 
 
@@ -78,7 +81,9 @@ def test_fwd_argument_errors(lib):
     assert fwd(lib, N=-1) == E_SHAPE
     assert fwd(lib, Bt=-1) == E_SHAPE
     assert fwd(lib, D=96) == E_UNSUP
-    assert fwd(lib, D=256) == E_UNSUP
+    assert fwd(lib, D=512) == E_UNSUP
+    assert fwd(lib, D=256, block=32, dtype=0) == E_UNSUP   # fp32, D = 256: block 16 only
+    assert fwd(lib, D=256, block=32) == E_UNSUP             # bf16: block 64 only
     assert fwd(lib, dtype=7) == E_UNSUP
     assert fwd(lib, block=48) == E_UNSUP
     assert fwd(lib, block=32, dtype=1) == E_UNSUP          # bf16 supports block 64 only
@@ -154,6 +159,7 @@ def test_fwd_gated_argument_errors(lib):
     assert call(eps=-1.0) == E_SHAPE
     assert call(eps=float("nan")) == E_SHAPE
     assert call(D=96) == E_UNSUP
+    assert call(D=256) == E_UNSUP                          # complete 256-wide rows do not fit a workgroup
     assert call(y=P + 0x3000) == E_UNSUP                   # y aliases the gate
     assert call(y=P + 0x5000) == E_UNSUP                   # y aliases o
     assert call(u=P + 0x3008) == E_ALIGN
