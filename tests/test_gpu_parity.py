@@ -351,17 +351,19 @@ def test_long_context_linear_time_and_parity():
         q, k, v = synth.make_qkv(1, H, N, D, torch.bfloat16, synth.LONG_CONTEXT_SEED)
         g = synth.make_do(1, H, N, D, torch.bfloat16, synth.LONG_CONTEXT_SEED)
         qd, kd, vd, gd, dd = gpu(q, k, v, g, decay)
-        for _ in range(2):
+        for _ in range(5):
             o = ltn.ltn_attn_fwd(qd, kd, vd, dd)
             grads = ltn.ltn_attn_bwd(qd, kd, vd, gd, dd)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(3):
+        # the fastest of several steps: clock ramps and other tenants of the box only add time
+        n_it = 12
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_it + 1)]
+        for i in range(n_it):
+            ev[i].record()
             o = ltn.ltn_attn_fwd(qd, kd, vd, dd)
             grads = ltn.ltn_attn_bwd(qd, kd, vd, gd, dd)
-        e1.record()
+        ev[n_it].record()
         torch.cuda.synchronize()
-        times[N] = e0.elapsed_time(e1) / 3
+        times[N] = min(ev[i].elapsed_time(ev[i + 1]) for i in range(n_it))
         if N == 65536:
             for h in (0, 31):
                 sl = (slice(0, 1), slice(h, h + 1))
