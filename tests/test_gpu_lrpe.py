@@ -297,3 +297,51 @@ def test_lrpe_training_chain_gradients(dtype):
     check("dxq", dxq, dxq_r, tol)
     check("dxk", dxk, dxk_r, tol)
     assert orc.rel_l2(dthq + dthk, dthq_r + dthk_r) <= tol
+
+
+def test_first_layer_chain_on_a_side_stream_and_in_a_graph():
+    """The first-layer chain (expansion, attention, gradients, the expansion's derivative) is
+    enqueued on the caller's stream and can be captured: replays with fresh inputs, with eager
+    work in between, give the eager results bit for bit (no atomics, no memset nodes)."""
+    Bt, H, N, D = 2, 4, 200, 128
+    dtype = torch.bfloat16
+    dd, th = gpu(synth.decay_bench_rule(H), synth.make_theta(H, D, 680))
+    xq, xk, v, g = (torch.empty(Bt, H, N, D, dtype=dtype, device=dev()) for _ in range(4))
+
+    def fill(seed):
+        xq.copy_(synth.make_preact(Bt, H, N, D, dtype, seed, 0).to(dev()))
+        xk.copy_(synth.make_preact(Bt, H, N, D, dtype, seed, 1).to(dev()))
+        v.copy_(synth.make_qkv(Bt, H, N, D, dtype, seed)[2].to(dev()))
+        g.copy_(synth.make_do(Bt, H, N, D, dtype, seed).to(dev()))
+
+    def chain():
+        qe, ke = ltn.ltn_prologue_fwd(xq, th, pos0=7), ltn.ltn_prologue_fwd(xk, th, pos0=7)
+        o = ltn.ltn_attn_fwd_dkdv(qe, ke, v, dd)
+        dqe, dke, dv = ltn.ltn_attn_bwd_dkdv(qe, ke, v, g, dd)
+        dxq, dthq = ltn.ltn_prologue_bwd(xq, dqe, th, pos0=7)
+        dxk, dthk = ltn.ltn_prologue_bwd(xk, dke, th, pos0=7)
+        return [o, dv, dxq, dxk, dthq, dthk]
+
+    fill(1)
+    ref = chain()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        on_side = chain()
+    side.synchronize()
+    for a, b in zip(on_side, ref):
+        assert torch.equal(a, b)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        outs = chain()
+    for seed in (2, 3, 4):
+        fill(seed)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [x.clone() for x in outs]
+        want = chain()                                   # eager, between replays
+        torch.cuda.synchronize()
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), seed
