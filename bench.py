@@ -58,7 +58,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", action="store_true")
     ap.add_argument("--sections", default="",
-                    help="with --report: comma-separated subset of machine,shapes,gated,tiled,lrpe,d256,decode")
+                    help="with --report: comma-separated subset of machine,shapes,gated,tiled,lrpe,dims,decode")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one untimed 1 GiB device-to-device copy, so that a counter run "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic")
@@ -391,23 +391,24 @@ def extended_report(ltn, synth, torch, dev, sections=""):
                   file=sys.stderr, flush=True)
             del xq, xk, g, v, qe, ke, z, o, dqe
 
-    def section_d256():
-        # heads of 256 features at the 7B model width (16 heads x 256 = 32 x 128)
-        Bt, H, N, D2 = 4, 16, 8192, 256
-        q, k, v = (torch.randn(Bt, H, N, D2, device=dev, dtype=torch.float32).div_(D2 ** 0.5).to(torch.bfloat16)
-                   for _ in range(3))
-        g = torch.randn(Bt, H, N, D2, device=dev, dtype=torch.float32).to(torch.bfloat16)
-        dd = synth.decay_bench_rule(H).to(dev)
-        o = torch.empty_like(q)
-        gr = tuple(torch.empty_like(q) for _ in range(3))
-        f, fmin = time_stats(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o))
-        b, bmin = time_stats(lambda: ltn.ltn_attn_bwd(q, k, v, g, dd, out=gr))
-        unit = D2 * 2 * Bt * H * N
-        print(json.dumps({"workload": "d256_7b_width", "Bt": Bt, "H": H, "N": N, "D": D2,
-                          "fwd_ms": round(f, 4), "bwd_ms": round(b, 4), "fwd_min_ms": round(fmin, 4),
-                          "bwd_min_ms": round(bmin, 4), "tokens_per_s": round(Bt * N / ((f + b) * 1e-3), 1),
-                          "fwd_GBs": round(4 * unit / (f * 1e-3) / 1e9, 1),
-                          "bwd_GBs": round(7 * unit / (b * 1e-3) / 1e9, 1)}), file=sys.stderr, flush=True)
+    def section_dims():
+        # other head dims: 256 features at the 7B model width (16 heads x 256 = 32 x 128), and 96
+        for name, Bt, H, N, Dh in (("d256_7b_width", 4, 16, 8192, 256), ("d96_32_heads", 4, 32, 8192, 96)):
+            q, k, v = (torch.randn(Bt, H, N, Dh, device=dev, dtype=torch.float32).div_(Dh ** 0.5).to(torch.bfloat16)
+                       for _ in range(3))
+            g = torch.randn(Bt, H, N, Dh, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            dd = synth.decay_bench_rule(H).to(dev)
+            o = torch.empty_like(q)
+            gr = tuple(torch.empty_like(q) for _ in range(3))
+            f, fmin = time_stats(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o))
+            b, bmin = time_stats(lambda: ltn.ltn_attn_bwd(q, k, v, g, dd, out=gr))
+            unit = Dh * 2 * Bt * H * N
+            print(json.dumps({"workload": name, "Bt": Bt, "H": H, "N": N, "D": Dh,
+                              "fwd_ms": round(f, 4), "bwd_ms": round(b, 4), "fwd_min_ms": round(fmin, 4),
+                              "bwd_min_ms": round(bmin, 4), "tokens_per_s": round(Bt * N / ((f + b) * 1e-3), 1),
+                              "fwd_GBs": round(4 * unit / (f * 1e-3) / 1e9, 1),
+                              "bwd_GBs": round(7 * unit / (b * 1e-3) / 1e9, 1)}), file=sys.stderr, flush=True)
+            del q, k, v, g, o, gr
 
     def section_decode():
         c = synth.DECODE
@@ -441,7 +442,7 @@ def extended_report(ltn, synth, torch, dev, sections=""):
                               "batch_tokens_per_s": round(Bt * S / (t * 1e-3), 1)}), file=sys.stderr, flush=True)
 
     for name, fn in (("machine", section_machine), ("shapes", section_shapes), ("gated", section_gated),
-                     ("tiled", section_tiled), ("lrpe", section_lrpe), ("d256", section_d256),
+                     ("tiled", section_tiled), ("lrpe", section_lrpe), ("dims", section_dims),
                      ("decode", section_decode)):
         if want(name):
             fn()

@@ -34,13 +34,14 @@
  *     non-negative powers of lambda are ever formed, so lambda = 0 and
  *     lambda = 1 are exact and strong decays cannot overflow (the failure mode
  *     Sec. 3.3 describes for the factorised form of Algorithm 1).
- *   - Supported shapes: D in {64, 128, 256} for ltn_attn_fwd, ltn_attn_bwd and the
+ *   - Supported shapes: D in {64, 96, 128, 256} for ltn_attn_fwd, ltn_attn_bwd and the
  *     decode steps (D in {64, 128} for the gated forward, the gate kernels and the
  *     tiled comparison kernel); N >= 0 arbitrary (a short last block
  *     is handled on chip; the paper's listings assume block | N).
  *     `block` is the intra-block tile length: 0 lets the library choose
  *     (ltn_attn_pick_block); bf16 supports 64; fp32 supports 16, 32 and 64
- *     with D * block <= 4096.
+ *     with D * block <= 4096 (D = 96 counts as 128 there: its tiles are 128 wide
+ *     on chip, the last columns zero).
  *   - Results are bitwise reproducible run to run for fixed arguments (no
  *     floating-point atomics).
  */

@@ -18,6 +18,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // full width (fewest re-reads).  Measured on MI355X for 8..256 chains, forward and
 // backward.  LTN_ATTN_DV (debug, used by the parity tests) overrides the choice.
 int pick_dv(long long chain_passes, int D, ltn_dtype dtype) {
+    if (D == 96) return 32;                // three 32-column slices (the kernels exist for those only)
     // D = 256: the state copies of more than 64 columns do not fit the LDS
     const int hi = (D == 256) ? 64 : D;
     const int lo = (dtype == LTN_BF16) ? 32 : (D == 256 ? 64 : D / 2);
@@ -41,13 +42,13 @@ int pick_dv_range(long long chain_passes, int DC, int lo, int hi) {
 ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype dtype, int* blk_out) {
     if (Bt < 0 || H < 0 || N < 0 || D <= 0 || block < 0) return LTN_ERR_SHAPE;
     if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
-    if (D != 64 && D != 128 && D != 256) return LTN_ERR_UNSUPPORTED;
+    if (D != 64 && D != 96 && D != 128 && D != 256) return LTN_ERR_UNSUPPORTED;
     const int blk = block ? block : ltn_attn_pick_block(D, dtype);
     if (dtype == LTN_BF16) {
         if (blk != 64) return LTN_ERR_UNSUPPORTED;
     } else {
         if (blk != 16 && blk != 32 && blk != 64) return LTN_ERR_UNSUPPORTED;
-        if ((long long)D * blk > 4096) return LTN_ERR_UNSUPPORTED;
+        if ((long long)(D == 96 ? 128 : D) * blk > 4096) return LTN_ERR_UNSUPPORTED;   // 96 is computed as 128
     }
     if ((long long)Bt * H > 0x3fffffffLL) return LTN_ERR_SHAPE;
     *blk_out = blk;
@@ -68,7 +69,7 @@ constexpr long long kMinSegsFullWidth = 4;   // measured: 2 segments lose to one
 SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtype, bool full_width = false) {
     SegPlan plan = {1, 0};
     if (dtype != LTN_BF16 || chain_passes <= 0 || N <= 64) return plan;
-    if (D == 256) return plan;             // no state-only sweep for 256-wide heads
+    if (D == 256 || D == 96) return plan;  // no state-only sweep for these widths
     long long want = 256 / chain_passes;
     if (want > N / 1024) want = N / 1024;
     // a pass that must keep full-width slices has no column split to fall back on
@@ -138,15 +139,15 @@ ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void*
 extern "C" {
 
 int ltn_attn_pick_block(int D, ltn_dtype dtype) {
-    if (D != 64 && D != 128 && D != 256) return 0;
+    if (D != 64 && D != 96 && D != 128 && D != 256) return 0;
     if (dtype == LTN_BF16) return 64;
-    if (dtype == LTN_F32) return D == 64 ? 64 : (D == 128 ? 32 : 16);
+    if (dtype == LTN_F32) return D == 64 ? 64 : (D == 256 ? 16 : 32);
     return 0;
 }
 
 size_t ltn_attn_workspace_bytes(int Bt, int H, long long N, int D, int block, ltn_dtype dtype, int call) {
     (void)block;
-    if (Bt <= 0 || H <= 0 || N <= 0 || (D != 64 && D != 128 && D != 256) || call < 0 || call > 2) return 0;
+    if (Bt <= 0 || H <= 0 || N <= 0 || (D != 64 && D != 96 && D != 128 && D != 256) || call < 0 || call > 2) return 0;
     const long long chains = (long long)Bt * H;
     const int count = (call == 1) ? 3 : 1;
     const SegPlan plan = pick_segments(chains * count, N, D, dtype, call == 2);
@@ -186,7 +187,7 @@ static ltn_status fwd_common(const void* q, const void* k, const void* v, const 
     const ltn_status cs = check_common(Bt, H, N, D, block, dtype, &blk);
     if (cs != LTN_OK) return cs;
     if (gated && !(eps >= 0.0f)) return LTN_ERR_SHAPE;
-    if (gated && D == 256) return LTN_ERR_UNSUPPORTED;   // complete 256-wide output rows do not fit a workgroup
+    if (gated && (D == 256 || D == 96)) return LTN_ERR_UNSUPPORTED;   // no kernel with complete output rows of these widths
     if (workspace_bytes < ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, gated ? 2 : 0)) return LTN_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(u) || !aligned16(y) ||
         !aligned16(kv_in) || !aligned16(kv_out) || !aligned16(workspace) ||
@@ -344,7 +345,7 @@ ltn_status ltn_attn_decode_steps(const void* q, const void* k, const void* v, vo
     if (!decay || (!empty && (!q || !k || !v || !o || !kv))) return LTN_ERR_NULL;
     if (Bt < 0 || H < 0 || S < 0 || D <= 0) return LTN_ERR_SHAPE;
     if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
-    if (D != 64 && D != 128 && D != 256) return LTN_ERR_UNSUPPORTED;
+    if (D != 64 && D != 96 && D != 128 && D != 256) return LTN_ERR_UNSUPPORTED;
     if ((long long)Bt * H > 0x3fffffffLL) return LTN_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(kv) ||
         (reinterpret_cast<uintptr_t>(decay) & 3u))

@@ -80,9 +80,12 @@ struct Swz {
 // Wave u issues the wave-wide loads j = u, u+4, ...; load j fills LDS slots 64j .. 64j+63
 // (slot s = row s / CPR, chunk position s % CPR).  `src[i]` is this lane's byte offset
 // from the block's first row for its i-th load; `row[i]` the tile row it fetches.
-template <int COLS>
+// REAL < COLS: the tensor's rows hold only REAL features; the tile's remaining columns are
+// filled with zeros (a row index of kBlock marks such a slot: it is never below `valid`).
+template <int COLS, int REAL = COLS>
 struct TileDma {
     static_assert(Swz<COLS>::NI % 4 == 0, "every state wave issues the same number of loads");
+    static_assert(REAL % 8 == 0 && REAL <= COLS, "whole 16-byte chunks");
     static constexpr int PER_WAVE = Swz<COLS>::NI / 4;
     long long src[PER_WAVE];
     int row[PER_WAVE];
@@ -93,7 +96,7 @@ struct TileDma {
             const int slot = 64 * (u + 4 * i) + lane;
             const int r = slot / S::CPR;
             const int c = (slot % S::CPR) ^ S::key(r);
-            row[i] = r;
+            row[i] = (REAL < COLS && c * 8 >= REAL) ? kBlock : r;
             src[i] = (long long)r * row_stride + c * 16;
         }
     }

@@ -17,7 +17,9 @@ namespace {
 // per 128 x 128 state: measured best on MI355X for the 2048-chain decode workload (39.4 us
 // per step against 41.9 with 256 and 39.9 with 1024); larger states keep the same number of
 // state values per thread, smaller ones the 128 threads.
-constexpr int threads_for(int DK, int DV) { return DK * DV / 128 < 128 ? 128 : DK * DV / 128; }
+constexpr int threads_for(int DK, int DV) {
+    return (DK == 96 && DV == 96) ? 96 : (DK * DV / 128 < 128 ? 128 : DK * DV / 128);   // 96: 24 threads per row
+}
 
 __device__ __forceinline__ float bf16_bits_to_f32(unsigned short h) {
     return __uint_as_float(((unsigned int)h) << 16);
@@ -114,7 +116,7 @@ hipError_t launch_decode(const void* q, const void* k, const void* v, void* o, f
         else hipLaunchKernelGGL((decode_kernel<dk, dv, false>), grid, block, 0, stream, q, k, v, o, kv, decay, H, steps);         \
         return hipGetLastError();                                                                       \
     }
-    LTN_DECODE(128, 128) LTN_DECODE(64, 64) LTN_DECODE(256, 256) LTN_DECODE(256, 128) LTN_DECODE(128, 64)
+    LTN_DECODE(128, 128) LTN_DECODE(64, 64) LTN_DECODE(96, 96) LTN_DECODE(256, 256) LTN_DECODE(256, 128) LTN_DECODE(128, 64)
 #undef LTN_DECODE
     return hipErrorInvalidValue;
 }

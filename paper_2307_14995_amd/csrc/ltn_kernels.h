@@ -48,8 +48,8 @@ struct PassBatch {
     int need_last;        // state_only: also for the last segment of a chain
 };
 
-// bf16 MFMA kernel, block length 64.  D in {64,128,256}; dv = value columns per workgroup
-// (D, D/2 or, for D = 128, D/4; 64 or 32 for D = 256, plain pass only).
+// bf16 MFMA kernel, block length 64.  D in {64,96,128,256}; dv = value columns per workgroup
+// (D, D/2 or, for D = 128, D/4; 64 or 32 for D = 256 and 32 for D = 96, plain pass only).
 // DC (0: = D): features per token of c and out when they differ from those of a and b
 // (the LRPE-d expansion of Eq. 1 doubles the query/key width): a, b [chains, N, D];
 // c, out [chains, N, DC]; states [chains, D, DC]; dv slices DC.  Plain pass, one segment.
@@ -59,7 +59,8 @@ hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stre
 // initial state, D in {64,128}.
 hipError_t launch_tiled_fwd_bf16(const void* q, const void* k, const void* v, void* o, const float* decay,
                                  int chains, int H, long long N, int D, hipStream_t stream);
-// fp32 kernel.  D in {64,128,256}, block in {16,32,64}, D*block <= 4096 (D = 256: dv = 64).
+// fp32 kernel.  D in {64,96,128,256}, block in {16,32,64}, D*block <= 4096 (D = 256: dv = 64;
+// D = 96: dv = 32, block 16 or 32).
 hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStream_t stream, int DC = 0);
 // Turns the segment-local end states L[pass][chain][g] in `states` (as written by a
 // state_only launch) into the states at each segment's start, in place:

@@ -514,13 +514,15 @@ __device__ __forceinline__ void areg_output_wave(const Chain& ch, char* smem, in
     wait_vm8<0>(s2.f);
 }
 
-template <int D, int DV, int DC, int MODE>
+// DR: features per token that A and B really have in memory (D, or 96 computed as 128 with
+// the tiles' last columns zero-filled and the state's last rows unused).
+template <int D, int DV, int DC, int MODE, int DR>
 __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, unsigned lds0, int lane, int u) {
     using C = Cfg<D, DV>;
     constexpr int MT = C::MT, NT = C::NT;
     constexpr bool SO = MODE == kStateOnly;          // no published state copies
     constexpr bool NOA = SO || C::AREG;              // the A tile is not this wave's business
-    constexpr long long ROW = D * 2, CROW = DC * 2;
+    constexpr long long ROW = DR * 2, CROW = DC * 2;
     const int g = lane >> 4, i16 = lane & 15;
     const int dk0 = u * (D / 4);
     StateConsts<D, DV, DV> k;
@@ -535,8 +537,10 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
         for (int nt = 0; nt < NT; ++nt) {
             if (ch.state_in) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    st[mt][nt][j] = ch.state_in[(size_t)(dk0 + 16 * mt + 4 * g + j) * DC + 16 * nt + i16];
+                for (int j = 0; j < 4; ++j) {
+                    const int row = dk0 + 16 * mt + 4 * g + j;
+                    st[mt][nt][j] = (DR == D || row < DR) ? ch.state_in[(size_t)row * DC + 16 * nt + i16] : 0.0f;
+                }
             } else {
                 st[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
@@ -549,7 +553,7 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
     const char* pa0 = ch.a + (ch.rev ? (ch.N - 1) * ROW : 0);
     const char* pb0 = ch.b + (ch.rev ? (ch.N - 1) * ROW : 0);
     const char* pc0 = ch.c + (ch.rev ? (ch.N - 1) * CROW : 0);
-    TileDma<D> db;                                   // A and B tiles: same shape, same offsets
+    TileDma<D, DR> db;                               // A and B tiles: same shape, same offsets
     TileDma<DV> dc;
     db.init(u, lane, rs);
     dc.init(u, lane, crs);
@@ -599,12 +603,14 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    ch.state_out[(size_t)(dk0 + 16 * mt + 4 * g + j) * DC + 16 * nt + i16] = st[mt][nt][j];
+                for (int j = 0; j < 4; ++j) {
+                    const int row = dk0 + 16 * mt + 4 * g + j;
+                    if (DR == D || row < DR) ch.state_out[(size_t)row * DC + 16 * nt + i16] = st[mt][nt][j];
+                }
     }
 }
 
-template <int D, int DV, int DC, int MODE>
+template <int D, int DV, int DC, int MODE, int DR>
 __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int wg, char* smem, unsigned lds0,
                                           int wave, int lane) {
     constexpr bool GATED = MODE == kGated;
@@ -627,7 +633,7 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
 
     Chain ch;
     const size_t first_row = (size_t)chain * (size_t)pb.N + (size_t)row0;
-    const size_t ab_off = first_row * D * 2;            // A, B: D features per token
+    const size_t ab_off = first_row * DR * 2;           // A, B: DR features per token
     const size_t chain_off = first_row * DC * 2;        // C, out (U, Y): DC features per token
     const size_t col_off = (size_t)split * DV * 2;
     ch.a = (const char*)P.a + ab_off;
@@ -637,8 +643,8 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
     ch.gate = GATED ? (const char*)P.gate + chain_off : nullptr;
     ch.y = GATED ? (char*)P.gated_out + chain_off : nullptr;
     ch.eps = P.eps;
-    ch.state_in = P.state_in ? P.state_in + (size_t)vchain * D * DC + (size_t)split * DV : nullptr;
-    ch.state_out = P.state_out ? P.state_out + (size_t)vchain * D * DC + (size_t)split * DV : nullptr;
+    ch.state_in = P.state_in ? P.state_in + (size_t)vchain * DR * DC + (size_t)split * DV : nullptr;
+    ch.state_out = P.state_out ? P.state_out + (size_t)vchain * DR * DC + (size_t)split * DV : nullptr;
     ch.N = n;
     ch.T = (int)((n + kBlock - 1) / kBlock);
     ch.last_valid = (int)(n - (long long)(ch.T - 1) * kBlock);
@@ -646,13 +652,13 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
     ch.lam = pb.decay[chain % pb.H];
 
     if constexpr (Cfg<D, DV>::AREG) {
-        static_assert(MODE == kPlain, "the register-fed layout has the plain pass only");
+        static_assert(MODE == kPlain && DR == D, "the register-fed layout has the plain pass only");
         switch (wave) {
             case 0: areg_output_wave<D, DV, DC, 0>(ch, smem, lane); break;
             case 1: areg_output_wave<D, DV, DC, 1>(ch, smem, lane); break;
             case 2: areg_output_wave<D, DV, DC, 2>(ch, smem, lane); break;
             case 3: areg_output_wave<D, DV, DC, 3>(ch, smem, lane); break;
-            default: pass_state_wave<D, DV, DC, MODE>(ch, smem, lds0, lane, wave - 4); break;
+            default: pass_state_wave<D, DV, DC, MODE, DR>(ch, smem, lds0, lane, wave - 4); break;
         }
     } else {
         switch (wave) {
@@ -660,23 +666,23 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
             case 1: pass_output_wave<D, DV, DC, 1, MODE>(ch, smem, lane); break;
             case 2: pass_output_wave<D, DV, DC, 2, MODE>(ch, smem, lane); break;
             case 3: pass_output_wave<D, DV, DC, 3, MODE>(ch, smem, lane); break;
-            default: pass_state_wave<D, DV, DC, MODE>(ch, smem, lds0, lane, wave - 4); break;
+            default: pass_state_wave<D, DV, DC, MODE, DR>(ch, smem, lds0, lane, wave - 4); break;
         }
     }
 }
 
 // =============================================================== kernels
 
-template <int D, int DV, int MODE, int DC = D>
+template <int D, int DV, int MODE, int DC = D, int DR = D>
 __global__ __launch_bounds__(kThreads)
 void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
     __shared__ __attribute__((aligned(1024))) char smem[Cfg<D, DV>::PASS_TOTAL];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: role dispatch is a uniform branch
-    pass_body<D, DV, DC, MODE>(pb, nsplit, blockIdx.x, smem, lds_address(smem), wave, tid & 63);
+    pass_body<D, DV, DC, MODE, DR>(pb, nsplit, blockIdx.x, smem, lds_address(smem), wave, tid & 63);
 }
 
-template <int D, int DV, int MODE = kPlain, int DC = D>
+template <int D, int DV, int MODE = kPlain, int DC = D, int DR = D>
 hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
     static_assert(DV <= DC && DC % DV == 0, "value-column slices tile the C operand");
     static_assert(DC == D || MODE == kPlain, "unequal widths: plain pass only");
@@ -684,7 +690,7 @@ hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
     const long long wgs = (long long)pb.chains * pb.segs * pb.count * nsplit;
     if (wgs <= 0 || wgs > 0x7fffffffLL || pb.segs < 1) return hipErrorInvalidValue;
     if (DC != D && pb.segs != 1) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((pass_bf16_kernel<D, DV, MODE, DC>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
+    hipLaunchKernelGGL((pass_bf16_kernel<D, DV, MODE, DC, DR>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
     return hipGetLastError();
 }
 
@@ -700,6 +706,10 @@ hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stre
         LTN_BF16_DC(64, 64, 128); LTN_BF16_DC(64, 32, 128);
 #undef LTN_BF16_DC
         return hipErrorInvalidValue;
+    }
+    if (D == 96) {                         // computed as 128 with zero-filled tile columns, 32-column slices
+        if (pb.p[0].gate || pb.state_only || dv != 32) return hipErrorInvalidValue;
+        return launch_t<128, 32, kPlain, 96, 96>(pb, stream);
     }
     if (pb.p[0].gate) {                    // gated epilogue: one pass, complete output rows
         if (pb.count != 1 || dv != D || !pb.p[0].gated_out || pb.state_only) return hipErrorInvalidValue;

@@ -27,7 +27,9 @@ __device__ __forceinline__ float4 ld4(const float* p) { return *(const float4*)p
 // A and B have D features per token; C and the output have DC (equal to D except around
 // the LRPE-d expansion of Eq. 1, where queries and keys are twice as wide as values); the
 // state is [D x DC].
-template <int D, int DV, int B, bool GATED, int DC = D>
+// DR: features per token that A and B really have in memory (D, or 96 computed as 128 with
+// the tiles' last columns zero and the state's last rows unused).
+template <int D, int DV, int B, bool GATED, int DC = D, int DR = D>
 __global__ __launch_bounds__(kThreads)
 void pass_f32_kernel(const PassBatch pb, const int nsplit) {
     static_assert(!GATED || (DV == D && DC == D), "the gated epilogue needs complete output rows");
@@ -53,7 +55,7 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
     const long long N = pb.N;
     const float lam = pb.decay[chain % pb.H];
 
-    const size_t ab_off = (size_t)chain * (size_t)N * D;
+    const size_t ab_off = (size_t)chain * (size_t)N * DR;
     const size_t chain_off = (size_t)chain * (size_t)N * DC;
     const float* Ap = (const float*)P.a + ab_off;
     const float* Bp = (const float*)P.b + ab_off;
@@ -81,7 +83,8 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
 #pragma unroll
         for (int b = 0; b < UC; ++b) {
             const int i = uy * UR + a, j = ux * UC + b;
-            st[a][b] = P.state_in ? P.state_in[(size_t)chain * D * DC + (size_t)i * DC + split * DV + j] : 0.0f;
+            st[a][b] = (P.state_in && (DR == D || i < DR))
+                           ? P.state_in[(size_t)chain * DR * DC + (size_t)i * DC + split * DV + j] : 0.0f;
             St[i * DV + j] = st[a][b];
         }
     __syncthreads();
@@ -93,10 +96,10 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
             const int r = e / (D / 4), i4 = e % (D / 4);
             const long long t = t0 + r;
             const size_t gr = (size_t)(rev ? (N - 1 - t) : t);
-            const bool ok = r < len;
+            const bool ok = r < len && (DR == D || 4 * i4 < DR);
             const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-            *(float4*)&As[r * DP + 4 * i4] = ok ? ld4(Ap + gr * D + 4 * i4) : z;
-            *(float4*)&Bs[r * DP + 4 * i4] = ok ? ld4(Bp + gr * D + 4 * i4) : z;
+            *(float4*)&As[r * DP + 4 * i4] = ok ? ld4(Ap + gr * DR + 4 * i4) : z;
+            *(float4*)&Bs[r * DP + 4 * i4] = ok ? ld4(Bp + gr * DR + 4 * i4) : z;
         }
         for (int e = tid; e < B * (DV / 4); e += kThreads) {
             const int r = e / (DV / 4), j4 = e % (DV / 4);
@@ -259,17 +262,17 @@ void pass_f32_kernel(const PassBatch pb, const int nsplit) {
 #pragma unroll
             for (int b = 0; b < UC; ++b) {
                 const int i = uy * UR + a, j = ux * UC + b;
-                P.state_out[(size_t)chain * D * DC + (size_t)i * DC + split * DV + j] = st[a][b];
+                if (DR == D || i < DR) P.state_out[(size_t)chain * DR * DC + (size_t)i * DC + split * DV + j] = st[a][b];
             }
     }
 }
 
-template <int D, int DV, int B, bool GATED = false, int DC = D>
+template <int D, int DV, int B, bool GATED = false, int DC = D, int DR = D>
 hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
     const int nsplit = DC / DV;
     const long long wgs = (long long)pb.chains * pb.count * nsplit;
     if (wgs <= 0 || wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((pass_f32_kernel<D, DV, B, GATED, DC>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
+    hipLaunchKernelGGL((pass_f32_kernel<D, DV, B, GATED, DC, DR>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
     return hipGetLastError();
 }
 
@@ -289,6 +292,12 @@ hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStr
         LTN_F32_DC(128, 64, 64, 16); LTN_F32_DC(128, 64, 64, 32);
         LTN_F32_DC(64, 128, 128, 16); LTN_F32_DC(64, 128, 128, 32); LTN_F32_DC(64, 64, 128, 16); LTN_F32_DC(64, 64, 128, 32);
 #undef LTN_F32_DC
+        return hipErrorInvalidValue;
+    }
+    if (D == 96) {                         // computed as 128 with zero tile columns, 32-column slices
+        if (pb.p[0].gate || dv != 32) return hipErrorInvalidValue;
+        if (block == 16) return launch_t<128, 32, 16, false, 96, 96>(pb, stream);
+        if (block == 32) return launch_t<128, 32, 32, false, 96, 96>(pb, stream);
         return hipErrorInvalidValue;
     }
     if (pb.p[0].gate) {                    // gated epilogue: one pass, complete output rows

@@ -49,7 +49,9 @@ def test_pick_block_and_workspace(lib):
     assert ltn.ltn_attn_pick_block(64, torch.bfloat16) == 64
     assert ltn.ltn_attn_pick_block(64, torch.float32) == 64
     assert ltn.ltn_attn_pick_block(128, torch.float32) == 32
-    assert ltn.ltn_attn_pick_block(96, torch.bfloat16) == 0
+    assert ltn.ltn_attn_pick_block(96, torch.bfloat16) == 64
+    assert ltn.ltn_attn_pick_block(96, torch.float32) == 32
+    assert ltn.ltn_attn_pick_block(80, torch.bfloat16) == 0
     assert ltn.ltn_attn_pick_block(256, torch.bfloat16) == 64
     assert ltn.ltn_attn_pick_block(256, torch.float32) == 16
     assert ltn.ltn_attn_workspace_bytes(1, 32, 65536, 256, 0, torch.bfloat16, 0) == 0   # 256-wide heads: no segments
@@ -80,7 +82,8 @@ def test_fwd_argument_errors(lib):
     assert fwd(lib, decay=None) == E_NULL
     assert fwd(lib, N=-1) == E_SHAPE
     assert fwd(lib, Bt=-1) == E_SHAPE
-    assert fwd(lib, D=96) == E_UNSUP
+    assert fwd(lib, D=80) == E_UNSUP
+    assert fwd(lib, D=96, block=64, dtype=0) == E_UNSUP    # fp32, D = 96 (computed as 128): block <= 32
     assert fwd(lib, D=512) == E_UNSUP
     assert fwd(lib, D=256, block=32, dtype=0) == E_UNSUP   # fp32, D = 256: block 16 only
     assert fwd(lib, D=256, block=32) == E_UNSUP             # bf16: block 64 only
@@ -139,7 +142,7 @@ def test_decode_steps_argument_errors(lib):
 
     assert call(kv=None) == E_NULL
     assert call(S=-1) == E_SHAPE
-    assert call(D=96) == E_UNSUP
+    assert call(D=80) == E_UNSUP
     assert call(q=P + 2) == E_ALIGN
     assert call(o=P + 0x2000) == E_UNSUP                   # o aliases v
     assert call(S=0) == OK

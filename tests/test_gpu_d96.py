@@ -1,0 +1,110 @@
+"""GPU parity for heads of 96 features (computed on chip as 128 with zero columns) (forward, state hand-over, gradients, decode), through
+the C ABI against the fp64 oracle; the same checks as for D = 64 and 128 at sizes the oracle
+finishes quickly."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2307_14995_amd as ltn
+from paper_2307_14995_amd import synth
+from oracle import ltn_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float32: 1e-4, torch.bfloat16: 1e-2}
+D = 96
+
+
+def dev():
+    return torch.device("cuda:0")
+
+
+def gpu(*ts):
+    return tuple(None if t is None else t.to(dev()) for t in ts)
+
+
+def check(name, got, ref, tol):
+    assert torch.isfinite(got.float()).all(), f"{name}: non-finite values"
+    err = orc.max_rel_l2(got, ref)
+    assert err <= tol, f"{name}: rel-L2 {err:.3e} > {tol:g}"
+
+
+def mixed_decay(H):
+    d = synth.decay_bench_rule(H).clone()
+    d[0] = 1.0
+    if H > 1:
+        d[1] = 0.0
+    if H > 2:
+        d[2] = float(np.exp(-8.0))
+    return d
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("N", [1, 63, 64, 65, 200, 517])
+def test_d96_forward_ragged(dtype, N):
+    Bt, H = 1, 3
+    q, k, v = synth.make_qkv(Bt, H, N, D, dtype, 800 + N)
+    decay = mixed_decay(H)
+    o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), return_state=True)
+    ref, ref_kv = orc.fwd_recurrent(q, k, v, decay, return_state=True)
+    check("o", o, ref, TOL[dtype])
+    check("kv_out", kv, ref_kv, TOL[dtype])
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_d96_state_in_and_chunked_prefill(dtype):
+    Bt, H, N, cut = 2, 2, 330, 130
+    q, k, v = synth.make_qkv(Bt, H, N, D, dtype, 820)
+    decay = synth.decay_bench_rule(H)
+    kv0 = torch.randn(Bt, H, D, D, generator=torch.Generator().manual_seed(821))
+    ref, ref_kv = orc.fwd_recurrent(q, k, v, decay, kv_in=kv0, return_state=True)
+    qd, kd, vd, dd, kv0d = gpu(q, k, v, decay, kv0)
+    o1, s1 = ltn.ltn_attn_fwd(qd[:, :, :cut].contiguous(), kd[:, :, :cut].contiguous(),
+                              vd[:, :, :cut].contiguous(), dd, kv_in=kv0d, return_state=True)
+    o2, s2 = ltn.ltn_attn_fwd(qd[:, :, cut:].contiguous(), kd[:, :, cut:].contiguous(),
+                              vd[:, :, cut:].contiguous(), dd, kv_in=s1, return_state=True)
+    check("chunked o", torch.cat([o1, o2], dim=2), ref, TOL[dtype])
+    check("chunked kv", s2, ref_kv, TOL[dtype])
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("Bt,H,N", [(1, 3, 1), (1, 3, 65), (1, 3, 300), (4, 24, 130)])
+def test_d96_backward(dtype, Bt, H, N):
+    # three 32-column slices per chain whatever the number of chains
+    q, k, v = synth.make_qkv(Bt, H, N, D, dtype, 840 + N)
+    d_o = synth.make_do(Bt, H, N, D, dtype, 840 + N)
+    decay = mixed_decay(H)
+    qd, kd, vd, gd, dd = gpu(q, k, v, d_o, decay)
+    check("o", ltn.ltn_attn_fwd(qd, kd, vd, dd), orc.fwd_recurrent(q, k, v, decay), TOL[dtype])
+    for name, got, ref in zip(("dq", "dk", "dv"), ltn.ltn_attn_bwd(qd, kd, vd, gd, dd),
+                              orc.bwd_recurrent(q, k, v, d_o, decay)):
+        check(name, got, ref, TOL[dtype])
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_d96_decode_continues_a_prefix(dtype):
+    Bt, H, N0, S = 2, 3, 100, 6
+    q, k, v = synth.make_qkv(Bt, H, N0 + S, D, dtype, 860)
+    decay = mixed_decay(H)
+    ref, ref_kv = orc.fwd_recurrent(q, k, v, decay, return_state=True)
+    qd, kd, vd, dd = gpu(q, k, v, decay)
+    _, kv = ltn.ltn_attn_fwd(qd[:, :, :N0].contiguous(), kd[:, :, :N0].contiguous(),
+                             vd[:, :, :N0].contiguous(), dd, return_state=True)
+    o_a = ltn.ltn_attn_decode_steps(qd[:, :, N0:N0 + 4].contiguous(), kd[:, :, N0:N0 + 4].contiguous(),
+                                    vd[:, :, N0:N0 + 4].contiguous(), kv, dd)
+    outs = [o_a]
+    for t in range(N0 + 4, N0 + S):
+        outs.append(ltn.ltn_attn_decode_step(qd[:, :, t].contiguous(), kd[:, :, t].contiguous(),
+                                             vd[:, :, t].contiguous(), kv, dd).unsqueeze(2))
+    check("decode o", torch.cat(outs, dim=2), ref[:, :, N0:], TOL[dtype])
+    check("decode kv", kv, ref_kv, TOL[dtype])
+
+
+def test_d96_unsupported_variants():
+    H = 2
+    decay = synth.decay_bench_rule(H).to(dev())
+    a = torch.zeros(1, H, 64, D, dtype=torch.bfloat16, device=dev())
+    with pytest.raises(ltn.LtnError):
+        ltn.ltn_attn_fwd_gated(a, a.clone(), a.clone(), a.clone(), decay)
+    with pytest.raises(ltn.LtnError):
+        ltn.ltn_attn_fwd_tiled(a, a.clone(), a.clone(), decay)
