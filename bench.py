@@ -432,6 +432,14 @@ def extended_report(ltn, synth, torch, dev, sections=""):
         print(json.dumps({"workload": "decode_cfg5", "Bt": Bt, "H": H, "us_per_step": round(t * 1e3, 2),
                           "state_GBs": round(2 * Bt * H * D * D * 4 / (t * 1e-3) / 1e9, 1),
                           "batch_tokens_per_s": round(Bt / (t * 1e-3), 1)}), file=sys.stderr, flush=True)
+        for S in (16, 64):                         # a chunk of tokens through the block forward, state handed over
+            qs, ks, vs = (torch.randn(Bt, H, S, D, device=dev).div_(D ** 0.5).to(torch.bfloat16) for _ in range(3))
+            os_ = torch.empty_like(qs)
+            t = time_call(lambda: ltn.ltn_attn_fwd(qs, ks, vs, dd, kv_in=kv, kv_out=kv, out=os_), n=256, warm=20)
+            print(json.dumps({"workload": f"chunk_cfg5_{S}_tokens_block_forward", "Bt": Bt, "H": H, "S": S,
+                              "us_per_call": round(t * 1e3, 2), "us_per_token": round(t * 1e3 / S, 2),
+                              "state_GBs": round(2 * Bt * H * D * D * 4 / (t * 1e-3) / 1e9, 1),
+                              "batch_tokens_per_s": round(Bt * S / (t * 1e-3), 1)}), file=sys.stderr, flush=True)
         for S in (4, 16):                          # several tokens per call: the state moves once per call
             qs, ks, vs = (torch.randn(Bt, H, S, D, device=dev).to(torch.bfloat16) for _ in range(3))
             os_ = torch.empty_like(qs)
