@@ -335,6 +335,7 @@ ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void*
     pb.p[0] = ltn::PassArgs{k, q, d_o, dv, nullptr, nullptr, 1};
     pb.p[1] = ltn::PassArgs{v, d_o, q, dk, nullptr, nullptr, 1};
     pb.p[2] = ltn::PassArgs{d_o, v, k, dq, nullptr, nullptr, 0};
+    pb.pairs_first = 1;
     return run_passes(pb, D, blk, dtype, workspace, st);
 }
 

@@ -46,6 +46,9 @@ struct PassBatch {
     long long seg_len;
     int state_only;       // 1: compute only each segment's end state from a zero state
     int need_last;        // state_only: also for the last segment of a chain
+    // count == 3 only: passes 0 and 1 read the same token rows at the same time (same direction,
+    // two shared operands) and pass 2 does not; lets the bf16 kernel order workgroup ids for that
+    int pairs_first;
 };
 
 // bf16 MFMA kernel, block length 64.  D in {64,96,128,256}; dv = value columns per workgroup

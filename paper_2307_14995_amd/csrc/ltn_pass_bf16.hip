@@ -618,6 +618,24 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
     // chain the pair index is the chain index
     int vchain, within;
     map_workgroup(wg, pb.count * nsplit, pb.chains * pb.segs, vchain, within);
+    if (pb.pairs_first && pb.count == 3 && nsplit == 1 && ((pb.chains * pb.segs) & 7) == 0) {
+        // Backward at full width: passes 0 and 1 of a chain walk the token axis together and
+        // share two operands, pass 2 walks the other way.  Ids: all (pass 0, pass 1) pairs
+        // first, a chain's pair side by side on one XCD, then every pass 2.  With more
+        // workgroups than compute units the pairs still meet in L2 and the late-starting
+        // rounds are filled with pass-2 workgroups, which share nothing with anyone
+        // (measured on MI355X, 96..256 chains: 0..3 % faster than chain-major ids when backward
+        // launches follow each other, no different when they alternate with forward launches).
+        const int nch = pb.chains * pb.segs;
+        const int xcd = wg & 7, slot = wg >> 3;
+        if (wg < 2 * nch) {
+            within = slot & 1;
+            vchain = (slot >> 1) * 8 + xcd;
+        } else {
+            within = 2;
+            vchain = (slot - (nch >> 2)) * 8 + xcd;
+        }
+    }
     const int chain = vchain / pb.segs;
     const int seg = vchain - chain * pb.segs;
     if (MODE == kStateOnly && seg + 1 == pb.segs && !pb.need_last) return;   // nobody consumes this end state
