@@ -61,7 +61,9 @@ ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype 
 // extra read of B and C (the state-only sweep) and two more launches.  Measured on MI355X
 // (8 and 32 chains, N = 4096 .. 16384, forward and backward): pays when a chain can be cut at
 // least 8 ways into segments of at least 1024 tokens without exceeding one round of compute
-// units, and never otherwise.  bf16 kernels only.
+// units, and never otherwise.  bf16 kernels only.  Heads of 256 features always need four
+// 64-column workgroups per chain and segment; there the form pays from 4 segments on (measured:
+// Bt = 1, N = 8192 .. 32768, 4 .. 32 heads).
 // LTN_ATTN_SEGS (debug, used by the parity tests) forces a segment count.
 struct SegPlan { int segs; long long seg_len; };
 constexpr long long kMinSegsFullWidth = 4;   // measured: 2 segments lose to one workgroup per chain
@@ -69,11 +71,12 @@ constexpr long long kMinSegsFullWidth = 4;   // measured: 2 segments lose to one
 SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtype, bool full_width = false) {
     SegPlan plan = {1, 0};
     if (dtype != LTN_BF16 || chain_passes <= 0 || N <= 64) return plan;
-    if (D == 256 || D == 96) return plan;  // no state-only sweep for these widths
-    long long want = 256 / chain_passes;
+    if (D == 96) return plan;              // no state-only sweep for this width
+    // D = 256: every (chain, segment) still needs four 64-column workgroups
+    long long want = 256 / (D == 256 ? 4 * chain_passes : chain_passes);
     if (want > N / 1024) want = N / 1024;
     // a pass that must keep full-width slices has no column split to fall back on
-    if (want < (full_width ? kMinSegsFullWidth : 8)) want = 1;
+    if (want < ((full_width || D == 256) ? kMinSegsFullWidth : 8)) want = 1;
     if (const char* e = std::getenv("LTN_ATTN_SEGS")) {
         const long long v = std::atoll(e);
         if (v >= 1 && v <= 4096) want = v;
@@ -119,7 +122,7 @@ ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void*
         sweep.p[i].state_in = nullptr;
         sweep.p[i].state_out = states + i * per_pass;
     }
-    if (ltn::launch_pass_bf16(sweep, D, D, stream) != hipSuccess) return LTN_ERR_LAUNCH;
+    if (ltn::launch_pass_bf16(sweep, D, D == 256 ? 64 : D, stream) != hipSuccess) return LTN_ERR_LAUNCH;
     if (ltn::launch_segment_scan(states, kv_in, kv_out, pb.decay, pb.count, pb.chains, pb.H, plan.segs,
                                  plan.seg_len, pb.N, D, stream) != hipSuccess)
         return LTN_ERR_LAUNCH;

@@ -670,12 +670,18 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
     ch.lam = pb.decay[chain % pb.H];
 
     if constexpr (Cfg<D, DV>::AREG) {
-        static_assert(MODE == kPlain && DR == D, "the register-fed layout has the plain pass only");
+        static_assert(MODE != kGated && DR == D, "the register-fed layout has no gated epilogue");
         switch (wave) {
-            case 0: areg_output_wave<D, DV, DC, 0>(ch, smem, lane); break;
-            case 1: areg_output_wave<D, DV, DC, 1>(ch, smem, lane); break;
-            case 2: areg_output_wave<D, DV, DC, 2>(ch, smem, lane); break;
-            case 3: areg_output_wave<D, DV, DC, 3>(ch, smem, lane); break;
+            case 0: case 1: case 2: case 3:
+                if constexpr (MODE == kStateOnly) {
+                    pass_output_wave<D, DV, DC, 0, MODE>(ch, smem, lane);      // only keeps the barriers company
+                } else {
+                    if (wave == 0) areg_output_wave<D, DV, DC, 0>(ch, smem, lane);
+                    else if (wave == 1) areg_output_wave<D, DV, DC, 1>(ch, smem, lane);
+                    else if (wave == 2) areg_output_wave<D, DV, DC, 2>(ch, smem, lane);
+                    else areg_output_wave<D, DV, DC, 3>(ch, smem, lane);
+                }
+                break;
             default: pass_state_wave<D, DV, DC, MODE, DR>(ch, smem, lds0, lane, wave - 4); break;
         }
     } else {
@@ -736,6 +742,7 @@ hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stre
         return hipErrorInvalidValue;
     }
     if (pb.state_only) {                   // segment end states only (sequence-parallel form)
+        if (D == 256 && dv == 64) return launch_t<256, 64, kStateOnly>(pb, stream);
         if (D == 128 && dv == 128) return launch_t<128, 128, kStateOnly>(pb, stream);
         if (D == 128 && dv == 64) return launch_t<128, 64, kStateOnly>(pb, stream);
         if (D == 64 && dv == 64) return launch_t<64, 64, kStateOnly>(pb, stream);

@@ -108,3 +108,20 @@ def test_d256_unsupported_variants():
         ltn.ltn_attn_fwd_gated(a, a.clone(), a.clone(), a.clone(), decay)
     with pytest.raises(ltn.LtnError):
         ltn.ltn_attn_fwd_tiled(a, a.clone(), a.clone(), decay)
+
+
+def test_d256_segmented_by_default_for_few_long_chains():
+    Bt, H, N = 1, 2, 8192 + 77
+    need = ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 0)
+    assert need == 8 * Bt * H * D * D * 4               # eight segments of 1088 tokens
+    assert ltn.ltn_attn_workspace_bytes(4, 16, 8192, D, 0, torch.bfloat16, 0) == 0    # enough chains: whole chains
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 780)
+    g = synth.make_do(Bt, H, N, D, torch.bfloat16, 780)
+    decay = synth.decay_bench_rule(H)
+    o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), return_state=True)
+    ref, kv_ref = orc.fwd_recurrent(q, k, v, decay, return_state=True)
+    check("O", o, ref, 1e-2)
+    check("kv", kv, kv_ref, 1e-2)
+    for n, x, r in zip(("dQ", "dK", "dV"), ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay)),
+                       orc.bwd_recurrent(q, k, v, g, decay)):
+        check(n, x, r, 1e-2)

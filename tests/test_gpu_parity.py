@@ -423,7 +423,7 @@ class force_segs:
             os.environ["LTN_ATTN_SEGS"] = self.old
 
 
-@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("D", [64, 128, 256])
 @pytest.mark.parametrize("N,segs", [(130, 2), (517, 3), (1000, 5), (640, 10)])
 def test_bf16_segmented_forward_backward(D, N, segs):
     """Chains cut into segments (end states from zero, scan, per-segment pass) give the same
