@@ -5,9 +5,10 @@ One "step" = one forward + one backward call of the library on the headline work
 (7B-shaped layer: Bt=4, H=32, N=8192, D=128, bf16 tensors, fp32 accumulation), with
 all tensors resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3_7b|cfg2_385m|cfg_1b]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--preroll SECONDS] [--workload cfg3_7b|cfg2_385m|cfg_1b]
                   [--no-cpu-baseline] [--report] [--copy-calibration]
-  (--report adds the other workloads to stderr; --copy-calibration is for counter runs)
+  python bench.py --traffic-from FETCH.csv WRITE.csv      (no GPU: counter CSVs -> profiles/hbm_traffic_*.json)
+  (--report adds the other workloads to stderr; --copy-calibration and --preroll 0 are for counter runs)
 """
 from __future__ import annotations
 
@@ -25,21 +26,22 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 
 
-def flops_per_token_head(D: int, B: int):
-    """FLOP conventions per token-head (one multiply or one add = 1 FLOP), fwd+bwd."""
+def flops_per_token_head(D: int, B: int, plan_fwd=(0, 1), plan_bwd=(0, 1)):
+    """FLOP conventions per token-head (one multiply or one add = 1 FLOP), fwd+bwd.
+    plan_* = (value columns per workgroup, segments per chain) the library takes for the call."""
+    def issued(passes, plan):
+        # One decayed pass per token-head: 4 D^2 for the two state products (state update, query times
+        # state); per 64-token block 10 of 16 score tiles, recomputed by each of the D/dv value-column
+        # slices of a chain, and 12 of 16 score-times-value tiles; a chain cut into segments also runs the
+        # state-only sweep (one more state update, 2 D^2).
+        dv, segs = plan
+        slices = D // dv if dv else 1
+        return passes * ((1.25 * slices + 1.5) * B * D + 4 * D * D + (2 * D * D if segs > 1 else 0))
     return {
         "F_min": 14 * D * D,                               # recurrent form, block independent
         "F_alg": 14 * D * D + 7 * (B + 1) * D,             # blockwise method, causal half of each tile
-        # what the kernels issue: four passes (fwd + three gradient passes), each 4 D^2 for the
-        # state products plus, per 64-token block, 10 of 16 score tiles (twice in the forward,
-        # which runs two value-column slices per chain) and 12 of 16 score-times-value tiles
-        "F_exec": 16 * D * D + (5 * 1.25 + 4 * 1.5) * B * D,
+        "F_exec": issued(1, plan_fwd) + issued(3, plan_bwd),   # what the kernels issue under the plan taken
     }
-
-
-# HBM bytes per backward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
-# the same counters' reading of a plain copy of known size); see profiles/.  Keyed by workload.
-MEASURED_BWD_TRAFFIC_BYTES = {"cfg3_7b": 2.674e9}
 
 
 def algorithmic_bytes_per_token_head(D: int, esize: int):
@@ -47,13 +49,94 @@ def algorithmic_bytes_per_token_head(D: int, esize: int):
     return {"fwd": 4 * D * esize, "bwd": 7 * D * esize}
 
 
+def kernel_source_hash() -> str:
+    """Fingerprint of the sources of the timed kernels: a stored traffic measurement is only
+    quoted while it matches."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2307_14995_amd", "csrc")
+    for name in ("ltn_pass_bf16.hip", "ltn_bf16_tiles.h", "ltn_kernels.h", "ltn_api.hip"):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def traffic_profile_path(workload: str) -> str:
+    return os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.json")
+
+
+def stored_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` as measured by the counter runs (rocprofv3 --pmc FETCH_SIZE, then
+    WRITE_SIZE, each scaled by the same counter's reading of a plain copy of known size), read from
+    profiles/; None when there is no measurement of the kernels as they stand."""
+    try:
+        with open(traffic_profile_path(workload)) as f:
+            rec = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if rec.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    return rec.get("kernels", {}).get(kernel, {}).get("hbm_bytes_per_launch")
+
+
+def write_traffic_profile(workload: str, fetch_csv: str, write_csv: str) -> int:
+    """Turn the two counter-collection CSVs of
+        rocprofv3 --pmc FETCH_SIZE -- python3 bench.py --steps 3 --warmup 1 --preroll 0 --no-cpu-baseline --copy-calibration
+        rocprofv3 --pmc WRITE_SIZE -- (same)
+    into profiles/hbm_traffic_<workload>.json: per kernel, mean counter value per launch, scaled by what the
+    same counter read for the calibration copy (1 GiB read, 1 GiB written)."""
+    import csv
+    import re
+
+    def per_kernel(path, counter):
+        acc = {}
+        with open(path, newline="") as f:
+            for row in csv.DictReader(f):
+                if row["Counter_Name"] != counter:
+                    continue
+                acc.setdefault(row["Kernel_Name"], []).append(float(row["Counter_Value"]))
+        return acc
+
+    GIB = float(1 << 30)
+    out = {"workload": workload, "kernel_source_hash": kernel_source_hash(), "kernels": {},
+           "how": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), one counter per run, scaled by the "
+                  "counter's reading of a 1 GiB device-to-device copy in the same run"}
+    fetch, write = per_kernel(fetch_csv, "FETCH_SIZE"), per_kernel(write_csv, "WRITE_SIZE")
+    cal_f = [v for k, vs in fetch.items() if "copyBuffer" in k for v in vs if v > 1e5]
+    cal_w = [v for k, vs in write.items() if "copyBuffer" in k for v in vs if v > 1e5]
+    if not cal_f or not cal_w:
+        print("no calibration copy found in the counter runs (run bench.py with --copy-calibration)", file=sys.stderr)
+        return 1
+    sf, sw = GIB / (sum(cal_f) / len(cal_f) * 1024.0), GIB / (sum(cal_w) / len(cal_w) * 1024.0)
+    out["scale"] = {"FETCH_SIZE": round(sf, 4), "WRITE_SIZE": round(sw, 4)}
+    for name in fetch:
+        m = re.search(r"pass_bf16_kernel<(\d+), (\d+), (\d+)", name)
+        if not m or name not in write:
+            continue
+        key = f"pass_bf16_kernel<{m.group(1)},{m.group(2)}>" + ("" if m.group(3) == "0" else f" mode {m.group(3)}")
+        rd = sum(fetch[name]) / len(fetch[name]) * 1024.0 * sf
+        wr = sum(write[name]) / len(write[name]) * 1024.0 * sw
+        out["kernels"][key] = {"launches": len(fetch[name]), "read_bytes_per_launch": round(rd),
+                               "written_bytes_per_launch": round(wr), "hbm_bytes_per_launch": round(rd + wr)}
+    with open(traffic_profile_path(workload), "w") as f:
+        json.dump(out, f, indent=1)
+        f.write("\n")
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # defaults: the first ~100 steps after an idle GPU run 4-8 % slower (clocks ramp up); 100 warm-up
-    # and 400 timed steps are about 0.4 s of GPU time
+    # defaults: 100 warm-up and 400 timed steps are about 0.4 s of GPU time; the clock ramp of an idle GPU
+    # is taken out by the pre-roll below, whatever --warmup says
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--preroll", type=float, default=6.0,
+                    help="upper bound, in seconds, of the untimed pre-roll that brings the GPU to sustained "
+                         "clocks before the warm-up steps (0 = none; counter runs use 0)")
+    ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU work: write profiles/hbm_traffic_<workload>.json from two counter-collection CSVs")
     ap.add_argument("--workload", default="cfg3_7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", action="store_true")
@@ -63,6 +146,8 @@ def main() -> int:
                     help="first run one untimed 1 GiB device-to-device copy, so that a counter run "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic")
     args = ap.parse_args()
+    if args.traffic_from:
+        return write_traffic_profile(args.workload, *args.traffic_from)
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the attention path has no collective "
               "inside it and no multi-GPU code is part of it); run with --gpus 1", file=sys.stderr)
@@ -100,6 +185,27 @@ def main() -> int:
         ltn.ltn_attn_fwd(qd, kd, vd, dd, block=w.block, out=o)
         ltn.ltn_attn_bwd(qd, kd, vd, gd, dd, block=w.block, out=grads)
 
+    # Pre-roll (untimed, reported): after an idle period the GPU runs its first ~100 steps 4-8 % slower
+    # (clocks ramp up).  The same step is repeated in windows of 50 until two consecutive windows agree
+    # within 1 %, so that the timed figure is the sustained one whatever --warmup says.
+    preroll_steps, preroll_s = 0, 0.0
+    if args.preroll > 0:
+        t_pre = time.perf_counter()
+        prev = None
+        while time.perf_counter() - t_pre < args.preroll:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(50):
+                step()
+            e1.record()
+            torch.cuda.synchronize()
+            preroll_steps += 50
+            cur = e0.elapsed_time(e1)
+            if prev is not None and abs(cur - prev) <= 0.01 * prev:
+                break
+            prev = cur
+        preroll_s = time.perf_counter() - t_pre
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -117,28 +223,38 @@ def main() -> int:
         ev[i][2].record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t_wall0) * 1e3
-    fwd_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
-    bwd_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    fwd_t = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    bwd_t = sorted(e[1].elapsed_time(e[2]) for e in ev)
+    step_t = sorted(e[0].elapsed_time(e[2]) for e in ev)
+    fwd_ms = sum(fwd_t) / args.steps
+    bwd_ms = sum(bwd_t) / args.steps
     ms_per_step = wall_ms / args.steps
 
     token_heads = w.Bt * w.H * w.N
     tokens = w.Bt * w.N
     tokens_per_s = tokens / (ms_per_step * 1e-3)
-    fl = flops_per_token_head(w.D, block)
+    plan_f = ltn.ltn_attn_query_plan(w.Bt, w.H, w.N, w.D, w.dtype, 0)
+    plan_b = ltn.ltn_attn_query_plan(w.Bt, w.H, w.N, w.D, w.dtype, 1)
+    fl = flops_per_token_head(w.D, block, plan_f, plan_b)
     ab = algorithmic_bytes_per_token_head(w.D, esize)
     tflops = {n: f * token_heads / (ms_per_step * 1e-3) / 1e12 for n, f in fl.items()}
 
     # Dominant kernel: the backward launch (all three gradients in one kernel).
+    bwd_kernel = f"pass_bf16_kernel<{w.D},{plan_b[0]}>" if w.dtype == torch.bfloat16 else f"pass_f32_kernel<{w.D},{plan_b[0]}>"
     bwd_bytes = ab["bwd"] * token_heads
     achieved = bwd_bytes / (bwd_ms * 1e-3) / 1e9
     roofline = {
-        "bound": "hbm", "kernel": "pass_bf16_kernel<128,128> (the backward launch: dV, dK and dQ passes of every chain)",
+        "bound": "hbm",
+        "kernel": bwd_kernel + " (the backward launch: dV, dK and dQ passes of every chain"
+                  + (f", {plan_b[1]} segments per chain" if plan_b[1] > 1 else "") + ")",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": MEASURED_BWD_TRAFFIC_BYTES.get(args.workload),
+        "traffic": stored_traffic(args.workload, bwd_kernel),
         "algorithmic_bytes": bwd_bytes,
         "kernel_ms": round(bwd_ms, 4),
+        "kernel_ms_median": round(bwd_t[len(bwd_t) // 2], 4), "kernel_ms_min": round(bwd_t[0], 4),
         "fwd_kernel_ms": round(fwd_ms, 4),
+        "fwd_kernel_ms_median": round(fwd_t[len(fwd_t) // 2], 4), "fwd_kernel_ms_min": round(fwd_t[0], 4),
         "fwd_achieved_GBs": round(ab["fwd"] * token_heads / (fwd_ms * 1e-3) / 1e9, 1),
     }
 
@@ -151,6 +267,9 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_events": {"mean": round(sum(step_t) / args.steps, 4), "median": round(step_t[len(step_t) // 2], 4),
+                               "min": round(step_t[0], 4)},
+        "preroll_s": round(preroll_s, 2), "preroll_steps": preroll_steps,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

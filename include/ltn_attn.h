@@ -24,8 +24,10 @@
  *     (row = key feature, column = value feature).
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
  *     default stream).  Calls return without synchronising.
- *   - Outputs are fully overwritten; inputs are never written.  An output that
- *     aliases an input is rejected (LTN_ERR_UNSUPPORTED).
+ *   - Outputs are fully overwritten; inputs are never written.  An output whose
+ *     bytes overlap an input's or another output's (not only equal base
+ *     pointers; the workspace counts as an output) is rejected
+ *     (LTN_ERR_UNSUPPORTED).  The one exception: kv_out may be kv_in itself.
  *   - Errors are return codes only.  Argument errors are detected on the host
  *     before anything is launched.  Bt == 0 or H == 0 is a successful no-op; when
  *     Bt * H * N == 0 the token tensors are not touched and may be NULL.
@@ -176,8 +178,14 @@ ltn_status ltn_attn_decode_step(const void* q, const void* k, const void* v, voi
  *
  *   q, k, v in : device, [Bt,H,S,D] dtype     o out: device, [Bt,H,S,D] dtype
  *   kv  in/out : device, [Bt,H,D,D] fp32      S == 0 is a successful no-op
- * All arithmetic is fp32 whatever `dtype` is (unlike ltn_attn_fwd with kv_in/kv_out, which
- * computes the same thing blockwise with bf16 MFMA for bf16 tensors).
+ * All arithmetic is fp32 whatever `dtype` is, and the result is bit for bit that of S
+ * single-token calls.  The loop is bound by its fp32 multiply-adds from about 8 tokens per
+ * call on: a caller with more tokens per sequence than that (bf16 tensors) gets the same
+ * state and outputs, to rounding, faster from ltn_attn_fwd(q, k, v, o, ..., kv_in = kv,
+ * kv_out = kv, N = S), which evaluates the S iterations blockwise with bf16 MFMA
+ * (measured on MI355X, 2048 chains: 16 tokens 66 us against 101 us, 64 tokens 79 us
+ * against 312 us).  The library does not switch by itself because the two differ in
+ * rounding.
  */
 ltn_status ltn_attn_decode_steps(const void* q, const void* k, const void* v, void* o,
                                  float* kv, const float* decay,
@@ -265,8 +273,28 @@ ltn_status ltn_attn_decode_steps_dkdv(const void* q, const void* k, const void* 
                                       int Bt, int H, int S, int Dk, int Dv,
                                       ltn_dtype dtype, void* stream);
 
-/* Block length the library uses for (D, dtype) when `block` is 0; 0 if unsupported. */
+/* Block length the library uses for (D, dtype) when `block` is 0; 0 if unsupported.
+ * The paper leaves the block sizes B_r, B_c of its tiling as inputs (App. B, Algorithms 3
+ * and 4); the result does not depend on them beyond rounding.  bf16: 64 for every D (a
+ * 128-token block does not leave room for two pipeline stages in the 160 KB of LDS, a
+ * 32-token block doubles the per-token cost of reading the state copy); fp32: the largest
+ * of 16, 32, 64 whose tiles fit. */
 int ltn_attn_pick_block(int D, ltn_dtype dtype);
+
+/* The launch plan the library takes for these arguments (call as in
+ * ltn_attn_workspace_bytes): value columns per workgroup in *dv, segments per chain in
+ * *segs (1 = whole chains).  For reports that need to name the kernel variant that ran. */
+ltn_status ltn_attn_query_plan(int Bt, int H, long long N, int D, ltn_dtype dtype, int call,
+                               int* dv, int* segs);
+
+/* TEST ONLY.  Forces the launch plan of ltn_attn_fwd / ltn_attn_bwd / ltn_attn_fwd_gated for
+ * the whole process until called again: dv = value columns per workgroup (0 = the library's
+ * choice; a value the kernels do not have for a given D is ignored), segs = segments per
+ * chain (0 = the library's choice, 1 = never cut).  It exists so that the parity tests can
+ * reach every kernel variant at small sizes; it also changes what
+ * ltn_attn_workspace_bytes returns.  Not thread-safe against concurrent calls into the
+ * library.  LTN_ERR_SHAPE for values outside {0, 32, 64, 128, 256} / [0, 4096]. */
+ltn_status ltn_attn_set_debug_plan(int dv, int segs);
 
 /* Scratch bytes a call needs for these arguments: call = 0 for ltn_attn_fwd, 1 for
  * ltn_attn_bwd, 2 for ltn_attn_fwd_gated.  A smaller workspace makes the call fail with

@@ -22,6 +22,7 @@ SYMBOLS = (
     "ltn_attn_workspace_bytes", "ltn_attn_check_decay", "ltn_status_str",
     "ltn_prologue_fwd", "ltn_prologue_bwd", "ltn_prologue_workspace_bytes",
     "ltn_attn_fwd_dkdv", "ltn_attn_bwd_dkdv", "ltn_attn_decode_steps_dkdv",
+    "ltn_attn_query_plan", "ltn_attn_set_debug_plan",
 )
 
 
@@ -84,6 +85,10 @@ def load_library():
     lib.ltn_attn_bwd_dkdv.restype = ci
     lib.ltn_attn_decode_steps_dkdv.argtypes = [vp, vp, vp, vp, fp, fp, ci, ci, ci, ci, ci, ci, vp]
     lib.ltn_attn_decode_steps_dkdv.restype = ci
+    lib.ltn_attn_query_plan.argtypes = [ci, ci, cl, ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
+    lib.ltn_attn_query_plan.restype = ci
+    lib.ltn_attn_set_debug_plan.argtypes = [ci, ci]
+    lib.ltn_attn_set_debug_plan.restype = ci
     _lib = lib
     return lib
 
@@ -99,6 +104,23 @@ def ltn_attn_pick_block(D: int, dtype: torch.dtype) -> int:
 def ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, call) -> int:
     """call: 0 = ltn_attn_fwd, 1 = ltn_attn_bwd, 2 = ltn_attn_fwd_gated."""
     return int(load_library().ltn_attn_workspace_bytes(Bt, H, N, D, block, _dtype_code(dtype), int(call)))
+
+
+def ltn_attn_query_plan(Bt, H, N, D, dtype, call):
+    """(value columns per workgroup, segments per chain) the library takes for these arguments."""
+    dv, segs = ctypes.c_int(0), ctypes.c_int(0)
+    rc = load_library().ltn_attn_query_plan(int(Bt), int(H), int(N), int(D), _dtype_code(dtype), int(call),
+                                            ctypes.byref(dv), ctypes.byref(segs))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_query_plan")
+    return dv.value, segs.value
+
+
+def ltn_attn_set_debug_plan(dv=0, segs=0) -> None:
+    """Test only: force the value-column split and the segment count (0 = the library's choice)."""
+    rc = load_library().ltn_attn_set_debug_plan(int(dv), int(segs))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_set_debug_plan")
 
 
 def ltn_attn_check_decay(decay) -> int:

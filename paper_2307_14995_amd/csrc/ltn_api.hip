@@ -4,26 +4,54 @@
 #include "../../include/ltn_attn.h"
 #include "ltn_kernels.h"
 
+#include <atomic>
 #include <cstdint>
-#include <cstdlib>
+#include <mutex>
 
 namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Test-only overrides of the launch plan (ltn_attn_set_debug_plan); 0 = the library's choice.
+std::atomic<int> g_debug_dv{0};
+std::atomic<int> g_debug_segs{0};
+
+// A tensor argument as a byte range.  Outputs are written while inputs are still being
+// read (tile loads run up to three blocks ahead of the stores), so any overlap between an
+// output and an input, or between two outputs, is rejected, not only equal base pointers.
+struct Span { const void* p; size_t bytes; };
+
+bool spans_overlap(const Span& a, const Span& b) {
+    if (!a.p || !b.p || a.bytes == 0 || b.bytes == 0) return false;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a.p), b0 = reinterpret_cast<uintptr_t>(b.p);
+    return a0 < b0 + b.bytes && b0 < a0 + a.bytes;
+}
+
+// true when some output overlaps an input or another output
+bool outputs_alias(const Span* outs, int n_out, const Span* ins, int n_in) {
+    for (int a = 0; a < n_out; ++a) {
+        for (int b = 0; b < n_in; ++b)
+            if (spans_overlap(outs[a], ins[b])) return true;
+        for (int b = a + 1; b < n_out; ++b)
+            if (spans_overlap(outs[a], outs[b])) return true;
+    }
+    return false;
+}
+
+size_t esize_of(ltn_dtype dtype) { return dtype == LTN_BF16 ? 2 : 4; }
 
 // Value columns handled per workgroup.  Every value-column slice of a chain recomputes
 // that chain's score tiles and re-reads its first two operands through L2, and a compute
 // unit holds one workgroup: the split is the deepest one whose workgroups still fit one
 // round of the 256 compute units; when even full-width slices need more than one round,
 // full width (fewest re-reads).  Measured on MI355X for 8..256 chains, forward and
-// backward.  LTN_ATTN_DV (debug, used by the parity tests) overrides the choice.
+// backward.  ltn_attn_set_debug_plan (test only) overrides the choice.
 int pick_dv(long long chain_passes, int D, ltn_dtype dtype) {
     if (D == 96) return 32;                // three 32-column slices (the kernels exist for those only)
     // D = 256: the state copies of more than 64 columns do not fit the LDS
     const int hi = (D == 256) ? 64 : D;
     const int lo = (dtype == LTN_BF16) ? 32 : (D == 256 ? 64 : D / 2);
-    if (const char* e = std::getenv("LTN_ATTN_DV")) {
-        const int v = std::atoi(e);
+    if (const int v = g_debug_dv.load(std::memory_order_relaxed)) {
         if ((v == D || v == D / 2 || v == D / 4 || v == D / 8) && v >= lo && v <= hi) return v;
     }
     for (int dv = lo; dv <= hi; dv *= 2)
@@ -64,7 +92,7 @@ ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype 
 // units, and never otherwise.  bf16 kernels only.  Heads of 256 features always need four
 // 64-column workgroups per chain and segment; there the form pays from 4 segments on (measured:
 // Bt = 1, N = 8192 .. 32768, 4 .. 32 heads).
-// LTN_ATTN_SEGS (debug, used by the parity tests) forces a segment count.
+// ltn_attn_set_debug_plan (test only) forces a segment count.
 struct SegPlan { int segs; long long seg_len; };
 constexpr long long kMinSegsFullWidth = 4;   // measured: 2 segments lose to one workgroup per chain
 
@@ -77,10 +105,7 @@ SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtyp
     if (want > N / 1024) want = N / 1024;
     // a pass that must keep full-width slices has no column split to fall back on
     if (want < ((full_width || D == 256) ? kMinSegsFullWidth : 8)) want = 1;
-    if (const char* e = std::getenv("LTN_ATTN_SEGS")) {
-        const long long v = std::atoll(e);
-        if (v >= 1 && v <= 4096) want = v;
-    }
+    if (const int v = g_debug_segs.load(std::memory_order_relaxed)) want = v;
     if (want <= 1) return plan;
     long long len = (N + want - 1) / want;
     len = (len + 63) / 64 * 64;
@@ -141,6 +166,27 @@ ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void*
 
 extern "C" {
 
+ltn_status ltn_attn_set_debug_plan(int dv, int segs) {
+    if (dv != 0 && dv != 32 && dv != 64 && dv != 128 && dv != 256) return LTN_ERR_SHAPE;
+    if (segs < 0 || segs > 4096) return LTN_ERR_SHAPE;
+    g_debug_dv.store(dv, std::memory_order_relaxed);
+    g_debug_segs.store(segs, std::memory_order_relaxed);
+    return LTN_OK;
+}
+
+ltn_status ltn_attn_query_plan(int Bt, int H, long long N, int D, ltn_dtype dtype, int call,
+                               int* dv_out, int* segs_out) {
+    if (!dv_out || !segs_out) return LTN_ERR_NULL;
+    if (Bt <= 0 || H <= 0 || N <= 0 || call < 0 || call > 2) return LTN_ERR_SHAPE;
+    if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
+    if (D != 64 && D != 96 && D != 128 && D != 256) return LTN_ERR_UNSUPPORTED;
+    const long long chain_passes = (long long)Bt * H * (call == 1 ? 3 : 1);
+    const SegPlan plan = pick_segments(chain_passes, N, D, dtype, call == 2);
+    *segs_out = plan.segs;
+    *dv_out = (call == 2) ? D : pick_dv(chain_passes * plan.segs, D, dtype);
+    return LTN_OK;
+}
+
 int ltn_attn_pick_block(int D, ltn_dtype dtype) {
     if (D != 64 && D != 96 && D != 128 && D != 256) return 0;
     if (dtype == LTN_BF16) return 64;
@@ -171,7 +217,7 @@ const char* ltn_status_str(ltn_status s) {
         case LTN_OK: return "LTN_OK";
         case LTN_ERR_NULL: return "LTN_ERR_NULL: a required pointer is NULL";
         case LTN_ERR_SHAPE: return "LTN_ERR_SHAPE: bad size or workspace too small";
-        case LTN_ERR_UNSUPPORTED: return "LTN_ERR_UNSUPPORTED: shape/dtype/block not supported, or output aliases an input";
+        case LTN_ERR_UNSUPPORTED: return "LTN_ERR_UNSUPPORTED: shape/dtype/block not supported, or an output overlaps an input or another output";
         case LTN_ERR_ALIGN: return "LTN_ERR_ALIGN: tensor pointer not 16-byte aligned";
         case LTN_ERR_DECAY: return "LTN_ERR_DECAY: decay value outside [0, 1]";
         case LTN_ERR_LAUNCH: return "LTN_ERR_LAUNCH: HIP launch failed";
@@ -191,27 +237,27 @@ static ltn_status fwd_common(const void* q, const void* k, const void* v, const 
     if (cs != LTN_OK) return cs;
     if (gated && !(eps >= 0.0f)) return LTN_ERR_SHAPE;
     if (gated && (D == 256 || D == 96)) return LTN_ERR_UNSUPPORTED;   // no kernel with complete output rows of these widths
-    if (workspace_bytes < ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, gated ? 2 : 0)) return LTN_ERR_SHAPE;
+    const size_t need_ws = ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, gated ? 2 : 0);
+    if (workspace_bytes < need_ws) return LTN_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(u) || !aligned16(y) ||
         !aligned16(kv_in) || !aligned16(kv_out) || !aligned16(workspace) ||
         (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
-    if (!empty) {
-        const void* ins[4] = {q, k, v, u};
-        const void* outs[3] = {o, y, kv_out};
-        for (int a = 0; a < 3; ++a) {
-            if (!outs[a]) continue;
-            for (int b = 0; b < 4; ++b)
-                if (outs[a] == ins[b]) return LTN_ERR_UNSUPPORTED;
-            for (int b = a + 1; b < 3; ++b)
-                if (outs[a] == outs[b]) return LTN_ERR_UNSUPPORTED;
-        }
-    }
     const long long chains = (long long)Bt * H;
+    if (!empty) {
+        const size_t tb = (size_t)chains * (size_t)N * D * esize_of(dtype), sb = (size_t)chains * D * D * sizeof(float);
+        // kv_out may be kv_in itself (a state updated in place); any other overlap is refused
+        const Span ins[5] = {{q, tb}, {k, tb}, {v, tb}, {u, tb}, {kv_in == kv_out ? nullptr : kv_in, sb}};
+        const Span outs[4] = {{o, tb}, {y, tb}, {kv_out, sb}, {workspace, need_ws}};
+        if (outputs_alias(outs, 4, ins, 5)) return LTN_ERR_UNSUPPORTED;
+    }
     if (chains == 0) return LTN_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (N == 0) {
         if (!kv_out) return LTN_OK;
+        if (kv_in && kv_in != kv_out && spans_overlap({kv_in, (size_t)chains * D * D * sizeof(float)},
+                                                      {kv_out, (size_t)chains * D * D * sizeof(float)}))
+            return LTN_ERR_UNSUPPORTED;
         return ltn::launch_state_copy(kv_in, kv_out, (size_t)chains * D * D, st) == hipSuccess
                    ? LTN_OK : LTN_ERR_LAUNCH;
     }
@@ -267,7 +313,12 @@ ltn_status ltn_attn_fwd_tiled(const void* q, const void* k, const void* v, void*
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) ||
         (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
-    if (!empty && (o == q || o == k || o == v)) return LTN_ERR_UNSUPPORTED;
+    if (!empty) {
+        const size_t tb = (size_t)Bt * H * (size_t)N * D * esize_of(dtype);
+        const Span ins[3] = {{q, tb}, {k, tb}, {v, tb}};
+        const Span outs[1] = {{o, tb}};
+        if (outputs_alias(outs, 1, ins, 3)) return LTN_ERR_UNSUPPORTED;
+    }
     if (empty) return LTN_OK;
     return ltn::launch_tiled_fwd_bf16(q, k, v, o, decay, Bt * H, H, N, D, static_cast<hipStream_t>(stream)) ==
                    hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
@@ -282,8 +333,12 @@ static ltn_status gate_common(const void* x, const void* u, const void* d_y, voi
     if (rows == 0) return LTN_OK;
     if (!x || !u || !o0 || (bwd && (!d_y || !o1))) return LTN_ERR_NULL;
     if (!aligned16(x) || !aligned16(u) || !aligned16(d_y) || !aligned16(o0) || !aligned16(o1)) return LTN_ERR_ALIGN;
-    if (o0 == x || o0 == u || o0 == d_y || (bwd && (o1 == x || o1 == u || o1 == d_y || o1 == o0)))
-        return LTN_ERR_UNSUPPORTED;
+    {
+        const size_t tb = (size_t)rows * D * esize_of(dtype);
+        const Span ins[3] = {{x, tb}, {u, tb}, {d_y, tb}};
+        const Span outs[2] = {{o0, tb}, {bwd ? o1 : nullptr, tb}};
+        if (outputs_alias(outs, 2, ins, 3)) return LTN_ERR_UNSUPPORTED;
+    }
     const hipError_t e = ltn::launch_gate(x, u, d_y, o0, o1, eps, rows, D, dtype == LTN_BF16, bwd,
                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
@@ -308,19 +363,18 @@ ltn_status ltn_attn_bwd(const void* q, const void* k, const void* v, const void*
     int blk = 0;
     const ltn_status cs = check_common(Bt, H, N, D, block, dtype, &blk);
     if (cs != LTN_OK) return cs;
-    if (workspace_bytes < ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, 1)) return LTN_ERR_SHAPE;
+    const size_t need_ws = ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, 1);
+    if (workspace_bytes < need_ws) return LTN_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) ||
         !aligned16(dk) || !aligned16(dv) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
-    const void* ins[4] = {q, k, v, d_o};
-    const void* outs[3] = {dq, dk, dv};
-    for (int a = 0; a < 3 && !empty; ++a) {
-        for (int b = 0; b < 4; ++b)
-            if (outs[a] == ins[b]) return LTN_ERR_UNSUPPORTED;
-        for (int b = a + 1; b < 3; ++b)
-            if (outs[a] == outs[b]) return LTN_ERR_UNSUPPORTED;
-    }
     const long long chains = (long long)Bt * H;
+    if (!empty) {
+        const size_t tb = (size_t)chains * (size_t)N * D * esize_of(dtype);
+        const Span ins[4] = {{q, tb}, {k, tb}, {v, tb}, {d_o, tb}};
+        const Span outs[4] = {{dq, tb}, {dk, tb}, {dv, tb}, {workspace, need_ws}};
+        if (outputs_alias(outs, 4, ins, 4)) return LTN_ERR_UNSUPPORTED;
+    }
     if (chains == 0 || N == 0) return LTN_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     // The three gradients are three decayed linear-attention passes with permuted
@@ -354,10 +408,13 @@ ltn_status ltn_attn_decode_steps(const void* q, const void* k, const void* v, vo
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(kv) ||
         (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
-    if (!empty && (o == q || o == k || o == v || (const void*)kv == q || (const void*)kv == k ||
-                   (const void*)kv == v || (const void*)kv == o))
-        return LTN_ERR_UNSUPPORTED;
     const int chains = Bt * H;
+    if (!empty) {
+        const size_t tb = (size_t)chains * S * D * esize_of(dtype);
+        const Span ins[3] = {{q, tb}, {k, tb}, {v, tb}};
+        const Span outs[2] = {{o, tb}, {kv, (size_t)chains * D * D * sizeof(float)}};
+        if (outputs_alias(outs, 2, ins, 3)) return LTN_ERR_UNSUPPORTED;
+    }
     if (empty) return LTN_OK;
     const hipError_t e = ltn::launch_decode(q, k, v, o, kv, decay, chains, H, S, D, D, dtype == LTN_BF16,
                                             static_cast<hipStream_t>(stream));
@@ -419,10 +476,14 @@ ltn_status ltn_attn_fwd_dkdv(const void* q, const void* k, const void* v, void* 
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(kv_in) ||
         !aligned16(kv_out) || (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
-    if (!empty && (o == q || o == k || o == v || (const void*)kv_out == q || (const void*)kv_out == k ||
-                   (const void*)kv_out == v || (const void*)kv_out == o))
-        return LTN_ERR_UNSUPPORTED;
     const long long chains = (long long)Bt * H;
+    if (!empty) {
+        const size_t qb = (size_t)chains * (size_t)N * Dk * esize_of(dtype), vb = (size_t)chains * (size_t)N * Dv * esize_of(dtype);
+        const size_t sb = (size_t)chains * Dk * Dv * sizeof(float);
+        const Span ins[4] = {{q, qb}, {k, qb}, {v, vb}, {kv_in == kv_out ? nullptr : kv_in, sb}};
+        const Span outs[2] = {{o, vb}, {kv_out, sb}};
+        if (outputs_alias(outs, 2, ins, 4)) return LTN_ERR_UNSUPPORTED;
+    }
     if (chains == 0) return LTN_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (N == 0) {
@@ -453,15 +514,13 @@ ltn_status ltn_attn_bwd_dkdv(const void* q, const void* k, const void* v, const 
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) ||
         !aligned16(dk) || !aligned16(dv) || (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
-    const void* ins[4] = {q, k, v, d_o};
-    const void* outs[3] = {dq, dk, dv};
-    for (int a = 0; a < 3 && !empty; ++a) {
-        for (int b = 0; b < 4; ++b)
-            if (outs[a] == ins[b]) return LTN_ERR_UNSUPPORTED;
-        for (int b = a + 1; b < 3; ++b)
-            if (outs[a] == outs[b]) return LTN_ERR_UNSUPPORTED;
-    }
     const long long chains = (long long)Bt * H;
+    if (!empty) {
+        const size_t qb = (size_t)chains * (size_t)N * Dk * esize_of(dtype), vb = (size_t)chains * (size_t)N * Dv * esize_of(dtype);
+        const Span ins[4] = {{q, qb}, {k, qb}, {v, vb}, {d_o, vb}};
+        const Span outs[3] = {{dq, qb}, {dk, qb}, {dv, vb}};
+        if (outputs_alias(outs, 3, ins, 4)) return LTN_ERR_UNSUPPORTED;
+    }
     if (chains == 0 || N == 0) return LTN_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     // The same three passes as ltn_attn_bwd; they come in two shapes, hence two launches:
@@ -495,9 +554,12 @@ ltn_status ltn_attn_decode_steps_dkdv(const void* q, const void* k, const void* 
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(kv) ||
         (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
-    if (!empty && (o == q || o == k || o == v || (const void*)kv == q || (const void*)kv == k ||
-                   (const void*)kv == v || (const void*)kv == o))
-        return LTN_ERR_UNSUPPORTED;
+    if (!empty) {
+        const size_t qb = (size_t)Bt * H * S * Dk * esize_of(dtype), vb = (size_t)Bt * H * S * Dv * esize_of(dtype);
+        const Span ins[3] = {{q, qb}, {k, qb}, {v, vb}};
+        const Span outs[2] = {{o, vb}, {kv, (size_t)Bt * H * Dk * Dv * sizeof(float)}};
+        if (outputs_alias(outs, 2, ins, 3)) return LTN_ERR_UNSUPPORTED;
+    }
     if (empty) return LTN_OK;
     const hipError_t e = ltn::launch_decode(q, k, v, o, kv, decay, Bt * H, H, S, Dk, Dv, dtype == LTN_BF16,
                                             static_cast<hipStream_t>(stream));
@@ -528,14 +590,13 @@ static ltn_status prologue_common(const void* x, const float* theta, const void*
         (reinterpret_cast<uintptr_t>(theta) & 3u) || (reinterpret_cast<uintptr_t>(d_theta) & 3u))
         return LTN_ERR_ALIGN;
     if (!empty) {
-        const void* ins[3] = {x, d_y, theta};
-        const void* outs[2] = {out, d_theta};
-        for (int a = 0; a < 2; ++a) {
-            if (!outs[a]) continue;
-            for (int b = 0; b < 3; ++b)
-                if (outs[a] == ins[b]) return LTN_ERR_UNSUPPORTED;
-        }
-        if (out == (const void*)d_theta) return LTN_ERR_UNSUPPORTED;
+        // x and d_x have D features per token; y and d_y have 2D behind the expansion, D without it
+        const size_t xb = (size_t)Bt * H * (size_t)N * D * esize_of(dtype), yb = theta ? 2 * xb : xb;
+        const size_t hb = (size_t)H * D * sizeof(float);
+        const Span ins[3] = {{x, xb}, {d_y, yb}, {theta, hb}};
+        const Span outs[3] = {{out, bwd ? xb : yb}, {d_theta, hb},
+                              {want_dtheta ? workspace : nullptr, ltn_prologue_workspace_bytes(Bt, H, N, D)}};
+        if (outputs_alias(outs, 3, ins, 3)) return LTN_ERR_UNSUPPORTED;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (empty) {

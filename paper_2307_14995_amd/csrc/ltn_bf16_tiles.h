@@ -31,7 +31,7 @@ static __device__ __attribute__((aligned(256))) const unsigned char kZeros[256] 
 // Direct global -> LDS load: the wave writes 64 consecutive 16-byte LDS slots starting at
 // the wave-uniform LDS byte address `lds`; lane i fills slot i from its own global address.
 __device__ __forceinline__ void dma16(unsigned lds, const char* g) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(g) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(g) : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory"); }

@@ -13,7 +13,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "ltn_attn.h")
 
 OK, E_NULL, E_SHAPE, E_UNSUP, E_ALIGN, E_DECAY, E_LAUNCH = range(7)
-P = 0x10000  # fake, 16-byte aligned, never dereferenced: validation fails before any launch
+P = 1 << 44  # fake, 16-byte aligned, never dereferenced: validation fails before any launch.
+# Fake tensors sit 4 GiB or more apart, so that only the cases that mean to overlap do.
 
 
 @pytest.fixture(scope="module")
@@ -68,13 +69,13 @@ def test_check_decay(lib):
     assert lib.ltn_attn_check_decay(None, 3) == E_NULL
 
 
-def fwd(lib, q=P, k=P + 0x1000, v=P + 0x2000, o=P + 0x3000, decay=P + 0x4000, kv_in=None, kv_out=None,
+def fwd(lib, q=P, k=P + 0x1000000000, v=P + 0x2000000000, o=P + 0x3000000000, decay=P + 0x4000000000, kv_in=None, kv_out=None,
         Bt=1, H=2, N=256, D=64, block=0, dtype=1, ws=None, ws_bytes=0):
     return lib.ltn_attn_fwd(q, k, v, o, decay, kv_in, kv_out, Bt, H, N, D, block, dtype, ws, ws_bytes, None)
 
 
-def bwd(lib, q=P, k=P + 0x1000, v=P + 0x2000, g=P + 0x3000, dq=P + 0x5000, dk=P + 0x6000, dv=P + 0x7000,
-        decay=P + 0x4000, Bt=1, H=2, N=256, D=64, block=0, dtype=1):
+def bwd(lib, q=P, k=P + 0x1000000000, v=P + 0x2000000000, g=P + 0x3000000000, dq=P + 0x5000000000, dk=P + 0x6000000000, dv=P + 0x7000000000,
+        decay=P + 0x4000000000, Bt=1, H=2, N=256, D=64, block=0, dtype=1):
     return lib.ltn_attn_bwd(q, k, v, g, dq, dk, dv, decay, Bt, H, N, D, block, dtype, None, 0, None)
 
 
@@ -94,10 +95,10 @@ def test_fwd_argument_errors(lib):
     assert fwd(lib, block=32, dtype=1) == E_UNSUP          # bf16 supports block 64 only
     assert fwd(lib, D=128, block=64, dtype=0) == E_UNSUP   # fp32: D * block <= 4096
     assert fwd(lib, q=P + 8) == E_ALIGN
-    assert fwd(lib, kv_out=P + 0x8004) == E_ALIGN
-    assert fwd(lib, decay=P + 0x4002) == E_ALIGN
+    assert fwd(lib, kv_out=P + 0x8000000004) == E_ALIGN
+    assert fwd(lib, decay=P + 0x4000000002) == E_ALIGN
     assert fwd(lib, o=P) == E_UNSUP                        # output aliases q
-    assert fwd(lib, kv_out=P + 0x2000) == E_UNSUP          # state aliases v
+    assert fwd(lib, kv_out=P + 0x2000000000) == E_UNSUP          # state aliases v
     # empty problems succeed without touching the GPU
     assert fwd(lib, Bt=0) == OK
     assert fwd(lib, H=0) == OK
@@ -112,14 +113,14 @@ def test_bwd_argument_errors(lib):
     assert bwd(lib, block=128) == E_UNSUP
     assert bwd(lib, dk=P + 4) == E_ALIGN
     assert bwd(lib, dq=P) == E_UNSUP                       # dq aliases q
-    assert bwd(lib, dk=P + 0x5000) == E_UNSUP              # dk aliases dq
+    assert bwd(lib, dk=P + 0x5000000000) == E_UNSUP              # dk aliases dq
     assert bwd(lib, Bt=0) == OK
     assert bwd(lib, N=0) == OK
 
 
 def test_decode_argument_errors(lib):
     f = lib.ltn_attn_decode_step
-    args = dict(q=P, k=P + 0x100, v=P + 0x200, o=P + 0x300, kv=P + 0x1000, decay=P + 0x4000)
+    args = dict(q=P, k=P + 0x100000000, v=P + 0x200000000, o=P + 0x300000000, kv=P + 0x1000000000, decay=P + 0x4000000000)
 
     def call(Bt=2, H=2, D=128, dtype=1, **over):
         a = dict(args, **over)
@@ -130,15 +131,15 @@ def test_decode_argument_errors(lib):
     assert call(Bt=-2) == E_SHAPE
     assert call(D=100) == E_UNSUP
     assert call(dtype=3) == E_UNSUP
-    assert call(v=P + 0x202) == E_ALIGN
-    assert call(o=P + 0x100) == E_UNSUP
+    assert call(v=P + 0x200000002) == E_ALIGN
+    assert call(o=P + 0x100000000) == E_UNSUP
     assert call(Bt=0) == OK
 
 
 def test_decode_steps_argument_errors(lib):
     f = lib.ltn_attn_decode_steps
 
-    def call(q=P, k=P + 0x1000, v=P + 0x2000, o=P + 0x3000, kv=P + 0x10000, decay=P + 0x4000,
+    def call(q=P, k=P + 0x1000000000, v=P + 0x2000000000, o=P + 0x3000000000, kv=P + 0x10000000000, decay=P + 0x4000000000,
              Bt=2, H=2, S=4, D=128, dtype=1):
         return f(q, k, v, o, kv, decay, Bt, H, S, D, dtype, None)
 
@@ -146,7 +147,7 @@ def test_decode_steps_argument_errors(lib):
     assert call(S=-1) == E_SHAPE
     assert call(D=80) == E_UNSUP
     assert call(q=P + 2) == E_ALIGN
-    assert call(o=P + 0x2000) == E_UNSUP                   # o aliases v
+    assert call(o=P + 0x2000000000) == E_UNSUP                   # o aliases v
     assert call(S=0) == OK
     assert call(S=0, q=None, k=None, v=None, o=None) == OK # nothing to read: pointers may be NULL
 
@@ -155,7 +156,7 @@ def test_fwd_gated_argument_errors(lib):
     f = lib.ltn_attn_fwd_gated
     cf = ctypes.c_float
 
-    def call(q=P, k=P + 0x1000, v=P + 0x2000, u=P + 0x3000, o=P + 0x5000, y=P + 0x6000, decay=P + 0x4000,
+    def call(q=P, k=P + 0x1000000000, v=P + 0x2000000000, u=P + 0x3000000000, o=P + 0x5000000000, y=P + 0x6000000000, decay=P + 0x4000000000,
              kv_in=None, kv_out=None, eps=1e-6, Bt=1, H=2, N=256, D=64, block=0, dtype=1):
         return f(q, k, v, u, o, y, decay, kv_in, kv_out, cf(eps), Bt, H, N, D, block, dtype, None, 0, None)
 
@@ -165,9 +166,9 @@ def test_fwd_gated_argument_errors(lib):
     assert call(eps=float("nan")) == E_SHAPE
     assert call(D=96) == E_UNSUP
     assert call(D=256) == E_UNSUP                          # complete 256-wide rows do not fit a workgroup
-    assert call(y=P + 0x3000) == E_UNSUP                   # y aliases the gate
-    assert call(y=P + 0x5000) == E_UNSUP                   # y aliases o
-    assert call(u=P + 0x3008) == E_ALIGN
+    assert call(y=P + 0x3000000000) == E_UNSUP                   # y aliases the gate
+    assert call(y=P + 0x5000000000) == E_UNSUP                   # y aliases o
+    assert call(u=P + 0x3000000008) == E_ALIGN
     assert call(N=0) == OK
     assert call(Bt=0, q=None, k=None, v=None, u=None, o=None, y=None) == OK
 
@@ -175,36 +176,36 @@ def test_fwd_gated_argument_errors(lib):
 def test_fwd_tiled_argument_errors(lib):
     f = lib.ltn_attn_fwd_tiled
 
-    def call(q=P, k=P + 0x1000, v=P + 0x2000, o=P + 0x3000, decay=P + 0x4000, Bt=1, H=2, N=256, D=128, dtype=1):
+    def call(q=P, k=P + 0x1000000000, v=P + 0x2000000000, o=P + 0x3000000000, decay=P + 0x4000000000, Bt=1, H=2, N=256, D=128, dtype=1):
         return f(q, k, v, o, decay, Bt, H, N, D, dtype, None)
 
     assert call(o=None) == E_NULL
     assert call(N=-1) == E_SHAPE
     assert call(dtype=0) == E_UNSUP                        # bf16 only
     assert call(D=96) == E_UNSUP
-    assert call(k=P + 0x1002) == E_ALIGN
-    assert call(o=P + 0x1000) == E_UNSUP                   # o aliases k
+    assert call(k=P + 0x1000000002) == E_ALIGN
+    assert call(o=P + 0x1000000000) == E_UNSUP                   # o aliases k
     assert call(N=0) == OK
 
 
 def test_gate_argument_errors(lib):
     cf = ctypes.c_float
     fw, bw = lib.ltn_gate_fwd, lib.ltn_gate_bwd
-    assert fw(None, P + 0x1000, P + 0x2000, cf(0.0), 16, 128, 1, None) == E_NULL
-    assert fw(P, P + 0x1000, P + 0x2000, cf(0.0), -1, 128, 1, None) == E_SHAPE
-    assert fw(P, P + 0x1000, P + 0x2000, cf(-0.5), 16, 128, 1, None) == E_SHAPE
-    assert fw(P, P + 0x1000, P + 0x2000, cf(0.0), 16, 96, 1, None) == E_UNSUP
-    assert fw(P, P + 0x1000, P + 0x2000, cf(0.0), 16, 128, 5, None) == E_UNSUP
-    assert fw(P, P + 0x1000, P, cf(0.0), 16, 128, 1, None) == E_UNSUP              # y aliases x
-    assert fw(P, P + 0x1004, P + 0x2000, cf(0.0), 16, 128, 1, None) == E_ALIGN
+    assert fw(None, P + 0x1000000000, P + 0x2000000000, cf(0.0), 16, 128, 1, None) == E_NULL
+    assert fw(P, P + 0x1000000000, P + 0x2000000000, cf(0.0), -1, 128, 1, None) == E_SHAPE
+    assert fw(P, P + 0x1000000000, P + 0x2000000000, cf(-0.5), 16, 128, 1, None) == E_SHAPE
+    assert fw(P, P + 0x1000000000, P + 0x2000000000, cf(0.0), 16, 96, 1, None) == E_UNSUP
+    assert fw(P, P + 0x1000000000, P + 0x2000000000, cf(0.0), 16, 128, 5, None) == E_UNSUP
+    assert fw(P, P + 0x1000000000, P, cf(0.0), 16, 128, 1, None) == E_UNSUP              # y aliases x
+    assert fw(P, P + 0x1000000004, P + 0x2000000000, cf(0.0), 16, 128, 1, None) == E_ALIGN
     assert fw(None, None, None, cf(0.0), 0, 128, 1, None) == OK                     # no rows
-    assert bw(P, P + 0x1000, None, P + 0x3000, P + 0x4000, cf(0.0), 16, 128, 1, None) == E_NULL
-    assert bw(P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x3000, cf(0.0), 16, 128, 1, None) == E_UNSUP  # d_x aliases d_u
-    assert bw(P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x4000, cf(0.0), 16, 64, 7, None) == E_UNSUP
+    assert bw(P, P + 0x1000000000, None, P + 0x3000000000, P + 0x4000000000, cf(0.0), 16, 128, 1, None) == E_NULL
+    assert bw(P, P + 0x1000000000, P + 0x2000000000, P + 0x3000000000, P + 0x3000000000, cf(0.0), 16, 128, 1, None) == E_UNSUP  # d_x aliases d_u
+    assert bw(P, P + 0x1000000000, P + 0x2000000000, P + 0x3000000000, P + 0x4000000000, cf(0.0), 16, 64, 7, None) == E_UNSUP
 
 
 def test_dkdv_argument_errors(lib):
-    def f(q=P, k=P + 0x1000, v=P + 0x2000, o=P + 0x3000, decay=P + 0x4000, kv_in=None, kv_out=None,
+    def f(q=P, k=P + 0x1000000000, v=P + 0x2000000000, o=P + 0x3000000000, decay=P + 0x4000000000, kv_in=None, kv_out=None,
           Bt=1, H=2, N=256, Dk=256, Dv=128, block=0, dtype=1):
         return lib.ltn_attn_fwd_dkdv(q, k, v, o, decay, kv_in, kv_out, Bt, H, N, Dk, Dv, block, dtype, None)
     assert f(q=None) == E_NULL and f(o=None) == E_NULL and f(decay=None) == E_NULL
@@ -220,45 +221,89 @@ def test_dkdv_argument_errors(lib):
     assert f(q=None, k=None, v=None, o=None, N=0) == OK
     assert f(Bt=0) == OK
 
-    def b(q=P, k=P + 0x1000, v=P + 0x2000, g=P + 0x3000, dq=P + 0x5000, dk=P + 0x6000, dv=P + 0x7000,
-          decay=P + 0x4000, Bt=1, H=2, N=256, Dk=256, Dv=128, block=0, dtype=1):
+    def b(q=P, k=P + 0x1000000000, v=P + 0x2000000000, g=P + 0x3000000000, dq=P + 0x5000000000, dk=P + 0x6000000000, dv=P + 0x7000000000,
+          decay=P + 0x4000000000, Bt=1, H=2, N=256, Dk=256, Dv=128, block=0, dtype=1):
         return lib.ltn_attn_bwd_dkdv(q, k, v, g, dq, dk, dv, decay, Bt, H, N, Dk, Dv, block, dtype, None)
     assert b(g=None) == E_NULL and b(dk=None) == E_NULL
     assert b(Dk=128, Dv=128) == E_UNSUP and b(N=-2) == E_SHAPE
-    assert b(dq=P) == E_UNSUP and b(dk=P + 0x7000) == E_UNSUP
-    assert b(dv=P + 0x7008) == E_ALIGN
+    assert b(dq=P) == E_UNSUP and b(dk=P + 0x7000000000) == E_UNSUP
+    assert b(dv=P + 0x7000000008) == E_ALIGN
     assert b(N=0) == OK
 
-    def d(q=P, k=P + 0x1000, v=P + 0x2000, o=P + 0x3000, kv=P + 0x8000, decay=P + 0x4000,
+    def d(q=P, k=P + 0x1000000000, v=P + 0x2000000000, o=P + 0x3000000000, kv=P + 0x8000000000, decay=P + 0x4000000000,
           Bt=1, H=2, S=3, Dk=256, Dv=128, dtype=1):
         return lib.ltn_attn_decode_steps_dkdv(q, k, v, o, kv, decay, Bt, H, S, Dk, Dv, dtype, None)
     assert d(kv=None) == E_NULL and d(S=-1) == E_SHAPE and d(Dk=128, Dv=128) == E_UNSUP
-    assert d(kv=P + 0x3000) == E_UNSUP and d(o=P + 2) == E_ALIGN
+    assert d(kv=P + 0x3000000000) == E_UNSUP and d(o=P + 2) == E_ALIGN
     assert d(S=0, q=None, k=None, v=None, o=None, kv=None) == OK
 
 
 def test_prologue_argument_errors(lib):
-    def f(x=P, theta=P + 0x4000, y=P + 0x1000, act=1, Bt=1, H=2, N=100, D=128, pos0=0, dtype=1):
+    def f(x=P, theta=P + 0x4000000000, y=P + 0x1000000000, act=1, Bt=1, H=2, N=100, D=128, pos0=0, dtype=1):
         return lib.ltn_prologue_fwd(x, theta, y, act, Bt, H, N, D, pos0, dtype, None)
     assert f(x=None) == E_NULL and f(y=None) == E_NULL
     assert f(N=-1) == E_SHAPE and f(pos0=-1) == E_SHAPE and f(pos0=1 << 41) == E_SHAPE
     assert f(D=96) == E_UNSUP and f(dtype=3) == E_UNSUP
-    assert f(x=P + 2) == E_ALIGN and f(theta=P + 0x4002) == E_ALIGN
+    assert f(x=P + 2) == E_ALIGN and f(theta=P + 0x4000000002) == E_ALIGN
     assert f(y=P) == E_UNSUP                       # output aliases the input
     assert f(N=0, x=None, y=None) == OK
 
-    def b(x=P, theta=P + 0x4000, dy=P + 0x1000, dx=P + 0x2000, dth=P + 0x5000, act=1, Bt=1, H=2, N=100, D=128,
-          pos0=0, dtype=1, ws=P + 0x9000, ws_bytes=1 << 20):
+    def b(x=P, theta=P + 0x4000000000, dy=P + 0x1000000000, dx=P + 0x2000000000, dth=P + 0x5000000000, act=1, Bt=1, H=2, N=100, D=128,
+          pos0=0, dtype=1, ws=P + 0x9000000000, ws_bytes=1 << 20):
         return lib.ltn_prologue_bwd(x, theta, dy, dx, dth, act, Bt, H, N, D, pos0, dtype, ws, ws_bytes, None)
     assert b(dy=None) == E_NULL and b(dx=None) == E_NULL
     assert b(theta=None) == E_NULL                 # an angle gradient without angles
     assert b(ws=None) == E_NULL and b(ws_bytes=16) == E_SHAPE
-    assert b(dx=P) == E_UNSUP and b(dth=P + 0x1000) == E_UNSUP
-    assert b(dth=P + 0x5002) == E_ALIGN
+    assert b(dx=P) == E_UNSUP and b(dth=P + 0x1000000000) == E_UNSUP
+    assert b(dth=P + 0x5000000002) == E_ALIGN
     need = lib.ltn_prologue_workspace_bytes(1, 2, 100, 128)
     assert need == 2 * 2 * 128 * 8                 # two 64-token chunks x H x D doubles
     assert b(ws_bytes=need - 1) == E_SHAPE
     assert lib.ltn_prologue_workspace_bytes(1, 2, 0, 128) == 0
+
+
+def test_partial_overlap_is_refused(lib):
+    """Aliasing is judged on byte ranges, not base pointers: an output that starts inside an
+    input (or inside another output, or the workspace inside a tensor) is refused."""
+    tb = 1 * 2 * 256 * 64 * 2                      # bytes of one [1,2,256,64] bf16 tensor
+    assert fwd(lib, o=P + 128) == E_UNSUP          # o starts inside q
+    assert fwd(lib, o=P + tb - 16) == E_UNSUP      # o's first row is q's last
+    assert fwd(lib, o=P + tb) == OK or fwd(lib, o=P + tb) == E_LAUNCH   # adjacent is fine (fake pointers: no GPU here)
+    assert bwd(lib, dk=P + 0x50_0000_0000 + 64) == E_UNSUP   # dk inside dq
+    assert bwd(lib, dv=P + 0x20_0000_0000 - 16) == E_UNSUP   # dv's tail reaches into v
+    f = lib.ltn_attn_decode_steps
+    assert f(P, P + (1 << 32), P + (2 << 32), P + (3 << 32), P + (3 << 32) + 256, P + (9 << 32), 2, 2, 4, 128, 1, None) == E_UNSUP
+    # kv_out == kv_in is the one allowed alias; a shifted overlap of the two is not
+    assert fwd(lib, kv_in=P + (7 << 32), kv_out=P + (7 << 32) + 4096) == E_UNSUP
+
+
+def test_debug_plan_and_plan_query(lib):
+    import torch
+    assert lib.ltn_attn_set_debug_plan(48, 0) == E_SHAPE
+    assert lib.ltn_attn_set_debug_plan(0, -1) == E_SHAPE
+    assert lib.ltn_attn_set_debug_plan(0, 5000) == E_SHAPE
+    assert ltn.ltn_attn_query_plan(4, 32, 8192, 128, torch.bfloat16, 0) == (64, 1)    # headline forward: two slices
+    assert ltn.ltn_attn_query_plan(4, 32, 8192, 128, torch.bfloat16, 1) == (128, 1)   # headline backward: full width
+    assert ltn.ltn_attn_query_plan(1, 2, 8192, 128, torch.bfloat16, 0) == (32, 8)       # 16 chain segments, four slices each
+    try:
+        ltn.ltn_attn_set_debug_plan(32, 3)
+        assert ltn.ltn_attn_query_plan(4, 32, 8192, 128, torch.bfloat16, 0) == (32, 3)
+        assert ltn.ltn_attn_workspace_bytes(4, 32, 8192, 128, 0, torch.bfloat16, 0) == 128 * 3 * 128 * 128 * 4
+    finally:
+        ltn.ltn_attn_set_debug_plan(0, 0)
+    assert ltn.ltn_attn_workspace_bytes(4, 32, 8192, 128, 0, torch.bfloat16, 0) == 0
+    dv, segs = ctypes.c_int(), ctypes.c_int()
+    assert lib.ltn_attn_query_plan(1, 1, 64, 128, 1, 0, None, ctypes.byref(segs)) == E_NULL
+    assert lib.ltn_attn_query_plan(1, 1, 64, 80, 1, 0, ctypes.byref(dv), ctypes.byref(segs)) == E_UNSUP
+    assert lib.ltn_attn_query_plan(1, 1, 64, 128, 1, 7, ctypes.byref(dv), ctypes.byref(segs)) == E_SHAPE
+
+
+def test_environment_does_not_change_the_plan(lib, monkeypatch):
+    import torch
+    monkeypatch.setenv("LTN_ATTN_DV", "32")
+    monkeypatch.setenv("LTN_ATTN_SEGS", "5")
+    assert ltn.ltn_attn_query_plan(4, 32, 8192, 128, torch.bfloat16, 0) == (64, 1)
+    assert ltn.ltn_attn_workspace_bytes(4, 32, 8192, 128, 0, torch.bfloat16, 0) == 0
 
 
 def test_workspace_query(lib):

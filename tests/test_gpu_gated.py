@@ -8,34 +8,11 @@ import torch
 import paper_2307_14995_amd as ltn
 from paper_2307_14995_amd import synth
 from oracle import ltn_oracle as orc
+from _helpers import TOL_ROW, check, check_rows, dev, force_plan, gpu, mixed_decay
 
 pytestmark = pytest.mark.gpu
 
 TOL = {torch.float32: 1e-4, torch.bfloat16: 1e-2}
-
-
-def dev():
-    return torch.device("cuda:0")
-
-
-def gpu(*ts):
-    return tuple(None if t is None else t.to(dev()) for t in ts)
-
-
-def check(name, got, ref, tol):
-    assert torch.isfinite(got.float()).all(), f"{name}: non-finite values"
-    err = orc.max_rel_l2(got, ref)
-    assert err <= tol, f"{name}: rel-L2 {err:.3e} > {tol:g}"
-
-
-def mixed_decay(H):
-    d = synth.decay_bench_rule(H).clone()
-    d[0] = 1.0
-    if H > 1:
-        d[1] = 0.0
-    if H > 2:
-        d[2] = float(np.exp(-8.0))
-    return d
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
@@ -140,19 +117,19 @@ def test_bf16_forward_gated_many_chains_fused_with_o():
 
 
 @pytest.mark.parametrize("segs,N", [(3, 517), (5, 1000)])
-def test_bf16_forward_gated_segmented(segs, N, monkeypatch):
+def test_bf16_forward_gated_segmented(segs, N):
     """The fused epilogue on chains cut into segments (forced), with an initial state."""
-    monkeypatch.setenv("LTN_ATTN_SEGS", str(segs))
     Bt, H, D = 1, 3, 128
     q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 460 + N)
     u = synth.make_gate(Bt, H, N, D, torch.bfloat16, 460 + N)
     kv0 = torch.randn(Bt, H, D, D, generator=torch.Generator().manual_seed(N)) * 0.1
     decay = mixed_decay(H)
-    assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 2) > 0
     o_ref, y_ref = orc.fwd_gated(q, k, v, u, decay, eps=1e-6, kv_in=kv0)
     _, kv_ref = orc.fwd_recurrent(q, k, v, decay, kv_in=kv0, return_state=True)
-    _, y, kv = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6, kv_in=kv0.to(dev()),
-                                      return_state=True, store_o=False)
+    with force_plan(segs=segs):
+        assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 2) > 0
+        _, y, kv = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6, kv_in=kv0.to(dev()),
+                                          return_state=True, store_o=False)
     check("Y", y, y_ref, 1e-2)
     check("kv", kv, kv_ref, 1e-2)
 
@@ -173,7 +150,11 @@ def test_bf16_forward_gated_few_long_chains_by_default():
 
 
 def test_training_chain_through_the_gate():
-    """fwd_gated (stores O) -> gate_bwd -> attn_bwd equals the oracle's chain rule."""
+    """fwd_gated (stores O) -> gate_bwd -> attn_bwd.  Every kernel is held to the 1e-2 bound
+    against the oracle applied to the inputs that kernel really saw (the stored bf16 O, the
+    stored bf16 dO); the chain end to end, whose error also holds the oracle's own sensitivity
+    to those two roundings (the norm's derivative amplifies an error in O about twofold), is
+    held to 2e-2."""
     Bt, H, N, D = 2, 3, 160, 128
     q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 47)
     u = synth.make_gate(Bt, H, N, D, torch.bfloat16, 47)
@@ -183,26 +164,40 @@ def test_training_chain_through_the_gate():
     o, y = ltn.ltn_attn_fwd_gated(qd, kd, vd, ud, dd, eps=1e-6)
     d_o, d_u = ltn.ltn_gate_bwd(o, ud, dyd, eps=1e-6)
     dq, dk, dv = ltn.ltn_attn_bwd(qd, kd, vd, d_o, dd)
-    o_ref, _ = orc.fwd_gated(q, k, v, u, decay, eps=1e-6)
+    # kernel by kernel, on the tensors each kernel was handed
+    o_ref, y_ref = orc.fwd_gated(q, k, v, u, decay, eps=1e-6)
+    check("O", o, o_ref, 1e-2)
+    check("Y", y, y_ref, 1e-2)
+    do_k, du_k = orc.gate_bwd(o.cpu(), u, dy, eps=1e-6)
+    check("dO | stored O", d_o, do_k, 1e-2)
+    check("dU | stored O", d_u, du_k, 1e-2)
+    for n, x, r in zip(("dQ", "dK", "dV"), (dq, dk, dv), orc.bwd_recurrent(q, k, v, d_o.cpu(), decay)):
+        check(n + " | stored dO", x, r, 1e-2)
+    # end to end against the oracle's own chain
     do_ref, du_ref = orc.gate_bwd(o_ref, u, dy, eps=1e-6)
-    check("dO", d_o, do_ref, 2e-2)          # two bf16 roundings deep (O stored, then dO)
+    check("dO", d_o, do_ref, 2e-2)
     check("dU", d_u, du_ref, 1e-2)
     for n, x, r in zip(("dQ", "dK", "dV"), (dq, dk, dv), orc.bwd_recurrent(q, k, v, do_ref, decay)):
         check(n, x, r, 2e-2)
 
 
-def test_forward_gated_full_size_sampled_chains():
-    """The 7B-shaped workload in the launch configuration the report times; sampled chains."""
+def test_forward_gated_full_size_every_chain():
+    """The 7B-shaped workload in the launch configuration the report times: every chain's Y
+    against the oracle, slice by slice and token by token."""
     w = synth.CONFIGS["cfg3_7b"]
     q, k, v = synth.make_qkv(w.Bt, w.H, w.N, w.D, w.dtype, w.seed)
     u = synth.make_gate(w.Bt, w.H, w.N, w.D, w.dtype, w.seed)
     decay = synth.decay_bench_rule(w.H)
     _, y = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6, store_o=False)
-    for b, h in ((0, 0), (1, 17), (3, 31)):
-        sl = (slice(b, b + 1), slice(h, h + 1))
-        o_ref = orc.fwd_recurrent(q[sl], k[sl], v[sl], decay[h:h + 1])
+    y = y.cpu()
+    worst = 0.0
+    for b in range(w.Bt):
+        sl = slice(b, b + 1)
+        o_ref = orc.fwd_recurrent(q[sl], k[sl], v[sl], decay)
         y_ref = orc.gate_fwd(o_ref, u[sl], 1e-6)
-        assert orc.rel_l2(y[sl], y_ref) <= 1e-2, (b, h)
+        check(f"Y[{b}]", y[sl], y_ref, 1e-2)
+        worst = max(worst, check_rows(f"Y[{b}] rows", y[sl], y_ref, TOL_ROW[w.dtype]))
+    print(f"gated cfg3: worst per-token error {worst:.2e}")
 
 
 def test_forward_gated_argument_errors():

@@ -9,35 +9,12 @@ import torch
 import paper_2307_14995_amd as ltn
 from paper_2307_14995_amd import synth
 from oracle import ltn_oracle as orc
+from _helpers import check, dev, gpu, mixed_decay
 
 pytestmark = pytest.mark.gpu
 
 TOL = {torch.float32: 1e-4, torch.bfloat16: 1e-2}
 SHAPES = [(256, 128), (128, 64)]
-
-
-def dev():
-    return torch.device("cuda:0")
-
-
-def gpu(*ts):
-    return tuple(None if t is None else t.to(dev()) for t in ts)
-
-
-def check(name, got, ref, tol):
-    assert torch.isfinite(got.float()).all(), f"{name}: non-finite values"
-    err = orc.max_rel_l2(got, ref)
-    assert err <= tol, f"{name}: rel-L2 {err:.3e} > {tol:g}"
-
-
-def mixed_decay(H):
-    d = synth.decay_bench_rule(H).clone()
-    d[0] = 1.0
-    if H > 1:
-        d[1] = 0.0
-    if H > 2:
-        d[2] = float(np.exp(-8.0))
-    return d
 
 
 # ------------------------------------------------------------------ attention, Dk = 2 Dv
