@@ -63,7 +63,8 @@ typedef enum {
     LTN_ERR_UNSUPPORTED = 3, /* D / block / dtype combination not built, aliasing   */
     LTN_ERR_ALIGN = 4,       /* a tensor pointer is not 16-byte aligned             */
     LTN_ERR_DECAY = 5,       /* ltn_attn_check_decay: a value outside [0, 1] or NaN */
-    LTN_ERR_LAUNCH = 6       /* the HIP runtime refused the launch                  */
+    LTN_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                  */
+    LTN_ERR_SCRATCH = 7      /* ltn_attn_fwd_static: needs more than the static scratch */
 } ltn_status;
 
 typedef enum { LTN_F32 = 0, LTN_BF16 = 1 } ltn_dtype;
@@ -88,6 +89,29 @@ ltn_status ltn_attn_fwd(const void* q, const void* k, const void* v, void* o,
                         const float* decay, const float* kv_in, float* kv_out,
                         int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ltn_attn_fwd for callers that cannot allocate device memory and so have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results (bit for bit) and errors as ltn_attn_fwd, without
+ * the workspace pair: where ltn_attn_fwd would use a workspace (few long chains, cut into
+ * segments), this entry point uses a scratch buffer of LTN_ATTN_STATIC_SCRATCH_BYTES that
+ * is part of the library's device code (every GPU the library runs on holds one copy
+ * until the process ends).  It calls no hipMalloc / hipFree and no allocating routine.
+ *   - A call whose plan needs more scratch than that returns LTN_ERR_SCRATCH and launches
+ *     nothing (the library's own plans need at most 16 MiB: 256 segment states of 64 KB).
+ *   - The device that owns `stream` must be the current device.  The first call on a
+ *     device looks up the buffer's address (once per device); make that call outside graph
+ *     capture.
+ *   - All calls on one GPU share the one buffer: calls that overlap in time on the same GPU
+ *     (different streams, different threads) race and must be serialised by the caller.
+ *     Its contents are scratch and mean nothing between calls.
+ */
+#define LTN_ATTN_STATIC_SCRATCH_BYTES (16u << 20)
+ltn_status ltn_attn_fwd_static(const void* q, const void* k, const void* v, void* o,
+                               const float* decay, const float* kv_in, float* kv_out,
+                               int Bt, int H, long long N, int D, int block, ltn_dtype dtype,
+                               void* stream);
 
 /*
  * Forward pass with the token mixer's epilogue fused in (Sec. 3.1.2, Eq. 3:

@@ -22,7 +22,7 @@ SYMBOLS = (
     "ltn_attn_workspace_bytes", "ltn_attn_check_decay", "ltn_status_str",
     "ltn_prologue_fwd", "ltn_prologue_bwd", "ltn_prologue_workspace_bytes",
     "ltn_attn_fwd_dkdv", "ltn_attn_bwd_dkdv", "ltn_attn_decode_steps_dkdv",
-    "ltn_attn_query_plan", "ltn_attn_set_debug_plan",
+    "ltn_attn_query_plan", "ltn_attn_set_debug_plan", "ltn_attn_fwd_static",
 )
 
 
@@ -85,6 +85,8 @@ def load_library():
     lib.ltn_attn_bwd_dkdv.restype = ci
     lib.ltn_attn_decode_steps_dkdv.argtypes = [vp, vp, vp, vp, fp, fp, ci, ci, ci, ci, ci, ci, vp]
     lib.ltn_attn_decode_steps_dkdv.restype = ci
+    lib.ltn_attn_fwd_static.argtypes = [vp, vp, vp, vp, fp, fp, fp, ci, ci, cl, ci, ci, ci, vp]
+    lib.ltn_attn_fwd_static.restype = ci
     lib.ltn_attn_query_plan.argtypes = [ci, ci, cl, ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
     lib.ltn_attn_query_plan.restype = ci
     lib.ltn_attn_set_debug_plan.argtypes = [ci, ci]
@@ -184,6 +186,32 @@ def ltn_attn_fwd(q, k, v, decay, kv_in=None, return_state=False, block=0, out=No
     if rc != 0:
         raise LtnError(rc, "ltn_attn_fwd")
     return (o, kv_out) if (return_state or kv_out is not None) else o
+
+
+def ltn_attn_fwd_static(q, k, v, decay, out, kv_in=None, kv_out=None, block=0):
+    """ltn_attn_fwd through the library's static scratch: every buffer comes from the caller,
+    nothing is allocated here or in the library.  Returns `out`."""
+    lib = load_library()
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (decay, "decay"), (out, "out")):
+        _dev(t, n)
+    if q.shape != k.shape or q.shape != v.shape or q.shape != out.shape or q.dim() != 4:
+        raise ValueError("q, k, v, out must be [Bt,H,N,D] tensors of one shape")
+    if not (q.dtype == k.dtype == v.dtype == out.dtype):
+        raise ValueError("q, k, v, out must share a dtype")
+    Bt, H, N, D = q.shape
+    if decay.dtype != torch.float32 or decay.numel() != H:
+        raise ValueError("decay must be fp32 [H]")
+    for t, n in ((kv_in, "kv_in"), (kv_out, "kv_out")):
+        if t is not None:
+            _dev(t, n)
+            if t.dtype != torch.float32 or tuple(t.shape) != (Bt, H, D, D):
+                raise ValueError(f"{n} must be fp32 [Bt,H,D,D]")
+    with torch.cuda.device(q.device):
+        rc = lib.ltn_attn_fwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(decay), _ptr(kv_in), _ptr(kv_out),
+                                     Bt, H, N, D, int(block), _dtype_code(q.dtype), _stream(q.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_fwd_static")
+    return out
 
 
 def ltn_attn_fwd_gated(q, k, v, u, decay, eps=0.0, kv_in=None, return_state=False, store_o=True, block=0,

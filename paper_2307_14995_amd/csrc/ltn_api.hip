@@ -162,6 +162,31 @@ ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void*
     return ltn::launch_pass_bf16(main, D, dv, stream) == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
 }
 
+// Scratch of ltn_attn_fwd_static: device memory that belongs to the library's code object,
+// so that entry point needs no allocation and no caller workspace.  Every GPU the library
+// runs on holds its own copy at its own address until the process ends; in host code the
+// array's name is only a handle for hipGetSymbolAddress, never an address to pass on.
+constexpr size_t kScratchBytes = (size_t)LTN_ATTN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up once per device).
+ltn_status scratch_on_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LTN_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LTN_ERR_LAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LTN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -221,6 +246,7 @@ const char* ltn_status_str(ltn_status s) {
         case LTN_ERR_ALIGN: return "LTN_ERR_ALIGN: tensor pointer not 16-byte aligned";
         case LTN_ERR_DECAY: return "LTN_ERR_DECAY: decay value outside [0, 1]";
         case LTN_ERR_LAUNCH: return "LTN_ERR_LAUNCH: HIP launch failed";
+        case LTN_ERR_SCRATCH: return "LTN_ERR_SCRATCH: the call needs more scratch than the library's static buffer holds";
     }
     return "LTN_ERR_?: unknown status";
 }
@@ -293,6 +319,20 @@ ltn_status ltn_attn_fwd(const void* q, const void* k, const void* v, void* o,
                         void* workspace, size_t workspace_bytes, void* stream) {
     return fwd_common(q, k, v, nullptr, o, nullptr, decay, kv_in, kv_out, 0.0f, Bt, H, N, D, block, dtype,
                       workspace, workspace_bytes, stream, false);
+}
+
+ltn_status ltn_attn_fwd_static(const void* q, const void* k, const void* v, void* o,
+                               const float* decay, const float* kv_in, float* kv_out,
+                               int Bt, int H, long long N, int D, int block, ltn_dtype dtype, void* stream) {
+    // the plan (and so the scratch it needs) is the one ltn_attn_fwd would take
+    if (ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, 0) > kScratchBytes) return LTN_ERR_SCRATCH;
+    void* ws = nullptr;
+    const ltn_status s = scratch_on_current_device(&ws);
+    if (s != LTN_OK) return s;
+    // Nothing in the scratch has to start at zero: the scan reads exactly the segment end
+    // states that the state-only sweep of the same call has written.
+    return fwd_common(q, k, v, nullptr, o, nullptr, decay, kv_in, kv_out, 0.0f, Bt, H, N, D, block, dtype,
+                      ws, kScratchBytes, stream, false);
 }
 
 ltn_status ltn_attn_fwd_gated(const void* q, const void* k, const void* v, const void* u, void* o, void* y,
