@@ -462,23 +462,32 @@ def extended_report(ltn, synth, torch, dev, sections=""):
             del q, k, v, u, g, o, y, dx, du
 
     def section_tiled():
-        # the paper's quadratic tiling (App. B Algorithm 3) against the state recurrence, forward only
+        # the paper's quadratic tilings (App. B Algorithms 3 and 4) against the state recurrence
         Bt, H = 4, 32
         dd = synth.decay_bench_rule(H).to(dev)
         for N in (128, 256, 512, 1024, 2048, 4096, 8192):
             q, k, v = (torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).div_(D ** 0.5).to(torch.bfloat16)
                        for _ in range(3))
+            g = torch.randn(Bt, H, N, D, device=dev, dtype=torch.float32).to(torch.bfloat16)
             o = torch.empty_like(q)
+            gr = tuple(torch.empty_like(q) for _ in range(3))
+            few = 5 if N >= 4096 else 20
             t_rec = time_call(lambda: ltn.ltn_attn_fwd(q, k, v, dd, out=o), n=20, warm=5)
-            t_til = time_call(lambda: ltn.ltn_attn_fwd_tiled(q, k, v, dd, out=o), n=5 if N >= 4096 else 20, warm=2)
+            t_til = time_call(lambda: ltn.ltn_attn_fwd_tiled(q, k, v, dd, out=o), n=few, warm=2)
+            b_rec = time_call(lambda: ltn.ltn_attn_bwd(q, k, v, g, dd, out=gr), n=20, warm=5)
+            b_til = time_call(lambda: ltn.ltn_attn_bwd_tiled(q, k, v, g, dd, out=gr), n=few, warm=2)
             T = N // 64
             tile_pairs = Bt * H * T * (T + 1) // 2
             print(json.dumps({"workload": "tiled_vs_recurrence", "Bt": Bt, "H": H, "N": N,
                               "recurrence_ms": round(t_rec, 4), "tiled_ms": round(t_til, 4),
                               "tiled_over_recurrence": round(t_til / t_rec, 2),
-                              "tiled_TFLOPs_full_tiles": round(tile_pairs * 4 * 64 * 64 * D / (t_til * 1e-3) / 1e12, 1)}),
+                              "tiled_TFLOPs_full_tiles": round(tile_pairs * 4 * 64 * 64 * D / (t_til * 1e-3) / 1e12, 1),
+                              "bwd_recurrence_ms": round(b_rec, 4), "bwd_tiled_ms": round(b_til, 4),
+                              "bwd_tiled_over_recurrence": round(b_til / b_rec, 2),
+                              # Algorithm 4 without atomics: six tile products per (i, j) pair
+                              "bwd_tiled_TFLOPs_full_tiles": round(tile_pairs * 12 * 64 * 64 * D / (b_til * 1e-3) / 1e12, 1)}),
                   file=sys.stderr, flush=True)
-            del q, k, v, o
+            del q, k, v, g, o, gr
 
     def section_lrpe():
         # first layer: swish + LRPE-d expansion of queries and keys (Eq. 1, Eq. 2), then the attention with

@@ -64,10 +64,16 @@ typedef enum {
     LTN_ERR_ALIGN = 4,       /* a tensor pointer is not 16-byte aligned             */
     LTN_ERR_DECAY = 5,       /* ltn_attn_check_decay: a value outside [0, 1] or NaN */
     LTN_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                  */
-    LTN_ERR_SCRATCH = 7      /* ltn_attn_fwd_static: needs more than the static scratch */
+    LTN_ERR_SCRATCH = 7,     /* ltn_attn_fwd_static: needs more than the static scratch */
+    /* not status codes: they make every int a valid value of the type, so that a caller
+     * (or a foreign-function binding) passing an unknown code is an error path, not
+     * undefined behaviour in a C++ implementation */
+    LTN_STATUS_INT_MIN_ = -2147483647 - 1, LTN_STATUS_INT_MAX_ = 2147483647
 } ltn_status;
 
-typedef enum { LTN_F32 = 0, LTN_BF16 = 1 } ltn_dtype;
+typedef enum { LTN_F32 = 0, LTN_BF16 = 1,
+               LTN_DTYPE_INT_MIN_ = -2147483647 - 1, LTN_DTYPE_INT_MAX_ = 2147483647 /* as above */
+} ltn_dtype;
 
 /*
  * Forward pass (Sec. 3.2.1; App. B Algorithm 3 computes the same O with a
@@ -166,6 +172,20 @@ ltn_status ltn_gate_bwd(const void* x, const void* u, const void* d_y, void* d_x
  *   q, k, v in : device, [Bt,H,N,D] bf16      o out: device, [Bt,H,N,D] bf16
  */
 ltn_status ltn_attn_fwd_tiled(const void* q, const void* k, const void* v, void* o, const float* decay,
+                              int Bt, int H, long long N, int D, ltn_dtype dtype, void* stream);
+
+/*
+ * The gradients by the paper's own evaluation order (App. B, Algorithm 4, with its misprints
+ * corrected as in ltn_attn_bwd): one workgroup per block of 64 keys/values keeps K_j, V_j on
+ * chip, loops over all query blocks i >= j and accumulates dK_j and dV_j; dQ_i comes from a
+ * second kind of workgroup that loops over j <= i and forms dA_ij = (dO_i V_j^T) (.) M_ij
+ * again, in place of the listing's read-modify-write of dQ_i in memory (no atomics).
+ * Quadratic in N; a comparison kernel like ltn_attn_fwd_tiled, bf16 only, D in {64, 128}.
+ *
+ *   q, k, v, d_o in : device, [Bt,H,N,D] bf16      dq, dk, dv out: device, [Bt,H,N,D] bf16
+ */
+ltn_status ltn_attn_bwd_tiled(const void* q, const void* k, const void* v, const void* d_o,
+                              void* dq, void* dk, void* dv, const float* decay,
                               int Bt, int H, long long N, int D, ltn_dtype dtype, void* stream);
 
 /*

@@ -22,7 +22,7 @@ SYMBOLS = (
     "ltn_attn_workspace_bytes", "ltn_attn_check_decay", "ltn_status_str",
     "ltn_prologue_fwd", "ltn_prologue_bwd", "ltn_prologue_workspace_bytes",
     "ltn_attn_fwd_dkdv", "ltn_attn_bwd_dkdv", "ltn_attn_decode_steps_dkdv",
-    "ltn_attn_query_plan", "ltn_attn_set_debug_plan", "ltn_attn_fwd_static",
+    "ltn_attn_query_plan", "ltn_attn_set_debug_plan", "ltn_attn_fwd_static", "ltn_attn_bwd_tiled",
 )
 
 
@@ -55,6 +55,8 @@ def load_library():
     lib.ltn_attn_fwd_gated.restype = ci
     lib.ltn_attn_fwd_tiled.argtypes = [vp, vp, vp, vp, fp, ci, ci, cl, ci, ci, vp]
     lib.ltn_attn_fwd_tiled.restype = ci
+    lib.ltn_attn_bwd_tiled.argtypes = [vp, vp, vp, vp, vp, vp, vp, fp, ci, ci, cl, ci, ci, vp]
+    lib.ltn_attn_bwd_tiled.restype = ci
     lib.ltn_gate_fwd.argtypes = [vp, vp, vp, cf, cl, ci, ci, vp]
     lib.ltn_gate_fwd.restype = ci
     lib.ltn_gate_bwd.argtypes = [vp, vp, vp, vp, vp, cf, cl, ci, ci, vp]
@@ -375,6 +377,30 @@ def ltn_attn_fwd_tiled(q, k, v, decay, out=None):
     if rc != 0:
         raise LtnError(rc, "ltn_attn_fwd_tiled")
     return o
+
+
+def ltn_attn_bwd_tiled(q, k, v, d_o, decay, out=None):
+    """(dQ, dK, dV) by the quadratic tile loops of App. B Algorithm 4 (comparison kernel, bf16)."""
+    lib = load_library()
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (d_o, "d_o"), (decay, "decay")):
+        _dev(t, n)
+    if not (q.shape == k.shape == v.shape == d_o.shape) or q.dim() != 4:
+        raise ValueError("q, k, v, d_o must be [Bt,H,N,D] tensors of one shape")
+    if not (q.dtype == k.dtype == v.dtype == d_o.dtype):
+        raise ValueError("q, k, v, d_o must share a dtype")
+    Bt, H, N, D = q.shape
+    if decay.dtype != torch.float32 or decay.numel() != H:
+        raise ValueError("decay must be fp32 [H]")
+    if out is None:
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    else:
+        dq, dk, dv = (_dev(t, "out") for t in out)
+    with torch.cuda.device(q.device):
+        rc = lib.ltn_attn_bwd_tiled(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(decay),
+                                    Bt, H, N, D, _dtype_code(q.dtype), _stream(q.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_attn_bwd_tiled")
+    return dq, dk, dv
 
 
 def ltn_prologue_workspace_bytes(Bt, H, N, D) -> int:

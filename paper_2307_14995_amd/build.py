@@ -42,8 +42,17 @@ def _headers():
     return glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
 
 
-def _obj_of(src: str) -> str:
-    return os.path.join(OBJ, os.path.basename(src) + ".o")
+# Host-side sanitizer build (a checker's build, never what the product loads): AddressSanitizer and
+# UndefinedBehaviorSanitizer on the host code only -- argument validation, plan selection, launch
+# wrappers -- with the device code compiled as usual.
+SAN_OBJ = os.path.join(PKG, "_build_san")
+SAN_LIB = os.path.join(SAN_OBJ, "libltn_attn_san.so")
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-omit-frame-pointer", "-Xarch_host", "-fno-sanitize-recover=undefined"]
+
+
+def _obj_of(src: str, objdir: str = OBJ) -> str:
+    return os.path.join(objdir, os.path.basename(src) + ".o")
 
 
 def _stale(target: str, deps) -> bool:
@@ -73,9 +82,9 @@ def check_resource_report(report: str) -> None:
         raise RuntimeError("kernels with register-resident asynchronous loads must not spill:\n  " + "\n  ".join(bad))
 
 
-def _compile(src: str, hipcc: str, verbose: bool) -> str:
-    obj = _obj_of(src)
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-c", src, "-o", obj]
+def _compile(src: str, hipcc: str, verbose: bool, objdir: str = OBJ, extra=()) -> str:
+    obj = _obj_of(src, objdir)
+    cmd = [hipcc] + HIPCC_FLAGS + list(extra) + ["-I", os.path.join(ROOT, "include"), "-c", src, "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -107,6 +116,37 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
         if res.returncode != 0:
             raise RuntimeError("link failed:\n" + res.stdout + res.stderr)
     return LIB
+
+
+def sanitizer_runtime() -> str:
+    """Path of the shared AddressSanitizer runtime of the compiler that hipcc drives."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    res = subprocess.run([hipcc, "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True)
+    path = res.stdout.strip()
+    if not os.path.isabs(path):
+        cands = glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so")
+        path = cands[0] if cands else ""
+    return path
+
+
+def build_sanitized(verbose: bool = False) -> str:
+    """The same sources with ASan + UBSan on the host code, linked against the shared sanitizer
+    runtime, into _build_san/ (only what is stale is recompiled)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(SAN_OBJ, exist_ok=True)
+    srcs = sources()
+    todo = [s for s in srcs if _stale(_obj_of(s, SAN_OBJ), [s] + _headers())]
+    jobs = int(os.environ.get("MAX_JOBS", "8") or 8)
+    with ThreadPoolExecutor(max_workers=max(1, min(jobs, 16))) as pool:
+        list(pool.map(lambda s: _compile(s, hipcc, verbose, SAN_OBJ, SAN_FLAGS), todo))
+    objs = [_obj_of(s, SAN_OBJ) for s in srcs]
+    if todo or _stale(SAN_LIB, objs):
+        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined",
+               "-shared-libsan"] + objs + ["-o", SAN_LIB]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("sanitizer link failed:\n" + res.stdout + res.stderr)
+    return SAN_LIB
 
 
 if __name__ == "__main__":

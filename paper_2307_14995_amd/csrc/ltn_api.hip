@@ -247,6 +247,7 @@ const char* ltn_status_str(ltn_status s) {
         case LTN_ERR_DECAY: return "LTN_ERR_DECAY: decay value outside [0, 1]";
         case LTN_ERR_LAUNCH: return "LTN_ERR_LAUNCH: HIP launch failed";
         case LTN_ERR_SCRATCH: return "LTN_ERR_SCRATCH: the call needs more scratch than the library's static buffer holds";
+        default: break;
     }
     return "LTN_ERR_?: unknown status";
 }
@@ -362,6 +363,26 @@ ltn_status ltn_attn_fwd_tiled(const void* q, const void* k, const void* v, void*
     if (empty) return LTN_OK;
     return ltn::launch_tiled_fwd_bf16(q, k, v, o, decay, Bt * H, H, N, D, static_cast<hipStream_t>(stream)) ==
                    hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+}
+
+ltn_status ltn_attn_bwd_tiled(const void* q, const void* k, const void* v, const void* d_o,
+                              void* dq, void* dk, void* dv, const float* decay,
+                              int Bt, int H, long long N, int D, ltn_dtype dtype, void* stream) {
+    const bool empty = (Bt == 0 || H == 0 || N == 0);
+    if (!decay || (!empty && (!q || !k || !v || !d_o || !dq || !dk || !dv))) return LTN_ERR_NULL;
+    if (Bt < 0 || H < 0 || N < 0 || D <= 0) return LTN_ERR_SHAPE;
+    if (dtype != LTN_BF16 || (D != 64 && D != 128)) return LTN_ERR_UNSUPPORTED;
+    if ((long long)Bt * H > 0x3fffffffLL) return LTN_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) ||
+        !aligned16(dk) || !aligned16(dv) || (reinterpret_cast<uintptr_t>(decay) & 3u))
+        return LTN_ERR_ALIGN;
+    if (empty) return LTN_OK;
+    const size_t tb = (size_t)Bt * H * (size_t)N * D * esize_of(dtype);
+    const Span ins[4] = {{q, tb}, {k, tb}, {v, tb}, {d_o, tb}};
+    const Span outs[3] = {{dq, tb}, {dk, tb}, {dv, tb}};
+    if (outputs_alias(outs, 3, ins, 4)) return LTN_ERR_UNSUPPORTED;
+    return ltn::launch_tiled_bwd_bf16(q, k, v, d_o, dq, dk, dv, decay, Bt * H, H, N, D,
+                                      static_cast<hipStream_t>(stream)) == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
 }
 
 static ltn_status gate_common(const void* x, const void* u, const void* d_y, void* o0, void* o1, float eps,

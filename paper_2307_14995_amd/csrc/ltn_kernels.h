@@ -62,6 +62,11 @@ hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stre
 // initial state, D in {64,128}.
 hipError_t launch_tiled_fwd_bf16(const void* q, const void* k, const void* v, void* o, const float* decay,
                                  int chains, int H, long long N, int D, hipStream_t stream);
+// Gradients by the tiling of App. B Algorithm 4 (comparison kernel), bf16, D in {64,128}: one
+// workgroup per key/value block (dK, dV) and one per query block (dQ), in one launch.
+hipError_t launch_tiled_bwd_bf16(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk,
+                                 void* dv, const float* decay, int chains, int H, long long N, int D,
+                                 hipStream_t stream);
 // fp32 kernel.  D in {64,96,128,256}, block in {16,32,64}, D*block <= 4096 (D = 256: dv = 64;
 // D = 96: dv = 32, block 16 or 32).
 hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStream_t stream, int DC = 0);

@@ -18,9 +18,9 @@ from paper_2307_14995_amd import synth
 from oracle import ltn_oracle as orc
 
 TOL = {torch.float32: 1e-4, torch.bfloat16: 1e-2}
-# per-token bound: 3x the slice bound (the largest of ~1e6 rows of a Gaussian-error population
-# sits about 1.5x above the typical one in L2 over 128 features; inputs of unusual size add the rest)
-TOL_ROW = {torch.float32: 3e-4, torch.bfloat16: 3e-2}
+# per-token bound: measured worst rows of the full-size workloads sit at 2.4e-3 .. 4.9e-3 (bf16; the
+# denominator holds the floor, so a typical row reads about half its relative error); 3x that.
+TOL_ROW = {torch.float32: 2e-4, torch.bfloat16: 1.5e-2}
 
 
 def dev():

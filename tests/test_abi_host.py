@@ -188,6 +188,22 @@ def test_fwd_tiled_argument_errors(lib):
     assert call(N=0) == OK
 
 
+def test_bwd_tiled_argument_errors(lib):
+    f = lib.ltn_attn_bwd_tiled
+
+    def call(q=P, k=P + (1 << 36), v=P + (2 << 36), g=P + (3 << 36), dq=P + (5 << 36), dk=P + (6 << 36),
+             dv=P + (7 << 36), decay=P + (4 << 36), Bt=1, H=2, N=256, D=128, dtype=1):
+        return f(q, k, v, g, dq, dk, dv, decay, Bt, H, N, D, dtype, None)
+
+    assert call(g=None) == E_NULL and call(dq=None) == E_NULL and call(decay=None) == E_NULL
+    assert call(N=-1) == E_SHAPE
+    assert call(dtype=0) == E_UNSUP                        # bf16 only
+    assert call(D=96) == E_UNSUP
+    assert call(dk=P + (6 << 36) + 2) == E_ALIGN
+    assert call(dv=P + (2 << 36) + 64) == E_UNSUP          # dv starts inside v
+    assert call(N=0) == OK and call(Bt=0) == OK
+
+
 def test_gate_argument_errors(lib):
     cf = ctypes.c_float
     fw, bw = lib.ltn_gate_fwd, lib.ltn_gate_bwd

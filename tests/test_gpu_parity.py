@@ -485,6 +485,39 @@ def test_bf16_tiled_forward_many_chains_long():
         ltn.ltn_attn_fwd_tiled(*gpu(q.float(), k.float(), v.float(), decay))     # bf16 only
 
 
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("N", [1, 63, 64, 65, 200, 517])
+def test_bf16_tiled_backward(D, N):
+    """App. B Algorithm 4 (corrected) evaluated on the GPU: the gradients of the definition, by
+    the quadratic tile loops (one workgroup per key/value block for dK, dV; one per query block
+    for dQ)."""
+    Bt, H = 1, 3
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 820 + N)
+    g = synth.make_do(Bt, H, N, D, torch.bfloat16, 820 + N)
+    for name, decay in decays(H).items():
+        outs = ltn.ltn_attn_bwd_tiled(*gpu(q, k, v, g, decay))
+        for n, x, r in zip(("dQ", "dK", "dV"), outs, orc.bwd_quadratic(q, k, v, g, decay)):
+            check(f"{n}[{name}]", x, r, 1e-2)
+
+
+def test_bf16_tiled_backward_many_chains_long():
+    Bt, H, N, D = 2, 8, 1500, 128           # 16 chains (XCD-grouped), 24 blocks each, ragged tail
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 89)
+    g = synth.make_do(Bt, H, N, D, torch.bfloat16, 89)
+    decay = synth.decay_bench_rule(H)
+    poison = tuple(torch.full((Bt, H, N, D), float("nan"), dtype=torch.bfloat16, device=dev()) for _ in range(3))
+    outs = ltn.ltn_attn_bwd_tiled(*gpu(q, k, v, g, decay), out=poison)
+    refs = orc.bwd_recurrent(q, k, v, g, decay)
+    for n, x, r in zip(("dQ", "dK", "dV"), outs, refs):
+        check(n, x, r, 1e-2)
+        check_rows(n + " rows", x, r, TOL_ROW[torch.bfloat16])
+    again = ltn.ltn_attn_bwd_tiled(*gpu(q, k, v, g, decay))
+    for a, b in zip(outs, again):
+        assert torch.equal(a, b)             # no atomics: reproducible bit for bit
+    with pytest.raises(ltn.LtnError):
+        ltn.ltn_attn_bwd_tiled(*gpu(q.float(), k.float(), v.float(), g.float(), decay))     # bf16 only
+
+
 # --------------------------------------------------------------------------- cost linear in N
 
 
