@@ -24,6 +24,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
+MFMA_FP32_PEAK_TFLOPS = 157.3   # MI355X published fp32 matrix rate
 
 
 def flops_per_token_head(D: int, B: int, plan_fwd=(0, 1), plan_bwd=(0, 1)):
@@ -55,7 +56,7 @@ def kernel_source_hash() -> str:
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2307_14995_amd", "csrc")
-    for name in ("ltn_pass_bf16.hip", "ltn_bf16_tiles.h", "ltn_kernels.h", "ltn_api.hip"):
+    for name in ("ltn_pass_bf16.hip", "ltn_pass_f32_mfma.hip", "ltn_bf16_tiles.h", "ltn_kernels.h", "ltn_api.hip"):
         with open(os.path.join(csrc, name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]
@@ -111,9 +112,13 @@ def write_traffic_profile(workload: str, fetch_csv: str, write_csv: str) -> int:
     out["scale"] = {"FETCH_SIZE": round(sf, 4), "WRITE_SIZE": round(sw, 4)}
     for name in fetch:
         m = re.search(r"pass_bf16_kernel<(\d+), (\d+), (\d+)", name)
-        if not m or name not in write:
+        mf = re.search(r"pass_f32_mfma_kernel<(\d+), (\d+), (\d+)", name)
+        if not (m or mf) or name not in write:
             continue
-        key = f"pass_bf16_kernel<{m.group(1)},{m.group(2)}>" + ("" if m.group(3) == "0" else f" mode {m.group(3)}")
+        if m:
+            key = f"pass_bf16_kernel<{m.group(1)},{m.group(2)}>" + ("" if m.group(3) == "0" else f" mode {m.group(3)}")
+        else:
+            key = f"pass_f32_mfma_kernel<{mf.group(1)},{mf.group(2)},{mf.group(3)}>"
         rd = sum(fetch[name]) / len(fetch[name]) * 1024.0 * sf
         wr = sum(write[name]) / len(write[name]) * 1024.0 * sw
         out["kernels"][key] = {"launches": len(fetch[name]), "read_bytes_per_launch": round(rd),
@@ -141,7 +146,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", action="store_true")
     ap.add_argument("--sections", default="",
-                    help="with --report: comma-separated subset of machine,shapes,gated,tiled,lrpe,dims,decode")
+                    help="with --report: comma-separated subset of machine,shapes,fp32,gated,tiled,lrpe,dims,decode")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one untimed 1 GiB device-to-device copy, so that a counter run "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic")
@@ -240,23 +245,38 @@ def main() -> int:
     tflops = {n: f * token_heads / (ms_per_step * 1e-3) / 1e12 for n, f in fl.items()}
 
     # Dominant kernel: the backward launch (all three gradients in one kernel).
-    bwd_kernel = f"pass_bf16_kernel<{w.D},{plan_b[0]}>" if w.dtype == torch.bfloat16 else f"pass_f32_kernel<{w.D},{plan_b[0]}>"
+    bwd_kernel = f"pass_bf16_kernel<{w.D},{plan_b[0]}>" if w.dtype == torch.bfloat16 else f"pass_f32_mfma_kernel<{w.D},{plan_b[0]},{block}>"
     bwd_bytes = ab["bwd"] * token_heads
     achieved = bwd_bytes / (bwd_ms * 1e-3) / 1e9
-    roofline = {
-        "bound": "hbm",
-        "kernel": bwd_kernel + " (the backward launch: dV, dK and dQ passes of every chain"
-                  + (f", {plan_b[1]} segments per chain" if plan_b[1] > 1 else "") + ")",
-        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": stored_traffic(args.workload, bwd_kernel),
-        "algorithmic_bytes": bwd_bytes,
-        "kernel_ms": round(bwd_ms, 4),
-        "kernel_ms_median": round(bwd_t[len(bwd_t) // 2], 4), "kernel_ms_min": round(bwd_t[0], 4),
-        "fwd_kernel_ms": round(fwd_ms, 4),
-        "fwd_kernel_ms_median": round(fwd_t[len(fwd_t) // 2], 4), "fwd_kernel_ms_min": round(fwd_t[0], 4),
-        "fwd_achieved_GBs": round(ab["fwd"] * token_heads / (fwd_ms * 1e-3) / 1e9, 1),
-    }
+    if w.dtype == torch.float32:
+        # fp32 tensors: the matrix cores' fp32 rate bounds the launch, not memory.  FLOPs the backward launch
+        # issues per token-head: three passes, each with causal score tiles ((B/16+1)/2 of B/16 per 16-token
+        # strip, recomputed per value-column slice), the same share of P C, and 4 D^2 of state products.
+        causal = (block / 16 + 1) / 2 * 16
+        bwd_flops = 3 * (2 * causal * w.D * (w.D // plan_b[0]) + 2 * causal * w.D + 4 * w.D * w.D) * token_heads
+        ach_t = bwd_flops / (bwd_ms * 1e-3) / 1e12
+        roofline = {
+            "bound": "mfma", "kernel": bwd_kernel + " (the backward launch: dV, dK and dQ passes of every chain)",
+            "achieved": round(ach_t, 1), "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(ach_t / MFMA_FP32_PEAK_TFLOPS, 4), "traffic": stored_traffic(args.workload, bwd_kernel),
+            "issued_flops": bwd_flops, "kernel_ms": round(bwd_ms, 4), "fwd_kernel_ms": round(fwd_ms, 4),
+            "hbm_achieved_GBs": round(achieved, 1),
+        }
+    else:
+        roofline = {
+            "bound": "hbm",
+            "kernel": bwd_kernel + " (the backward launch: dV, dK and dQ passes of every chain"
+                      + (f", {plan_b[1]} segments per chain" if plan_b[1] > 1 else "") + ")",
+            "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": stored_traffic(args.workload, bwd_kernel),
+            "algorithmic_bytes": bwd_bytes,
+            "kernel_ms": round(bwd_ms, 4),
+            "kernel_ms_median": round(bwd_t[len(bwd_t) // 2], 4), "kernel_ms_min": round(bwd_t[0], 4),
+            "fwd_kernel_ms": round(fwd_ms, 4),
+            "fwd_kernel_ms_median": round(fwd_t[len(fwd_t) // 2], 4), "fwd_kernel_ms_min": round(fwd_t[0], 4),
+            "fwd_achieved_GBs": round(ab["fwd"] * token_heads / (fwd_ms * 1e-3) / 1e9, 1),
+        }
 
     out = {
         "metric": "Lightning Attention fwd+bwd tokens/s (7B-shaped layer: Bt=4, H=32, N=8192, D=128)"
@@ -434,6 +454,34 @@ def extended_report(ltn, synth, torch, dev, sections=""):
                                               for a_, b_ in zip(long_times, long_times[1:])}}),
               file=sys.stderr, flush=True)
 
+    def section_fp32():
+        # fp32 tensors (fp32 MFMA kernel): config 1's tiny shape and the 385M-shaped layer
+        for name, Bt, H, N, Dh, blk in (("cfg1_fp32_small", 1, 2, 256, 64, 64), ("cfg2_385m_shape_fp32", 8, 8, 2048, 128, 0)):
+            q, k, v = (torch.randn(Bt, H, N, Dh, device=dev).div_(Dh ** 0.5) for _ in range(3))
+            g = torch.randn(Bt, H, N, Dh, device=dev)
+            dd = synth.decay_bench_rule(H).to(dev)
+            o = torch.empty_like(q)
+            gr = tuple(torch.empty_like(q) for _ in range(3))
+            f, fmin = time_stats(lambda: ltn.ltn_attn_fwd(q, k, v, dd, block=blk, out=o))
+            b, bmin = time_stats(lambda: ltn.ltn_attn_bwd(q, k, v, g, dd, block=blk, out=gr))
+            th = Bt * H * N
+            B_ = blk or ltn.ltn_attn_pick_block(Dh, torch.float32)
+            pf = ltn.ltn_attn_query_plan(Bt, H, N, Dh, torch.float32, 0)
+            pb_ = ltn.ltn_attn_query_plan(Bt, H, N, Dh, torch.float32, 1)
+            # FLOPs the kernel issues per token-head and pass with 16-token strips: causal score tiles
+            # (B/16+1)/2 of B/16 per strip, recomputed per value-column slice; the same share of P C
+            def issued(passes, dv):
+                causal = (B_ / 16 + 1) / 2 * 16
+                return passes * (2 * causal * Dh * (Dh // dv) + 2 * causal * Dh + 4 * Dh * Dh)
+            print(json.dumps({"workload": name, "Bt": Bt, "H": H, "N": N, "D": Dh, "block": B_, "dv_fwd": pf[0], "dv_bwd": pb_[0],
+                              "fwd_ms": round(f, 4), "bwd_ms": round(b, 4), "fwd_min_ms": round(fmin, 4), "bwd_min_ms": round(bmin, 4),
+                              "fwd_GBs": round(4 * Dh * 4 * th / (f * 1e-3) / 1e9, 1),
+                              "bwd_GBs": round(7 * Dh * 4 * th / (b * 1e-3) / 1e9, 1),
+                              "fwd_issued_TFLOPs": round(issued(1, pf[0]) * th / (f * 1e-3) / 1e12, 1),
+                              "bwd_issued_TFLOPs": round(issued(3, pb_[0]) * th / (b * 1e-3) / 1e12, 1),
+                              "fp32_mfma_peak_TFLOPs": 157.3}), file=sys.stderr, flush=True)
+            del q, k, v, g, o, gr
+
     def section_gated():
         # token mixer epilogue (gated SimpleRMSNorm): fused into the forward vs. forward + gate kernel
         for name, Bt, H, N in (("cfg3_7b", 4, 32, 8192), ("256chains", 8, 32, 4096)):
@@ -577,7 +625,7 @@ def extended_report(ltn, synth, torch, dev, sections=""):
                               "state_GBs": round(2 * Bt * H * D * D * 4 / (t * 1e-3) / 1e9, 1),
                               "batch_tokens_per_s": round(Bt * S / (t * 1e-3), 1)}), file=sys.stderr, flush=True)
 
-    for name, fn in (("machine", section_machine), ("shapes", section_shapes), ("gated", section_gated),
+    for name, fn in (("machine", section_machine), ("shapes", section_shapes), ("fp32", section_fp32), ("gated", section_gated),
                      ("tiled", section_tiled), ("lrpe", section_lrpe), ("dims", section_dims),
                      ("decode", section_decode)):
         if want(name):

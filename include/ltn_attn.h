@@ -32,7 +32,8 @@
  *     before anything is launched.  Bt == 0 or H == 0 is a successful no-op; when
  *     Bt * H * N == 0 the token tensors are not touched and may be NULL.
  *   - Arithmetic: bf16 tensors use bf16 MFMA with fp32 accumulation and an fp32
- *     running state; fp32 tensors use fp32 arithmetic throughout.  Only
+ *     running state; fp32 tensors use fp32 arithmetic throughout (fp32 MFMA for plain
+ *     passes with D in {64, 128}, fp32 multiply-adds elsewhere).  Only
  *     non-negative powers of lambda are ever formed, so lambda = 0 and
  *     lambda = 1 are exact and strong decays cannot overflow (the failure mode
  *     Sec. 3.3 describes for the factorised form of Algorithm 1).
@@ -337,7 +338,7 @@ ltn_status ltn_attn_query_plan(int Bt, int H, long long N, int D, ltn_dtype dtyp
  * chain (0 = the library's choice, 1 = never cut).  It exists so that the parity tests can
  * reach every kernel variant at small sizes; it also changes what
  * ltn_attn_workspace_bytes returns.  Not thread-safe against concurrent calls into the
- * library.  LTN_ERR_SHAPE for values outside {0, 32, 64, 128, 256} / [0, 4096]. */
+ * library.  LTN_ERR_SHAPE for values outside {0, 16, 32, 64, 128, 256} / [0, 4096]. */
 ltn_status ltn_attn_set_debug_plan(int dv, int segs);
 
 /* Scratch bytes a call needs for these arguments: call = 0 for ltn_attn_fwd, 1 for

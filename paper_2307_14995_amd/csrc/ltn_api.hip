@@ -46,14 +46,18 @@ size_t esize_of(ltn_dtype dtype) { return dtype == LTN_BF16 ? 2 : 4; }
 // round of the 256 compute units; when even full-width slices need more than one round,
 // full width (fewest re-reads).  Measured on MI355X for 8..256 chains, forward and
 // backward.  ltn_attn_set_debug_plan (test only) overrides the choice.
-int pick_dv(long long chain_passes, int D, ltn_dtype dtype) {
+int pick_dv(long long chain_passes, int D, ltn_dtype dtype, int blk) {
     if (D == 96) return 32;                // three 32-column slices (the kernels exist for those only)
     // D = 256: the state copies of more than 64 columns do not fit the LDS
     const int hi = (D == 256) ? 64 : D;
-    const int lo = (dtype == LTN_BF16) ? 32 : (D == 256 ? 64 : D / 2);
+    int lo = (dtype == LTN_BF16) ? 32 : (D == 256 ? 64 : D / 2);
+    // fp32 on the matrix cores: a quarter of the columns too where its kernel has them
+    if (dtype == LTN_F32 && ((D == 128 && blk == 32) || (D == 64 && blk == 64))) lo = D / 4;
     if (const int v = g_debug_dv.load(std::memory_order_relaxed)) {
         if ((v == D || v == D / 2 || v == D / 4 || v == D / 8) && v >= lo && v <= hi) return v;
     }
+    // (fp32 matrix-core kernel: letting the split fill two rounds' worth of compute units, two
+    // workgroups to a unit, measured slower -- 385M shape backward 0.60 ms against 0.49 ms.)
     for (int dv = lo; dv <= hi; dv *= 2)
         if (chain_passes * (D / dv) <= 256) return dv;
     return hi;
@@ -124,7 +128,7 @@ ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void*
     const SegPlan plan = pick_segments(chain_passes, pb.N, D, dtype, full_width);
     pb.segs = 1;
     if (plan.segs == 1) {
-        const int dv = full_width ? D : pick_dv(chain_passes, D, dtype);
+        const int dv = full_width ? D : pick_dv(chain_passes, D, dtype, blk);
         const hipError_t e = (dtype == LTN_BF16) ? ltn::launch_pass_bf16(pb, D, dv, stream)
                                                  : ltn::launch_pass_f32(pb, D, dv, blk, stream);
         return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
@@ -158,7 +162,7 @@ ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void*
         main.p[i].state_in = states + i * per_pass;
         main.p[i].state_out = nullptr;
     }
-    const int dv = full_width ? D : pick_dv(chain_passes * plan.segs, D, dtype);
+    const int dv = full_width ? D : pick_dv(chain_passes * plan.segs, D, dtype, blk);
     return ltn::launch_pass_bf16(main, D, dv, stream) == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
 }
 
@@ -192,7 +196,7 @@ ltn_status scratch_on_current_device(void** out) {
 extern "C" {
 
 ltn_status ltn_attn_set_debug_plan(int dv, int segs) {
-    if (dv != 0 && dv != 32 && dv != 64 && dv != 128 && dv != 256) return LTN_ERR_SHAPE;
+    if (dv != 0 && dv != 16 && dv != 32 && dv != 64 && dv != 128 && dv != 256) return LTN_ERR_SHAPE;
     if (segs < 0 || segs > 4096) return LTN_ERR_SHAPE;
     g_debug_dv.store(dv, std::memory_order_relaxed);
     g_debug_segs.store(segs, std::memory_order_relaxed);
@@ -208,7 +212,7 @@ ltn_status ltn_attn_query_plan(int Bt, int H, long long N, int D, ltn_dtype dtyp
     const long long chain_passes = (long long)Bt * H * (call == 1 ? 3 : 1);
     const SegPlan plan = pick_segments(chain_passes, N, D, dtype, call == 2);
     *segs_out = plan.segs;
-    *dv_out = (call == 2) ? D : pick_dv(chain_passes * plan.segs, D, dtype);
+    *dv_out = (call == 2) ? D : pick_dv(chain_passes * plan.segs, D, dtype, ltn_attn_pick_block(D, dtype));
     return LTN_OK;
 }
 

@@ -70,6 +70,11 @@ hipError_t launch_tiled_bwd_bf16(const void* q, const void* k, const void* v, co
 // fp32 kernel.  D in {64,96,128,256}, block in {16,32,64}, D*block <= 4096 (D = 256: dv = 64;
 // D = 96: dv = 32, block 16 or 32).
 hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStream_t stream, int DC = 0);
+// fp32 MFMA kernel (v_mfma_f32_16x16x4_f32) for plain passes with D in {64,128}: the
+// (D, dv, block) combinations pass_f32_mfma_supports() accepts; launch_pass_f32 routes those
+// here and keeps its plain-FMA kernel for the rest (gated epilogue, unequal widths, 96, 256).
+bool pass_f32_mfma_supports(int D, int dv, int block);
+hipError_t launch_pass_f32_mfma(const PassBatch& pb, int D, int dv, int block, hipStream_t stream);
 // Turns the segment-local end states L[pass][chain][g] in `states` (as written by a
 // state_only launch) into the states at each segment's start, in place:
 //   S[0] = kv_in (pass 0 only) or 0,   S[g+1] = lambda^len(g) S[g] + L[g],

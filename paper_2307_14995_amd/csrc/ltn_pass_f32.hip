@@ -10,8 +10,9 @@
 // product is register-tiled (a thread owns a small rectangle of the result and walks the
 // contraction with 16-byte LDS reads), the state rectangle of a thread stays in its
 // registers for the whole sequence and is mirrored to LDS once per block for the
-// A_i S_i product.  This path exists for fp32 callers and the fp32 parity configuration;
-// the throughput path is the bf16 kernel.
+// A_i S_i product.  Plain passes with D in {64, 128} run on the matrix cores instead
+// (ltn_pass_f32_mfma.hip); this kernel serves what that one does not have: the gated
+// epilogue, unequal query/key and value widths, and heads of 96 and 256 features.
 #include "ltn_kernels.h"
 
 namespace ltn {
@@ -294,6 +295,8 @@ hipError_t launch_pass_f32(const PassBatch& pb, int D, int dv, int block, hipStr
 #undef LTN_F32_DC
         return hipErrorInvalidValue;
     }
+    if (!pb.p[0].gate && pb.segs == 1 && !pb.state_only && pass_f32_mfma_supports(D, dv, block))
+        return launch_pass_f32_mfma(pb, D, dv, block, stream);       // the matrix-core kernel
     if (D == 96) {                         // computed as 128 with zero tile columns, 32-column slices
         if (pb.p[0].gate || dv != 32) return hipErrorInvalidValue;
         if (block == 16) return launch_t<128, 32, 16, false, 96, 96>(pb, stream);

@@ -117,6 +117,7 @@ class Workload:
 CONFIGS = {
     "cfg1_fp32_small": Workload("cfg1_fp32_small", torch.float32, 1, 2, 256, 64, 64, False, BASE_SEED + 0),
     "cfg2_385m": Workload("cfg2_385m", torch.bfloat16, 8, 8, 2048, 128, 0, True, BASE_SEED + 1),
+    "cfg2_385m_fp32": Workload("cfg2_385m_fp32", torch.float32, 8, 8, 2048, 128, 0, True, BASE_SEED + 1),
     "cfg_1b": Workload("cfg_1b", torch.bfloat16, 8, 16, 2048, 128, 0, True, BASE_SEED + 5),
     "cfg3_7b": Workload("cfg3_7b", torch.bfloat16, 4, 32, 8192, 128, 0, True, BASE_SEED + 2),
 }
