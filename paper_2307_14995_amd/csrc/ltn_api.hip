@@ -103,12 +103,12 @@ constexpr long long kMinSegsFullWidth = 4;   // measured: 2 segments lose to one
 SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtype, bool full_width = false) {
     SegPlan plan = {1, 0};
     if (dtype != LTN_BF16 || chain_passes <= 0 || N <= 64) return plan;
-    if (D == 96) return plan;              // no state-only sweep for this width
-    // D = 256: every (chain, segment) still needs four 64-column workgroups
-    long long want = 256 / (D == 256 ? 4 * chain_passes : chain_passes);
+    // D = 256: every (chain, segment) still needs four 64-column workgroups; D = 96: three of 32
+    const long long per_seg = (D == 256) ? 4 : (D == 96 ? 3 : 1);
+    long long want = 256 / (per_seg * chain_passes);
     if (want > N / 1024) want = N / 1024;
     // a pass that must keep full-width slices has no column split to fall back on
-    if (want < ((full_width || D == 256) ? kMinSegsFullWidth : 8)) want = 1;
+    if (want < ((full_width || per_seg > 1) ? kMinSegsFullWidth : 8)) want = 1;
     if (const int v = g_debug_segs.load(std::memory_order_relaxed)) want = v;
     if (want <= 1) return plan;
     long long len = (N + want - 1) / want;
@@ -151,7 +151,7 @@ ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void*
         sweep.p[i].state_in = nullptr;
         sweep.p[i].state_out = states + i * per_pass;
     }
-    if (ltn::launch_pass_bf16(sweep, D, D == 256 ? 64 : D, stream) != hipSuccess) return LTN_ERR_LAUNCH;
+    if (ltn::launch_pass_bf16(sweep, D, D == 256 ? 64 : (D == 96 ? 32 : D), stream) != hipSuccess) return LTN_ERR_LAUNCH;
     if (ltn::launch_segment_scan(states, kv_in, kv_out, pb.decay, pb.count, pb.chains, pb.H, plan.segs,
                                  plan.seg_len, pb.N, D, stream) != hipSuccess)
         return LTN_ERR_LAUNCH;

@@ -709,11 +709,11 @@ void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
 template <int D, int DV, int MODE = kPlain, int DC = D, int DR = D>
 hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
     static_assert(DV <= DC && DC % DV == 0, "value-column slices tile the C operand");
-    static_assert(DC == D || MODE == kPlain, "unequal widths: plain pass only");
+    static_assert(DC == D || MODE == kPlain || (MODE == kStateOnly && DR == DC), "unequal widths: plain pass only");
     const int nsplit = DC / DV;
     const long long wgs = (long long)pb.chains * pb.segs * pb.count * nsplit;
     if (wgs <= 0 || wgs > 0x7fffffffLL || pb.segs < 1) return hipErrorInvalidValue;
-    if (DC != D && pb.segs != 1) return hipErrorInvalidValue;
+    if (DC != D && DR != DC && pb.segs != 1) return hipErrorInvalidValue;    // segments: equal widths (96 as 128 included)
     hipLaunchKernelGGL((pass_bf16_kernel<D, DV, MODE, DC, DR>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
     return hipGetLastError();
 }
@@ -732,7 +732,8 @@ hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stre
         return hipErrorInvalidValue;
     }
     if (D == 96) {                         // computed as 128 with zero-filled tile columns, 32-column slices
-        if (pb.p[0].gate || pb.state_only || dv != 32) return hipErrorInvalidValue;
+        if (pb.p[0].gate || dv != 32) return hipErrorInvalidValue;
+        if (pb.state_only) return launch_t<128, 32, kStateOnly, 96, 96>(pb, stream);
         return launch_t<128, 32, kPlain, 96, 96>(pb, stream);
     }
     if (pb.p[0].gate) {                    // gated epilogue: one pass, complete output rows

@@ -57,7 +57,7 @@ def test_pick_block_and_workspace(lib):
     assert ltn.ltn_attn_pick_block(256, torch.float32) == 16
     assert ltn.ltn_attn_workspace_bytes(1, 32, 65536, 256, 0, torch.bfloat16, 0) == 0   # 256-wide heads: 4 workgroups per chain already
     assert ltn.ltn_attn_workspace_bytes(1, 8, 65536, 256, 0, torch.bfloat16, 0) == 8 * 8 * 256 * 256 * 4
-    assert ltn.ltn_attn_workspace_bytes(1, 8, 65536, 96, 0, torch.bfloat16, 0) == 0
+    assert ltn.ltn_attn_workspace_bytes(1, 8, 65536, 96, 0, torch.bfloat16, 0) == 8 * 10 * 96 * 96 * 4   # three 32-column workgroups per segment
     assert ltn.ltn_attn_workspace_bytes(4, 32, 8192, 128, 0, torch.bfloat16, 1) == 0
 
 

@@ -362,9 +362,11 @@ def test_long_context_linear_time_and_parity():
                 check(n, x, r, 1e-2)
                 check_rows(n + " rows", x, r, TOL_ROW[torch.bfloat16])
             del refs
+    # Doubling ratios from 16384 on (measured 1.92 .. 1.98; the two fixed launches of the sequence-parallel
+    # forward weigh less as N grows, hence slightly under 2; boxes of the pool differ by about 3 % run to run)
     for N in (32768, 65536):
         ratio = times[N] / times[N // 2]
-        assert 1.7 < ratio < 2.3, (times, ratio)
+        assert 1.85 < ratio < 2.15, (times, ratio)
 
 
 def test_decode_config5_all_steps_all_chains():
@@ -408,7 +410,7 @@ def test_decode_config5_all_steps_all_chains():
 # --------------------------------------------------------------------------- sequence-parallel form
 
 
-@pytest.mark.parametrize("D", [64, 128, 256])
+@pytest.mark.parametrize("D", [64, 96, 128, 256])
 @pytest.mark.parametrize("N,segs", [(130, 2), (517, 3), (1000, 5), (640, 10)])
 def test_bf16_segmented_forward_backward(D, N, segs):
     """Chains cut into segments (end states from zero, scan, per-segment pass) give the same
@@ -588,8 +590,8 @@ def test_time_is_linear_in_sequence_length():
         ev[20].record()
         torch.cuda.synchronize()
         times[N] = statistics.median(ev[i].elapsed_time(ev[i + 1]) for i in range(20))
-    assert 1.8 < times[32768] / times[16384] < 2.2, times
-    assert 1.8 < times[65536] / times[32768] < 2.2, times
+    assert 1.85 < times[32768] / times[16384] < 2.15, times
+    assert 1.85 < times[65536] / times[32768] < 2.15, times
 
 
 def test_work_goes_to_the_callers_stream():
