@@ -397,6 +397,18 @@ def extended_report(ltn, synth, torch, dev, sections=""):
         print(json.dumps({"workload": "machine", "copy_1GiB_GBs": round(2 * (1 << 30) / (t_copy * 1e-3) / 1e9, 1),
                           "bf16_gemm_8192_TFLOPs": round(2 * 8192 ** 3 / (t_gemm * 1e-3) / 1e12, 1)}),
               file=sys.stderr, flush=True)
+        # the library's own streaming-read probe: the tile pipeline's load pattern with nothing behind it
+        # (64 KB in flight per compute unit), out of L2 / the memory-side cache / HBM
+        buf = torch.ones(256 * (16 << 20), dtype=torch.uint8, device=dev)
+        for wgs in (256, 128):
+            line = {"workload": "stream_read_probe", "workgroups": wgs}
+            for label, per_wg in (("L2_64KB", 64 << 10), ("cache_512KB", 512 << 10), ("HBM_16MB", 16 << 20)):
+                iters = (64 << 20) // per_wg
+                for regs in (0, 1):
+                    t = time_call(lambda: ltn.ltn_probe_stream_read(buf, per_wg, wgs, iters, regs), n=3, warm=1)
+                    line[f"{label}_{'regs' if regs else 'lds'}_TBs"] = round(wgs * per_wg * iters / (t * 1e-3) / 1e12, 2)
+            print(json.dumps(line), file=sys.stderr, flush=True)
+        del buf
 
 
     def section_shapes():

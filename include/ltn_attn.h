@@ -352,6 +352,17 @@ ltn_status ltn_attn_set_debug_plan(int dv, int segs);
 size_t ltn_attn_workspace_bytes(int Bt, int H, long long N, int D, int block,
                                 ltn_dtype dtype, int call);
 
+/* Measurement aid (no attention arithmetic): `workgroups` workgroups of 512 threads each read
+ * their own contiguous bytes_per_workgroup bytes (a multiple of 64 KB) of `buf` `iters`
+ * times, eight 1 KB loads in flight per wave, straight into LDS (to_registers = 0, the way the
+ * attention kernels fetch their tiles) or into registers (1).  The benchmark's report times
+ * it to state what rate this machine gives such a pipeline out of L2, the memory-side cache
+ * and HBM, next to the published 8 TB/s.  buf: device, buf_bytes >= workgroups *
+ * bytes_per_workgroup, read only; sink: device, one word, written only if the data matches a
+ * magic pattern (it keeps the loads alive). */
+ltn_status ltn_probe_stream_read(const void* buf, size_t buf_bytes, size_t bytes_per_workgroup, int workgroups,
+                                 int iters, int to_registers, unsigned* sink, void* stream);
+
 /* Host-side validation of a HOST copy of the decay array: LTN_OK if every value
  * is in [0, 1], LTN_ERR_DECAY otherwise (Eq. 2 gives values in (0, 1]; the last
  * layer uses exactly 1). */

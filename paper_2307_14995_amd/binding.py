@@ -22,7 +22,7 @@ SYMBOLS = (
     "ltn_attn_workspace_bytes", "ltn_attn_check_decay", "ltn_status_str",
     "ltn_prologue_fwd", "ltn_prologue_bwd", "ltn_prologue_workspace_bytes",
     "ltn_attn_fwd_dkdv", "ltn_attn_bwd_dkdv", "ltn_attn_decode_steps_dkdv",
-    "ltn_attn_query_plan", "ltn_attn_set_debug_plan", "ltn_attn_fwd_static", "ltn_attn_bwd_tiled",
+    "ltn_attn_query_plan", "ltn_attn_set_debug_plan", "ltn_attn_fwd_static", "ltn_attn_bwd_tiled", "ltn_probe_stream_read",
 )
 
 
@@ -89,6 +89,8 @@ def load_library():
     lib.ltn_attn_decode_steps_dkdv.restype = ci
     lib.ltn_attn_fwd_static.argtypes = [vp, vp, vp, vp, fp, fp, fp, ci, ci, cl, ci, ci, ci, vp]
     lib.ltn_attn_fwd_static.restype = ci
+    lib.ltn_probe_stream_read.argtypes = [vp, sz, sz, ci, ci, ci, vp, vp]
+    lib.ltn_probe_stream_read.restype = ci
     lib.ltn_attn_query_plan.argtypes = [ci, ci, cl, ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
     lib.ltn_attn_query_plan.restype = ci
     lib.ltn_attn_set_debug_plan.argtypes = [ci, ci]
@@ -401,6 +403,20 @@ def ltn_attn_bwd_tiled(q, k, v, d_o, decay, out=None):
     if rc != 0:
         raise LtnError(rc, "ltn_attn_bwd_tiled")
     return dq, dk, dv
+
+
+def ltn_probe_stream_read(buf, bytes_per_workgroup, workgroups, iters, to_registers=False, sink=None):
+    """Measurement aid: enqueue the streaming-read probe on `buf` (a uint8 CUDA tensor)."""
+    lib = load_library()
+    _dev(buf, "buf")
+    if sink is None:
+        sink = torch.zeros(1, dtype=torch.int32, device=buf.device)
+    with torch.cuda.device(buf.device):
+        rc = lib.ltn_probe_stream_read(_ptr(buf), buf.numel() * buf.element_size(), int(bytes_per_workgroup), int(workgroups),
+                                       int(iters), int(bool(to_registers)), _ptr(sink), _stream(buf.device))
+    if rc != 0:
+        raise LtnError(rc, "ltn_probe_stream_read")
+    return sink
 
 
 def ltn_prologue_workspace_bytes(Bt, H, N, D) -> int:

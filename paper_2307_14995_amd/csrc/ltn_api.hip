@@ -631,6 +631,16 @@ ltn_status ltn_attn_decode_steps_dkdv(const void* q, const void* k, const void* 
     return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
 }
 
+ltn_status ltn_probe_stream_read(const void* buf, size_t buf_bytes, size_t bytes_per_workgroup, int workgroups,
+                                 int iters, int to_registers, unsigned* sink, void* stream) {
+    if (!buf || !sink) return LTN_ERR_NULL;
+    if (workgroups <= 0 || iters <= 0 || bytes_per_workgroup == 0 || bytes_per_workgroup % 65536 != 0) return LTN_ERR_SHAPE;
+    if (bytes_per_workgroup > buf_bytes / (size_t)workgroups) return LTN_ERR_SHAPE;      // every region inside the buffer
+    if (!aligned16(buf) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return LTN_ERR_ALIGN;
+    return ltn::launch_probe_stream(buf, bytes_per_workgroup, workgroups, iters, to_registers, sink,
+                                    static_cast<hipStream_t>(stream)) == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+}
+
 size_t ltn_prologue_workspace_bytes(int Bt, int H, long long N, int D) {
     if (Bt <= 0 || H <= 0 || N <= 0 || D <= 0) return 0;
     return (size_t)ltn::prologue_partial_count(N) * (size_t)H * (size_t)D * sizeof(double);

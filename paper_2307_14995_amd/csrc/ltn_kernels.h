@@ -105,6 +105,11 @@ hipError_t launch_prologue(const void* x, const float* theta, const void* dy, vo
 hipError_t launch_gate(const void* x, const void* u, const void* dy, void* o0, void* o1, float eps,
                        long long rows, int D, int is_bf16, int is_bwd, hipStream_t stream);
 
+// Streaming-read probe (see ltn_probe.hip): wgs workgroups each read their own per_wg bytes
+// (a multiple of 64 KB) of `buf` `iters` times, to LDS directly or to registers.
+hipError_t launch_probe_stream(const void* buf, size_t per_wg, int wgs, int iters, int to_registers, unsigned* sink,
+                               hipStream_t stream);
+
 // lambda^n, n >= 0, by binary powering in fp64 (only multiplications: exact up to
 // rounding, lambda = 0 gives 0^0 = 1, no transcendental).  Never called with n < 0.
 __device__ __forceinline__ float decay_pow(float lam, int n) {

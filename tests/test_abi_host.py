@@ -322,6 +322,17 @@ def test_environment_does_not_change_the_plan(lib, monkeypatch):
     assert ltn.ltn_attn_workspace_bytes(4, 32, 8192, 128, 0, torch.bfloat16, 0) == 0
 
 
+def test_probe_argument_errors(lib):
+    f = lib.ltn_probe_stream_read
+    big = 256 * (16 << 20)
+    assert f(None, big, 65536, 4, 1, 0, P + 64, None) == E_NULL
+    assert f(P, big, 65536, 4, 1, 0, None, None) == E_NULL
+    assert f(P, big, 1000, 4, 1, 0, P + (1 << 36), None) == E_SHAPE           # not a multiple of 64 KB
+    assert f(P, 65536 * 4 - 1, 65536, 4, 1, 0, P + (1 << 36), None) == E_SHAPE  # regions would leave the buffer
+    assert f(P, big, 65536, 0, 1, 0, P + (1 << 36), None) == E_SHAPE
+    assert f(P + 4, big, 65536, 4, 1, 0, P + (1 << 36), None) == E_ALIGN
+
+
 def test_workspace_query(lib):
     import torch
     D = 128
