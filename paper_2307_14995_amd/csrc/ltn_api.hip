@@ -56,10 +56,13 @@ int pick_dv(long long chain_passes, int D, ltn_dtype dtype, int blk) {
     if (const int v = g_debug_dv.load(std::memory_order_relaxed)) {
         if ((v == D || v == D / 2 || v == D / 4 || v == D / 8) && v >= lo && v <= hi) return v;
     }
-    // (fp32 matrix-core kernel: letting the split fill two rounds' worth of compute units, two
-    // workgroups to a unit, measured slower -- 385M shape backward 0.60 ms against 0.49 ms.)
     for (int dv = lo; dv <= hi; dv *= 2)
         if (chain_passes * (D / dv) <= 256) return dv;
+    // More than one round even at full width.  The fp32 matrix-core kernel is bound by its MFMA
+    // and LDS latencies, and two of its half-width workgroups fit one compute unit (76 KB of LDS
+    // each), so half width runs 5-7 % faster there (measured: 1B and 7B shapes, backward); the
+    // memory-bound bf16 kernel keeps full width (fewest re-reads).
+    if (dtype == LTN_F32 && D == 128 && blk == 32) return D / 2;
     return hi;
 }
 

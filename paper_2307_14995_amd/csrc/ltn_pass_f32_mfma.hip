@@ -7,9 +7,9 @@
 //   O_i  = P C_i + diag(lambda^(r+1)) A_i S_i
 //   S_i+1 = lambda^len S_i + sum_c lambda^(len-1-c) b_c^T c_c
 //
-// One 256-thread workgroup (4 waves, one per SIMD) per (chain, pass, slice of DV value
-// columns), blocks of B tokens.
-//   * Output part: wave w owns the token strip (w mod B/16) and a group of value-column tiles.
+// One 512-thread workgroup (8 waves, two per SIMD, in two roles so that one role's LDS waits
+// hide under the other's MFMAs) per (chain, pass, slice of DV value columns), blocks of B tokens.
+//   * Output waves 0..3: wave w owns the token strip (w mod B/16) and a group of value-column tiles.
 //     It forms the transposed scores P^T[keys][its 16 tokens]; their accumulator layout (lane
 //     holds keys 4g..4g+3 of a token) is the B operand of the next product with the
 //     contraction index permuted (k-slot g of step j <-> key 4g + j), so the masked scores stay
@@ -20,11 +20,12 @@
 //     read feeding four MFMAs; operands contracted over the token index (C in P C, B and C in
 //     the state update) are read 4 bytes per lane.  Row pitches are 4 floats more than a
 //     multiple of 64, which makes both kinds of read conflict-free.
-//   * State part: wave u owns state rows [u D/4, (u+1) D/4) x DV in accumulators for the whole
-//     sequence; once per block the new state goes to LDS transposed ([dv][dk], 16-byte writes)
-//     for the next block's A_i S_i.
-//   * The next block's tiles are fetched into registers while the current block is computed
-//     and written to LDS between two barriers at the end of the block.
+//   * State waves 4..7: wave 4 + u owns state rows [u D/4, (u+1) D/4) x DV in accumulators for
+//     the whole sequence; once per block the new state goes to LDS transposed ([dv][dk], 16-byte
+//     writes) for the next block's A_i S_i.
+//   * The next block's tiles are fetched into registers (all eight waves share the loads) while
+//     the current block is computed and written to LDS between two barriers at the end of the
+//     block.
 // Only non-negative powers of lambda are formed.
 #include "ltn_kernels.h"
 
@@ -33,7 +34,7 @@ namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-constexpr int kMThreads = 256;
+constexpr int kMThreads = 512;
 
 __device__ __forceinline__ v4f mfma4(float a, float b, v4f c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
@@ -55,15 +56,15 @@ struct FCfg {
     static_assert(D == 64 || D == 128, "head dims of this kernel");
     static_assert(NT % VG == 0 && NTW >= 1, "every wave needs a value-column tile");
     static_assert(FLOATS * 4 <= 163840, "LDS per workgroup");
-    // prefetch registers: 16-byte pieces per thread and tile
-    static constexpr int LA = B * (D / 4) / kMThreads, LC = B * (DV / 4) / kMThreads;
-    static_assert(LA >= 1 && LC >= 1 && B * (D / 4) % kMThreads == 0 && B * (DV / 4) % kMThreads == 0, "whole loads per thread");
+    // prefetch registers: 16-byte pieces per thread and tile (the last round of a tile may be partial)
+    static constexpr int EA = B * (D / 4), EC = B * (DV / 4);
+    static constexpr int LA = (EA + kMThreads - 1) / kMThreads, LC = (EC + kMThreads - 1) / kMThreads;
 };
 
 // The whole pass as one wave runs it; STRIP (the wave's token strip in the output part) is a
 // compile-time constant, so causal tile skipping and the choice of decay constants cost no
 // branches or indexed register reads inside a block.
-template <int D, int DV, int B, int STRIP>
+template <int D, int DV, int B, int STRIP, bool STATE>
 __device__ __forceinline__ void pass_f32_mfma_wave(const PassBatch& pb, const int nsplit, float* smem, const int wave) {
     using C = FCfg<D, DV, B>;
     constexpr int TS = C::TS, NT = C::NT, NTW = C::NTW, MT = C::MT, KC = C::KC, PA = C::PA, PC = C::PC;
@@ -95,28 +96,32 @@ __device__ __forceinline__ void pass_f32_mfma_wave(const PassBatch& pb, const in
 
     for (int n = tid; n <= B; n += kMThreads) pw[n] = decay_pow(lam, n);
 
-    // output part: strip and value-column tiles of this wave
+    // output waves: value-column tiles of this wave (its strip is STRIP)
     const int vg = wave / TS;
     const int nt0 = vg * NTW;
-    // state part: rows dkb .. dkb + D/4 of the state
-    const int dkb = wave * (D / 4);
+    // state waves: rows dkb .. dkb + D/4 of the state
+    const int dkb = (wave & 3) * (D / 4);
 
     // running state, fp32 accumulators: S[dkb + 16mt + 4g + j][16nt + i16]
-    v4f st[MT][NT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                st[mt][nt][j] = sin_p ? sin_p[(size_t)(dkb + 16 * mt + 4 * g + j) * D + 16 * nt + i16] : 0.0f;
-
-    auto publish_state = [&]() {
+    v4f st[STATE ? MT : 1][STATE ? NT : 1];
+    if constexpr (STATE) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                *(v4f*)&St[(16 * nt + i16) * PA + dkb + 16 * mt + 4 * g] = st[mt][nt];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    st[mt][nt][j] = sin_p ? sin_p[(size_t)(dkb + 16 * mt + 4 * g + j) * D + 16 * nt + i16] : 0.0f;
+    }
+
+    auto publish_state = [&]() {
+        if constexpr (STATE) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    *(v4f*)&St[(16 * nt + i16) * PA + dkb + 16 * mt + 4 * g] = st[mt][nt];
+        }
     };
 
     // tile prefetch through registers
@@ -126,7 +131,7 @@ __device__ __forceinline__ void pass_f32_mfma_wave(const PassBatch& pb, const in
 #pragma unroll
         for (int i = 0; i < C::LA; ++i) {
             const int e = tid + i * kMThreads, r = e / (D / 4), c4 = e % (D / 4);
-            const bool ok = r < left;
+            const bool ok = e < C::EA && r < left;
             const size_t gr = (size_t)(rev ? (N - 1 - (t0 + r)) : (t0 + r));
             ra[i] = ok ? *(const v4f*)(Ap + gr * D + 4 * c4) : v4f{0.f, 0.f, 0.f, 0.f};
             rb[i] = ok ? *(const v4f*)(Bp + gr * D + 4 * c4) : v4f{0.f, 0.f, 0.f, 0.f};
@@ -134,7 +139,7 @@ __device__ __forceinline__ void pass_f32_mfma_wave(const PassBatch& pb, const in
 #pragma unroll
         for (int i = 0; i < C::LC; ++i) {
             const int e = tid + i * kMThreads, r = e / (DV / 4), c4 = e % (DV / 4);
-            const bool ok = r < left;
+            const bool ok = e < C::EC && r < left;
             const size_t gr = (size_t)(rev ? (N - 1 - (t0 + r)) : (t0 + r));
             rc[i] = ok ? *(const v4f*)(Cp + gr * D + 4 * c4) : v4f{0.f, 0.f, 0.f, 0.f};
         }
@@ -143,13 +148,15 @@ __device__ __forceinline__ void pass_f32_mfma_wave(const PassBatch& pb, const in
 #pragma unroll
         for (int i = 0; i < C::LA; ++i) {
             const int e = tid + i * kMThreads, r = e / (D / 4), c4 = e % (D / 4);
-            *(v4f*)&As[r * PA + 4 * c4] = ra[i];
-            *(v4f*)&Bs[r * PA + 4 * c4] = rb[i];
+            if (e < C::EA) {
+                *(v4f*)&As[r * PA + 4 * c4] = ra[i];
+                *(v4f*)&Bs[r * PA + 4 * c4] = rb[i];
+            }
         }
 #pragma unroll
         for (int i = 0; i < C::LC; ++i) {
             const int e = tid + i * kMThreads, r = e / (DV / 4), c4 = e % (DV / 4);
-            *(v4f*)&Cs[r * PC + 4 * c4] = rc[i];
+            if (e < C::EC) *(v4f*)&Cs[r * PC + 4 * c4] = rc[i];
         }
     };
 
@@ -174,8 +181,8 @@ __device__ __forceinline__ void pass_f32_mfma_wave(const PassBatch& pb, const in
         const bool more = t0 + B < N;
         if (more) fetch(t0 + B);
 
-        // ------------------------------------------------ output part
-        {
+        // ------------------------------------------------ output waves
+        if constexpr (!STATE) {
             v4f af[KC];
 #pragma unroll
             for (int c = 0; c < KC; ++c) af[c] = *(const v4f*)&As[(16 * strip + i16) * PA + 16 * c + 4 * g];
@@ -233,8 +240,8 @@ __device__ __forceinline__ void pass_f32_mfma_wave(const PassBatch& pb, const in
             }
         }
 
-        // ------------------------------------------------ state part
-        if (more || sout_p) {
+        // ------------------------------------------------ state waves
+        if constexpr (STATE) if (more || sout_p) {
             const float lam_len = pw[len];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
@@ -268,7 +275,7 @@ __device__ __forceinline__ void pass_f32_mfma_wave(const PassBatch& pb, const in
         }
     }
 
-    if (sout_p) {
+    if constexpr (STATE) if (sout_p) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -285,18 +292,22 @@ void pass_f32_mfma_kernel(const PassBatch pb, const int nsplit) {
     using C = FCfg<D, DV, B>;
     __shared__ __attribute__((aligned(16))) float smem[C::FLOATS];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the dispatch is a uniform branch
+    if (wave >= 4) {
+        pass_f32_mfma_wave<D, DV, B, 0, true>(pb, nsplit, smem, wave);
+        return;
+    }
     const int strip = wave % C::TS;
     if constexpr (C::TS == 1) {
-        pass_f32_mfma_wave<D, DV, B, 0>(pb, nsplit, smem, wave);
+        pass_f32_mfma_wave<D, DV, B, 0, false>(pb, nsplit, smem, wave);
     } else if constexpr (C::TS == 2) {
-        if (strip == 0) pass_f32_mfma_wave<D, DV, B, 0>(pb, nsplit, smem, wave);
-        else pass_f32_mfma_wave<D, DV, B, 1>(pb, nsplit, smem, wave);
+        if (strip == 0) pass_f32_mfma_wave<D, DV, B, 0, false>(pb, nsplit, smem, wave);
+        else pass_f32_mfma_wave<D, DV, B, 1, false>(pb, nsplit, smem, wave);
     } else {
         switch (strip) {
-            case 0: pass_f32_mfma_wave<D, DV, B, 0>(pb, nsplit, smem, wave); break;
-            case 1: pass_f32_mfma_wave<D, DV, B, 1>(pb, nsplit, smem, wave); break;
-            case 2: pass_f32_mfma_wave<D, DV, B, 2>(pb, nsplit, smem, wave); break;
-            default: pass_f32_mfma_wave<D, DV, B, 3>(pb, nsplit, smem, wave); break;
+            case 0: pass_f32_mfma_wave<D, DV, B, 0, false>(pb, nsplit, smem, wave); break;
+            case 1: pass_f32_mfma_wave<D, DV, B, 1, false>(pb, nsplit, smem, wave); break;
+            case 2: pass_f32_mfma_wave<D, DV, B, 2, false>(pb, nsplit, smem, wave); break;
+            default: pass_f32_mfma_wave<D, DV, B, 3, false>(pb, nsplit, smem, wave); break;
         }
     }
 }
