@@ -37,9 +37,10 @@
  *     non-negative powers of lambda are ever formed, so lambda = 0 and
  *     lambda = 1 are exact and strong decays cannot overflow (the failure mode
  *     Sec. 3.3 describes for the factorised form of Algorithm 1).
- *   - Supported shapes: D in {64, 96, 128, 256} for ltn_attn_fwd, ltn_attn_bwd and the
- *     decode steps (D in {64, 128} for the gated forward, the gate kernels and the
- *     tiled comparison kernel); N >= 0 arbitrary (a short last block
+ *   - Supported shapes: D in {64, 96, 128, 256} for ltn_attn_fwd, ltn_attn_bwd, the decode
+ *     steps, the gate kernels and the gated forward (which for 96 and 256 features needs
+ *     its `o` argument); D in {64, 128} for the tiled comparison kernels; N >= 0
+ *     arbitrary (a short last block
  *     is handled on chip; the paper's listings assume block | N).
  *     `block` is the intra-block tile length: 0 lets the library choose
  *     (ltn_attn_pick_block); bf16 supports 64; fp32 supports 16, 32 and 64
@@ -137,7 +138,9 @@ ltn_status ltn_attn_fwd_static(const void* q, const void* k, const void* v, void
  *   y     out: device, [Bt,H,N,D] dtype
  * (With few chains and `o` requested, the library may instead run the plain forward and
  * apply the epilogue to the stored o in a second kernel; y then derives from o rounded
- * to `dtype`, so the two forms of the call agree to rounding, not bit for bit.)
+ * to `dtype`, so the two forms of the call agree to rounding, not bit for bit.  For D = 96
+ * and D = 256 that is the only form: a complete output row of these widths does not fit
+ * one workgroup's on-chip state, so `o` must be given -- LTN_ERR_UNSUPPORTED otherwise.)
  *   eps   >= 0, added to the mean square under the root (0 is the printed formula:
  *         an all-zero output row then yields NaN, as the formula does)
  * Other arguments, layout and errors as for ltn_attn_fwd.
@@ -156,7 +159,7 @@ ltn_status ltn_attn_fwd_gated(const void* q, const void* k, const void* v, const
  *
  *   x, u, d_y in : device, [rows, D] dtype (for attention tensors rows = Bt*H*N)
  *   y, d_x, d_u out: device, [rows, D] dtype; must not alias an input or each other
- *   D in {64, 128}; fp32 arithmetic inside for either dtype.
+ *   D in {64, 96, 128, 256}; fp32 arithmetic inside for either dtype.
  */
 ltn_status ltn_gate_fwd(const void* x, const void* u, void* y, float eps,
                         long long rows, int D, ltn_dtype dtype, void* stream);

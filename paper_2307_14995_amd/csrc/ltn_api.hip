@@ -270,7 +270,11 @@ static ltn_status fwd_common(const void* q, const void* k, const void* v, const 
     const ltn_status cs = check_common(Bt, H, N, D, block, dtype, &blk);
     if (cs != LTN_OK) return cs;
     if (gated && !(eps >= 0.0f)) return LTN_ERR_SHAPE;
-    if (gated && (D == 256 || D == 96)) return LTN_ERR_UNSUPPORTED;   // no kernel with complete output rows of these widths
+    // 96 and 256 features: no kernel holds a complete output row of these widths in one workgroup,
+    // so the epilogue is applied to the stored attention output by the gate kernel; a caller
+    // that does not want o stored has no fused form to fall back on
+    const bool unfused_only = gated && (D == 256 || D == 96);
+    if (unfused_only && !o && !empty) return LTN_ERR_UNSUPPORTED;
     const size_t need_ws = ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, gated ? 2 : 0);
     if (workspace_bytes < need_ws) return LTN_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(u) || !aligned16(y) ||
@@ -304,6 +308,14 @@ static ltn_status fwd_common(const void* q, const void* k, const void* v, const 
     pb.N = N;
     pb.p[0] = ltn::PassArgs{q, k, v, o, kv_in, kv_out, 0, gated ? u : nullptr, gated ? y : nullptr, eps};
     if (!gated) return run_passes(pb, D, blk, dtype, workspace, st);
+    if (unfused_only) {
+        pb.p[0].gate = nullptr;
+        pb.p[0].gated_out = nullptr;
+        const ltn_status s1 = run_passes(pb, D, blk, dtype, workspace, st);
+        if (s1 != LTN_OK) return s1;
+        return ltn::launch_gate(o, u, nullptr, y, nullptr, eps, chains * N, D, dtype == LTN_BF16, 0, st) == hipSuccess
+                   ? LTN_OK : LTN_ERR_LAUNCH;
+    }
     // The fused epilogue needs complete output rows in one workgroup, i.e. full-width slices
     // (one workgroup per chain, or per chain segment).  With few chains that can leave
     // compute units idle; when the caller wants the attention output stored anyway
@@ -396,7 +408,7 @@ static ltn_status gate_common(const void* x, const void* u, const void* d_y, voi
                               long long rows, int D, ltn_dtype dtype, void* stream, bool bwd) {
     if (rows < 0 || D <= 0) return LTN_ERR_SHAPE;
     if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
-    if (D != 64 && D != 128) return LTN_ERR_UNSUPPORTED;
+    if (D != 64 && D != 96 && D != 128 && D != 256) return LTN_ERR_UNSUPPORTED;
     if (!(eps >= 0.0f)) return LTN_ERR_SHAPE;
     if (rows == 0) return LTN_OK;
     if (!x || !u || !o0 || (bwd && (!d_y || !o1))) return LTN_ERR_NULL;

@@ -7,7 +7,8 @@
 // forward (the gated epilogue of the pass kernels); these stand-alone kernels serve the
 // backward (which needs the stored attention output x) and callers that hold x already.
 // Streaming kernels, HBM-bound: every lane owns 16 bytes of one row, a row's lanes are
-// neighbours in one wave and reduce with cross-lane shuffles; fp32 arithmetic.
+// neighbours in one wave and reduce with cross-lane shuffles (rows of 96 features take 16 or 32
+// lanes of which 12 or 24 hold data); fp32 arithmetic.
 #include "ltn_kernels.h"
 
 namespace ltn {
@@ -61,19 +62,25 @@ __global__ __launch_bounds__(kThreads)
 void gate_kernel(const char* __restrict__ x, const char* __restrict__ u, const char* __restrict__ dy,
                  char* __restrict__ o0, char* __restrict__ o1, float eps, long long rows) {
     using V = Vec<BF16>;
-    constexpr int LPR = D / V::N;                 // lanes per row
+    constexpr int ACT = D / V::N;                 // lanes that hold a piece of the row
+    constexpr int LPR = ACT <= 8 ? 8 : (ACT <= 16 ? 16 : (ACT <= 32 ? 32 : 64));   // lanes given to a row (96 features: 12 of 16, 24 of 32)
     constexpr int RPW = kThreads / LPR;           // rows per workgroup step
-    static_assert(LPR == 8 || LPR == 16 || LPR == 32, "a row's lanes sit in one wave");
+    static_assert(D % V::N == 0 && ACT <= 64, "a row's lanes sit in one wave");
     const int sub = threadIdx.x % LPR;
+    const bool live = sub < ACT;                  // idle lanes of a row contribute zeros and store nothing
     long long r = (long long)blockIdx.x * RPW + threadIdx.x / LPR;
     const long long stride = (long long)gridDim.x * RPW;
     // every lane of a wave runs the same number of steps (the shuffles need all of a
     // row's lanes); rows past the end are skipped as whole rows
     for (; r < rows; r += stride) {
-        const size_t off = ((size_t)r * LPR + sub) * 16;
+        const size_t off = ((size_t)r * ACT + (live ? sub : 0)) * 16;
         V xv, uv;
         xv.load(x + off);
         uv.load(u + off);
+        if (!live) {
+#pragma unroll
+            for (int i = 0; i < V::N; ++i) xv.v[i] = 0.f;
+        }
         float ss = 0.f;
 #pragma unroll
         for (int i = 0; i < V::N; ++i) ss = fmaf(xv.v[i], xv.v[i], ss);
@@ -83,7 +90,7 @@ void gate_kernel(const char* __restrict__ x, const char* __restrict__ u, const c
             V yv;
 #pragma unroll
             for (int i = 0; i < V::N; ++i) yv.v[i] = xv.v[i] * rstd * uv.v[i];
-            yv.store(o0 + off);
+            if (live) yv.store(o0 + off);
         } else {
             V gv;
             gv.load(dy + off);
@@ -101,8 +108,10 @@ void gate_kernel(const char* __restrict__ x, const char* __restrict__ u, const c
                 du.v[i] = gv.v[i] * n;
                 dx.v[i] = (gv.v[i] * uv.v[i] - n * mean) * rstd;
             }
-            dx.store(o0 + off);
-            du.store(o1 + off);
+            if (live) {
+                dx.store(o0 + off);
+                du.store(o1 + off);
+            }
         }
     }
 }
@@ -110,7 +119,8 @@ void gate_kernel(const char* __restrict__ x, const char* __restrict__ u, const c
 template <int D, bool BF16, bool BWD>
 hipError_t launch_gate_t(const void* x, const void* u, const void* dy, void* o0, void* o1, float eps,
                          long long rows, hipStream_t stream) {
-    constexpr int RPW = kThreads / (D / Vec<BF16>::N);
+    constexpr int ACT = D / Vec<BF16>::N;
+    constexpr int RPW = kThreads / (ACT <= 8 ? 8 : (ACT <= 16 ? 16 : (ACT <= 32 ? 32 : 64)));
     long long wgs = (rows + RPW - 1) / RPW;
     if (wgs > 256 * 16) wgs = 256 * 16;           // grid-stride beyond 16 workgroups per compute unit
     if (wgs <= 0) return hipSuccess;
@@ -129,6 +139,10 @@ hipError_t launch_gate(const void* x, const void* u, const void* dy, void* o0, v
     LTN_GATE_CASE(128, false, false); LTN_GATE_CASE(128, false, true);
     LTN_GATE_CASE(64, true, false); LTN_GATE_CASE(64, true, true);
     LTN_GATE_CASE(64, false, false); LTN_GATE_CASE(64, false, true);
+    LTN_GATE_CASE(96, true, false); LTN_GATE_CASE(96, true, true);
+    LTN_GATE_CASE(96, false, false); LTN_GATE_CASE(96, false, true);
+    LTN_GATE_CASE(256, true, false); LTN_GATE_CASE(256, true, true);
+    LTN_GATE_CASE(256, false, false); LTN_GATE_CASE(256, false, true);
 #undef LTN_GATE_CASE
     return hipErrorInvalidValue;
 }

@@ -164,8 +164,9 @@ def test_fwd_gated_argument_errors(lib):
     assert call(y=None) == E_NULL
     assert call(eps=-1.0) == E_SHAPE
     assert call(eps=float("nan")) == E_SHAPE
-    assert call(D=96) == E_UNSUP
-    assert call(D=256) == E_UNSUP                          # complete 256-wide rows do not fit a workgroup
+    assert call(D=96, o=None) == E_UNSUP                   # 96 / 256 features: only with the attention output stored
+    assert call(D=256, o=None) == E_UNSUP                  # (complete rows of these widths do not fit a workgroup)
+    assert call(D=80) == E_UNSUP
     assert call(y=P + 0x3000000000) == E_UNSUP                   # y aliases the gate
     assert call(y=P + 0x5000000000) == E_UNSUP                   # y aliases o
     assert call(u=P + 0x3000000008) == E_ALIGN
@@ -210,7 +211,7 @@ def test_gate_argument_errors(lib):
     assert fw(None, P + 0x1000000000, P + 0x2000000000, cf(0.0), 16, 128, 1, None) == E_NULL
     assert fw(P, P + 0x1000000000, P + 0x2000000000, cf(0.0), -1, 128, 1, None) == E_SHAPE
     assert fw(P, P + 0x1000000000, P + 0x2000000000, cf(-0.5), 16, 128, 1, None) == E_SHAPE
-    assert fw(P, P + 0x1000000000, P + 0x2000000000, cf(0.0), 16, 96, 1, None) == E_UNSUP
+    assert fw(P, P + 0x1000000000, P + 0x2000000000, cf(0.0), 16, 80, 1, None) == E_UNSUP
     assert fw(P, P + 0x1000000000, P + 0x2000000000, cf(0.0), 16, 128, 5, None) == E_UNSUP
     assert fw(P, P + 0x1000000000, P, cf(0.0), 16, 128, 1, None) == E_UNSUP              # y aliases x
     assert fw(P, P + 0x1000000004, P + 0x2000000000, cf(0.0), 16, 128, 1, None) == E_ALIGN

@@ -45,7 +45,7 @@ def test_gate_rows_empty_and_errors():
     with pytest.raises(ltn.LtnError):
         ltn.ltn_gate_fwd(a, a, out=a)                     # output aliases an input
     with pytest.raises(ltn.LtnError):
-        ltn.ltn_gate_fwd(a[:, :96].contiguous(), a[:, :96].contiguous())   # D = 96 not built
+        ltn.ltn_gate_fwd(a[:, :80].contiguous(), a[:, :80].contiguous())   # D = 80 not built
     with pytest.raises(ltn.LtnError):
         ltn.ltn_gate_fwd(a, a, eps=-1.0)
 
@@ -198,6 +198,38 @@ def test_forward_gated_full_size_every_chain():
         check(f"Y[{b}]", y[sl], y_ref, 1e-2)
         worst = max(worst, check_rows(f"Y[{b}] rows", y[sl], y_ref, TOL_ROW[w.dtype]))
     print(f"gated cfg3: worst per-token error {worst:.2e}")
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("D", [96, 256])
+def test_gated_other_head_dims(dtype, D):
+    """96 and 256 features: the gate kernels on rows, and the gated forward in its one form
+    there (plain forward, then the epilogue on the stored attention output)."""
+    tol = TOL[dtype]
+    rows = 1031
+    g = torch.Generator().manual_seed(940 + D)
+    x = (torch.randn(rows, D, generator=g) * 0.7).to(dtype)
+    u = torch.randn(rows, D, generator=g).to(dtype)
+    dy = torch.randn(rows, D, generator=g).to(dtype)
+    xd, ud, dyd = gpu(x, u, dy)
+    y = ltn.ltn_gate_fwd(xd, ud, 1e-6)
+    dx, du = ltn.ltn_gate_bwd(xd, ud, dyd, 1e-6)
+    yr = orc.gate_fwd(x, u, 1e-6)
+    dx_ref, du_ref = orc.gate_bwd(x, u, dy, 1e-6)
+    assert orc.rel_l2(y, yr) <= tol and orc.rel_l2(dx, dx_ref) <= tol and orc.rel_l2(du, du_ref) <= tol
+    row_err = np.linalg.norm(y.double().cpu().numpy() - yr, axis=1) / np.linalg.norm(yr, axis=1)
+    assert row_err.max() <= 2 * tol           # no row may be off (a reduction that mixes neighbouring rows)
+    Bt, H, N = 2, 3, 150
+    q, k, v = synth.make_qkv(Bt, H, N, D, dtype, 950 + D)
+    ug = synth.make_gate(Bt, H, N, D, dtype, 950 + D)
+    decay = mixed_decay(H)
+    o, yy = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, ug, decay), eps=1e-6)
+    o_ref = orc.fwd_recurrent(q, k, v, decay)
+    check("O", o, o_ref, tol)
+    check("Y | stored O", yy, orc.gate_fwd(o.cpu(), ug, 1e-6), tol)
+    check("Y", yy, orc.gate_fwd(o_ref, ug, 1e-6), 2 * tol)      # end to end: one stored rounding deep
+    with pytest.raises(ltn.LtnError):
+        ltn.ltn_attn_fwd_gated(*gpu(q, k, v, ug, decay), eps=1e-6, store_o=False)
 
 
 def test_forward_gated_argument_errors():
