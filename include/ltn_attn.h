@@ -304,17 +304,22 @@ size_t ltn_prologue_workspace_bytes(int Bt, int H, long long N, int D);
  *
  * Supported: (Dk, Dv) in {(256,128), (128,64)}; equal widths go through the entry points
  * above (LTN_ERR_UNSUPPORTED here).  block: 0 = library's choice; bf16 64; fp32 16, or 32
- * when Dk = 128.  No workspace is needed: long sequences are not cut into segments here.
+ * when Dk = 128.  workspace: device scratch of ltn_attn_workspace_bytes_dkdv(...) bytes (0
+ * unless few chains meet a long sequence, as for ltn_attn_fwd / ltn_attn_bwd; call = 0 for
+ * the forward, 1 for the backward); too small -> LTN_ERR_SHAPE, NULL when needed ->
+ * LTN_ERR_NULL.
  */
 ltn_status ltn_attn_fwd_dkdv(const void* q, const void* k, const void* v, void* o,
                              const float* decay, const float* kv_in, float* kv_out,
                              int Bt, int H, long long N, int Dk, int Dv, int block,
-                             ltn_dtype dtype, void* stream);
+                             ltn_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 ltn_status ltn_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
                              void* dq, void* dk, void* dv, const float* decay,
                              int Bt, int H, long long N, int Dk, int Dv, int block,
-                             ltn_dtype dtype, void* stream);
+                             ltn_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+size_t ltn_attn_workspace_bytes_dkdv(int Bt, int H, long long N, int Dk, int Dv, ltn_dtype dtype, int call);
 
 ltn_status ltn_attn_decode_steps_dkdv(const void* q, const void* k, const void* v, void* o,
                                       float* kv, const float* decay,

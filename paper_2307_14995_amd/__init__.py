@@ -29,6 +29,7 @@ from .binding import (  # noqa: F401
     ltn_attn_fwd_static,
     ltn_attn_bwd_tiled,
     ltn_probe_stream_read,
+    ltn_attn_workspace_bytes_dkdv,
 )
 
 __all__ = [
@@ -36,5 +37,5 @@ __all__ = [
     "ltn_attn_decode_step", "ltn_attn_decode_steps", "ltn_attn_pick_block", "ltn_attn_workspace_bytes",
     "ltn_attn_check_decay", "ltn_status_str", "ltn_prologue_fwd", "ltn_prologue_bwd", "ltn_prologue_workspace_bytes",
     "ltn_attn_fwd_dkdv", "ltn_attn_bwd_dkdv", "ltn_attn_decode_steps_dkdv",
-    "ltn_attn_query_plan", "ltn_attn_set_debug_plan", "ltn_attn_fwd_static", "ltn_attn_bwd_tiled", "ltn_probe_stream_read",
+    "ltn_attn_query_plan", "ltn_attn_set_debug_plan", "ltn_attn_fwd_static", "ltn_attn_bwd_tiled", "ltn_probe_stream_read", "ltn_attn_workspace_bytes_dkdv",
 ]

@@ -22,7 +22,7 @@ SYMBOLS = (
     "ltn_attn_workspace_bytes", "ltn_attn_check_decay", "ltn_status_str",
     "ltn_prologue_fwd", "ltn_prologue_bwd", "ltn_prologue_workspace_bytes",
     "ltn_attn_fwd_dkdv", "ltn_attn_bwd_dkdv", "ltn_attn_decode_steps_dkdv",
-    "ltn_attn_query_plan", "ltn_attn_set_debug_plan", "ltn_attn_fwd_static", "ltn_attn_bwd_tiled", "ltn_probe_stream_read",
+    "ltn_attn_query_plan", "ltn_attn_set_debug_plan", "ltn_attn_fwd_static", "ltn_attn_bwd_tiled", "ltn_probe_stream_read", "ltn_attn_workspace_bytes_dkdv",
 )
 
 
@@ -81,9 +81,11 @@ def load_library():
     lib.ltn_prologue_bwd.restype = ci
     lib.ltn_prologue_workspace_bytes.argtypes = [ci, ci, cl, ci]
     lib.ltn_prologue_workspace_bytes.restype = sz
-    lib.ltn_attn_fwd_dkdv.argtypes = [vp, vp, vp, vp, fp, fp, fp, ci, ci, cl, ci, ci, ci, ci, vp]
+    lib.ltn_attn_fwd_dkdv.argtypes = [vp, vp, vp, vp, fp, fp, fp, ci, ci, cl, ci, ci, ci, ci, vp, sz, vp]
     lib.ltn_attn_fwd_dkdv.restype = ci
-    lib.ltn_attn_bwd_dkdv.argtypes = [vp, vp, vp, vp, vp, vp, vp, fp, ci, ci, cl, ci, ci, ci, ci, vp]
+    lib.ltn_attn_bwd_dkdv.argtypes = [vp, vp, vp, vp, vp, vp, vp, fp, ci, ci, cl, ci, ci, ci, ci, vp, sz, vp]
+    lib.ltn_attn_workspace_bytes_dkdv.argtypes = [ci, ci, cl, ci, ci, ci, ci]
+    lib.ltn_attn_workspace_bytes_dkdv.restype = sz
     lib.ltn_attn_bwd_dkdv.restype = ci
     lib.ltn_attn_decode_steps_dkdv.argtypes = [vp, vp, vp, vp, fp, fp, ci, ci, ci, ci, ci, ci, vp]
     lib.ltn_attn_decode_steps_dkdv.restype = ci
@@ -127,6 +129,11 @@ def ltn_attn_set_debug_plan(dv=0, segs=0) -> None:
     rc = load_library().ltn_attn_set_debug_plan(int(dv), int(segs))
     if rc != 0:
         raise LtnError(rc, "ltn_attn_set_debug_plan")
+
+
+def ltn_attn_workspace_bytes_dkdv(Bt, H, N, Dk, Dv, dtype, call) -> int:
+    """call: 0 = ltn_attn_fwd_dkdv, 1 = ltn_attn_bwd_dkdv."""
+    return int(load_library().ltn_attn_workspace_bytes_dkdv(Bt, H, N, Dk, Dv, _dtype_code(dtype), int(call)))
 
 
 def ltn_attn_check_decay(decay) -> int:
@@ -499,9 +506,12 @@ def ltn_attn_fwd_dkdv(q, k, v, decay, kv_in=None, return_state=False, block=0, o
             raise ValueError("kv_in must be fp32 [Bt,H,Dk,Dv]")
     if kv_out is None and return_state:
         kv_out = torch.empty((Bt, H, Dk, Dv), dtype=torch.float32, device=q.device)
+    code = _dtype_code(q.dtype)
+    ws_bytes = int(lib.ltn_attn_workspace_bytes_dkdv(Bt, H, N, Dk, Dv, code, 0))
+    ws = _workspace(ws_bytes, q.device)
     with torch.cuda.device(q.device):
         rc = lib.ltn_attn_fwd_dkdv(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(decay), _ptr(kv_in), _ptr(kv_out),
-                                   Bt, H, N, Dk, Dv, int(block), _dtype_code(q.dtype), _stream(q.device))
+                                   Bt, H, N, Dk, Dv, int(block), code, _ptr(ws), ws_bytes, _stream(q.device))
     if rc != 0:
         raise LtnError(rc, "ltn_attn_fwd_dkdv")
     return (o, kv_out) if (return_state or kv_out is not None) else o
@@ -515,9 +525,12 @@ def ltn_attn_bwd_dkdv(q, k, v, d_o, decay, block=0):
     if d_o.shape != v.shape or d_o.dtype != v.dtype:
         raise ValueError("d_o must have v's shape and dtype")
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    code = _dtype_code(q.dtype)
+    ws_bytes = int(lib.ltn_attn_workspace_bytes_dkdv(Bt, H, N, Dk, Dv, code, 1))
+    ws = _workspace(ws_bytes, q.device)
     with torch.cuda.device(q.device):
         rc = lib.ltn_attn_bwd_dkdv(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(decay),
-                                   Bt, H, N, Dk, Dv, int(block), _dtype_code(q.dtype), _stream(q.device))
+                                   Bt, H, N, Dk, Dv, int(block), code, _ptr(ws), ws_bytes, _stream(q.device))
     if rc != 0:
         raise LtnError(rc, "ltn_attn_bwd_dkdv")
     return dq, dk, dv

@@ -528,41 +528,116 @@ static ltn_status check_dkdv(int Bt, int H, long long N, int Dk, int Dv, int blo
     return LTN_OK;
 }
 
-// One launch of `pb` (passes of one shape): a, b with DA features, c and out with DC.
-static ltn_status run_dkdv(const ltn::PassBatch& pb, int DA, int DC, int blk, ltn_dtype dtype, hipStream_t st) {
+// Slices the bf16 kernels exist for behind a DA-wide query/key side: 32..64 for 256 (its state
+// copies fill the LDS beyond that) and for 64, 32..min(DC,128) otherwise; the state-only sweep
+// of the sequence-parallel form uses the widest of them.
+static int dkdv_hi(int DA, int DC) { return (DA == 256 || DA == 64) ? 64 : (DC < 128 ? DC : 128); }
+
+// Sequence-parallel plan of a launch of `chain_passes` passes of shape (DA, DC): as for equal
+// widths (pick_segments), with DC / hi workgroups per chain segment.  bf16 only.
+static SegPlan pick_segments_dkdv(long long chain_passes, long long N, int DA, int DC, ltn_dtype dtype) {
+    SegPlan plan = {1, 0};
+    if (dtype != LTN_BF16 || chain_passes <= 0 || N <= 64) return plan;
+    const long long per_seg = DC / dkdv_hi(DA, DC);
+    long long want = 256 / (per_seg * chain_passes);
+    if (want > N / 1024) want = N / 1024;
+    if (want < kMinSegsFullWidth) want = 1;
+    if (const int v = g_debug_segs.load(std::memory_order_relaxed)) want = v;
+    if (want <= 1) return plan;
+    long long len = (N + want - 1) / want;
+    len = (len + 63) / 64 * 64;
+    const long long segs = (N + len - 1) / len;
+    if (segs <= 1 || segs > 0x7fff) return plan;
+    plan.segs = (int)segs;
+    plan.seg_len = len;
+    return plan;
+}
+
+// One launch of `pb` (passes of one shape): a, b with DA features, c and out with DC; cut into
+// segments (state-only sweep, scan, per-segment pass) when the plan says so.
+static ltn_status run_dkdv(ltn::PassBatch& pb, int DA, int DC, int blk, ltn_dtype dtype, void* workspace, hipStream_t st) {
     const long long chain_passes = (long long)pb.chains * pb.count;
+    pb.segs = 1;
     hipError_t e;
-    if (dtype == LTN_BF16) {
-        // slices the kernels exist for: 32..64 behind a 256-wide query/key side (its state
-        // copies fill the LDS beyond that) and behind a 64-wide one, 32..min(DC,128) otherwise
-        const int hi = (DA == 256 || DA == 64) ? 64 : (DC < 128 ? DC : 128);
-        e = ltn::launch_pass_bf16(pb, DA, pick_dv_range(chain_passes, DC, 32, hi), st, DC);
-    } else {
+    if (dtype != LTN_BF16) {
         const int lo = 64, hi = (DA == 256) ? 64 : (DC < 128 ? DC : 128);
         e = ltn::launch_pass_f32(pb, DA, pick_dv_range(chain_passes, DC, lo, hi), blk, st, DC);
+        return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
     }
+    const int hi = dkdv_hi(DA, DC);
+    const SegPlan plan = pick_segments_dkdv(chain_passes, pb.N, DA, DC, dtype);
+    if (plan.segs == 1) {
+        e = ltn::launch_pass_bf16(pb, DA, pick_dv_range(chain_passes, DC, 32, hi), st, DC);
+        return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+    }
+    if (!workspace) return LTN_ERR_NULL;
+    float* states = static_cast<float*>(workspace);
+    const size_t per_pass = (size_t)pb.chains * plan.segs * DA * DC;
+    const float* kv_in = pb.p[0].state_in;
+    float* kv_out = pb.p[0].state_out;
+    ltn::PassBatch sweep = pb;
+    sweep.segs = plan.segs;
+    sweep.seg_len = plan.seg_len;
+    sweep.state_only = 1;
+    sweep.need_last = kv_out != nullptr;
+    for (int i = 0; i < pb.count; ++i) {
+        sweep.p[i].out = nullptr;
+        sweep.p[i].state_in = nullptr;
+        sweep.p[i].state_out = states + i * per_pass;
+    }
+    if (ltn::launch_pass_bf16(sweep, DA, hi, st, DC) != hipSuccess) return LTN_ERR_LAUNCH;
+    if (ltn::launch_segment_scan(states, kv_in, kv_out, pb.decay, pb.count, pb.chains, pb.H, plan.segs, plan.seg_len,
+                                 pb.N, DA, st, DC) != hipSuccess)
+        return LTN_ERR_LAUNCH;
+    ltn::PassBatch main = pb;
+    main.segs = plan.segs;
+    main.seg_len = plan.seg_len;
+    for (int i = 0; i < pb.count; ++i) {
+        main.p[i].state_in = states + i * per_pass;
+        main.p[i].state_out = nullptr;
+    }
+    e = ltn::launch_pass_bf16(main, DA, pick_dv_range(chain_passes * plan.segs, DC, 32, hi), st, DC);
     return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
+}
+
+size_t ltn_attn_workspace_bytes_dkdv(int Bt, int H, long long N, int Dk, int Dv, ltn_dtype dtype, int call) {
+    if (Bt <= 0 || H <= 0 || N <= 0 || call < 0 || call > 1) return 0;
+    if (!((Dk == 256 && Dv == 128) || (Dk == 128 && Dv == 64))) return 0;
+    const long long chains = (long long)Bt * H;
+    const size_t state = (size_t)Dk * Dv * sizeof(float);
+    // forward and the dV pass: (Dk, Dv), one pass per chain; dK and dQ: (Dv, Dk), two; the two
+    // launches of the backward follow each other on the stream and share the workspace
+    const SegPlan a = pick_segments_dkdv(chains, N, Dk, Dv, dtype);
+    size_t need = a.segs > 1 ? (size_t)chains * a.segs * state : 0;
+    if (call == 1) {
+        const SegPlan b = pick_segments_dkdv(2 * chains, N, Dv, Dk, dtype);
+        const size_t nb = b.segs > 1 ? (size_t)2 * chains * b.segs * state : 0;
+        if (nb > need) need = nb;
+    }
+    return need;
 }
 
 ltn_status ltn_attn_fwd_dkdv(const void* q, const void* k, const void* v, void* o,
                              const float* decay, const float* kv_in, float* kv_out,
                              int Bt, int H, long long N, int Dk, int Dv, int block, ltn_dtype dtype,
-                             void* stream) {
+                             void* workspace, size_t workspace_bytes, void* stream) {
     const bool empty = (Bt == 0 || H == 0 || N == 0);
     if (!decay || (!empty && (!q || !k || !v || !o))) return LTN_ERR_NULL;
     int blk = 0;
     const ltn_status cs = check_dkdv(Bt, H, N, Dk, Dv, block, dtype, &blk);
     if (cs != LTN_OK) return cs;
+    const size_t need_ws = ltn_attn_workspace_bytes_dkdv(Bt, H, N, Dk, Dv, dtype, 0);
+    if (workspace_bytes < need_ws) return LTN_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(kv_in) ||
-        !aligned16(kv_out) || (reinterpret_cast<uintptr_t>(decay) & 3u))
+        !aligned16(kv_out) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
     const long long chains = (long long)Bt * H;
     if (!empty) {
         const size_t qb = (size_t)chains * (size_t)N * Dk * esize_of(dtype), vb = (size_t)chains * (size_t)N * Dv * esize_of(dtype);
         const size_t sb = (size_t)chains * Dk * Dv * sizeof(float);
         const Span ins[4] = {{q, qb}, {k, qb}, {v, vb}, {kv_in == kv_out ? nullptr : kv_in, sb}};
-        const Span outs[2] = {{o, vb}, {kv_out, sb}};
-        if (outputs_alias(outs, 2, ins, 4)) return LTN_ERR_UNSUPPORTED;
+        const Span outs[3] = {{o, vb}, {kv_out, sb}, {workspace, need_ws}};
+        if (outputs_alias(outs, 3, ins, 4)) return LTN_ERR_UNSUPPORTED;
     }
     if (chains == 0) return LTN_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -579,27 +654,29 @@ ltn_status ltn_attn_fwd_dkdv(const void* q, const void* k, const void* v, void* 
     pb.H = H;
     pb.N = N;
     pb.p[0] = ltn::PassArgs{q, k, v, o, kv_in, kv_out, 0};
-    return run_dkdv(pb, Dk, Dv, blk, dtype, st);
+    return run_dkdv(pb, Dk, Dv, blk, dtype, workspace, st);
 }
 
 ltn_status ltn_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
                              void* dq, void* dk, void* dv, const float* decay,
                              int Bt, int H, long long N, int Dk, int Dv, int block, ltn_dtype dtype,
-                             void* stream) {
+                             void* workspace, size_t workspace_bytes, void* stream) {
     const bool empty = (Bt == 0 || H == 0 || N == 0);
     if (!decay || (!empty && (!q || !k || !v || !d_o || !dq || !dk || !dv))) return LTN_ERR_NULL;
     int blk = 0;
     const ltn_status cs = check_dkdv(Bt, H, N, Dk, Dv, block, dtype, &blk);
     if (cs != LTN_OK) return cs;
+    const size_t need_ws = ltn_attn_workspace_bytes_dkdv(Bt, H, N, Dk, Dv, dtype, 1);
+    if (workspace_bytes < need_ws) return LTN_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) ||
-        !aligned16(dk) || !aligned16(dv) || (reinterpret_cast<uintptr_t>(decay) & 3u))
+        !aligned16(dk) || !aligned16(dv) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(decay) & 3u))
         return LTN_ERR_ALIGN;
     const long long chains = (long long)Bt * H;
     if (!empty) {
         const size_t qb = (size_t)chains * (size_t)N * Dk * esize_of(dtype), vb = (size_t)chains * (size_t)N * Dv * esize_of(dtype);
         const Span ins[4] = {{q, qb}, {k, qb}, {v, vb}, {d_o, vb}};
-        const Span outs[3] = {{dq, qb}, {dk, qb}, {dv, vb}};
-        if (outputs_alias(outs, 3, ins, 4)) return LTN_ERR_UNSUPPORTED;
+        const Span outs[4] = {{dq, qb}, {dk, qb}, {dv, vb}, {workspace, need_ws}};
+        if (outputs_alias(outs, 4, ins, 4)) return LTN_ERR_UNSUPPORTED;
     }
     if (chains == 0 || N == 0) return LTN_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -614,12 +691,12 @@ ltn_status ltn_attn_bwd_dkdv(const void* q, const void* k, const void* v, const 
     pb.N = N;
     pb.count = 1;
     pb.p[0] = ltn::PassArgs{k, q, d_o, dv, nullptr, nullptr, 1};
-    const ltn_status s1 = run_dkdv(pb, Dk, Dv, blk, dtype, st);
+    const ltn_status s1 = run_dkdv(pb, Dk, Dv, blk, dtype, workspace, st);
     if (s1 != LTN_OK) return s1;
     pb.count = 2;
     pb.p[0] = ltn::PassArgs{v, d_o, q, dk, nullptr, nullptr, 1};
     pb.p[1] = ltn::PassArgs{d_o, v, k, dq, nullptr, nullptr, 0};
-    return run_dkdv(pb, Dv, Dk, blk, dtype, st);
+    return run_dkdv(pb, Dv, Dk, blk, dtype, workspace, st);
 }
 
 ltn_status ltn_attn_decode_steps_dkdv(const void* q, const void* k, const void* v, void* o,

@@ -55,8 +55,8 @@ struct PassBatch {
 // (D, D/2 or, for D = 128, D/4; 64 or 32 for D = 256 and 32 for D = 96, plain pass only).
 // DC (0: = D): features per token of c and out when they differ from those of a and b
 // (the LRPE-d expansion of Eq. 1 doubles the query/key width): a, b [chains, N, D];
-// c, out [chains, N, DC]; states [chains, D, DC]; dv slices DC.  Plain pass, one segment.
-// (D, DC) in {(256,128), (128,256), (128,64), (64,128)}.
+// c, out [chains, N, DC]; states [chains, D, DC]; dv slices DC.  Plain pass, or the state-only
+// sweep with dv = 64 (128 for (128,256)).  (D, DC) in {(256,128), (128,256), (128,64), (64,128)}.
 hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream, int DC = 0);
 // Forward by the quadratic tiling of App. B Algorithm 3 (comparison kernel), bf16, zero
 // initial state, D in {64,128}.
@@ -81,7 +81,7 @@ hipError_t launch_pass_f32_mfma(const PassBatch& pb, int D, int dv, int block, h
 // and writes the state after the last segment to kv_out (pass 0) when given.
 hipError_t launch_segment_scan(float* states, const float* kv_in, float* kv_out, const float* decay,
                                int count, int chains, int H, int segs, long long seg_len, long long N,
-                               int D, hipStream_t stream);
+                               int D, hipStream_t stream, int DC = 0 /* 0: = D; states are [D x DC] */);
 // kv[c] (or zeros if null) -> kv_out[c], n floats.
 hipError_t launch_state_copy(const float* kv_in, float* kv_out, size_t n, hipStream_t stream);
 // `steps` consecutive decode steps per chain (q, k: [chains, steps, DK]; v, o: [chains,

@@ -709,11 +709,10 @@ void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
 template <int D, int DV, int MODE = kPlain, int DC = D, int DR = D>
 hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
     static_assert(DV <= DC && DC % DV == 0, "value-column slices tile the C operand");
-    static_assert(DC == D || MODE == kPlain || (MODE == kStateOnly && DR == DC), "unequal widths: plain pass only");
+    static_assert(DC == D || MODE != kGated, "unequal widths: no gated epilogue");
     const int nsplit = DC / DV;
     const long long wgs = (long long)pb.chains * pb.segs * pb.count * nsplit;
     if (wgs <= 0 || wgs > 0x7fffffffLL || pb.segs < 1) return hipErrorInvalidValue;
-    if (DC != D && DR != DC && pb.segs != 1) return hipErrorInvalidValue;    // segments: equal widths (96 as 128 included)
     hipLaunchKernelGGL((pass_bf16_kernel<D, DV, MODE, DC, DR>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
     return hipGetLastError();
 }
@@ -722,7 +721,14 @@ hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
 
 hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stream, int DC) {
     if (DC != 0 && DC != D) {              // queries/keys and values of different widths (plain pass only)
-        if (pb.p[0].gate || pb.state_only) return hipErrorInvalidValue;
+        if (pb.p[0].gate) return hipErrorInvalidValue;
+        if (pb.state_only) {               // segment end states: one slice width per shape
+            if (D == 256 && dv == 64 && DC == 128) return launch_t<256, 64, kStateOnly, 128>(pb, stream);
+            if (D == 128 && dv == 128 && DC == 256) return launch_t<128, 128, kStateOnly, 256>(pb, stream);
+            if (D == 128 && dv == 64 && DC == 64) return launch_t<128, 64, kStateOnly, 64>(pb, stream);
+            if (D == 64 && dv == 64 && DC == 128) return launch_t<64, 64, kStateOnly, 128>(pb, stream);
+            return hipErrorInvalidValue;
+        }
 #define LTN_BF16_DC(d, v, c) if (D == d && dv == v && DC == c) return launch_t<d, v, kPlain, c>(pb, stream)
         LTN_BF16_DC(256, 64, 128); LTN_BF16_DC(256, 32, 128);
         LTN_BF16_DC(128, 128, 256); LTN_BF16_DC(128, 64, 256); LTN_BF16_DC(128, 32, 256);

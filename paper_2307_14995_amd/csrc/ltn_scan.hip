@@ -44,13 +44,14 @@ void segment_scan_kernel(float* __restrict__ states, const float* __restrict__ k
 
 hipError_t launch_segment_scan(float* states, const float* kv_in, float* kv_out, const float* decay,
                                int count, int chains, int H, int segs, long long seg_len, long long N,
-                               int D, hipStream_t stream) {
-    const long long total = (long long)count * chains * D * D;
+                               int D, hipStream_t stream, int DC) {
+    if (DC == 0) DC = D;
+    const long long total = (long long)count * chains * D * DC;
     if (total <= 0 || segs < 1 || seg_len <= 0 || seg_len > 0x7fffffffLL) return hipErrorInvalidValue;
     const long long wgs = (total + 255) / 256;
     if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(segment_scan_kernel, dim3((unsigned)wgs), dim3(256), 0, stream,
-                       states, kv_in, kv_out, decay, count, chains, H, segs, seg_len, N, D * D);
+                       states, kv_in, kv_out, decay, count, chains, H, segs, seg_len, N, D * DC);
     return hipGetLastError();
 }
 

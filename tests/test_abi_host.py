@@ -224,7 +224,7 @@ def test_gate_argument_errors(lib):
 def test_dkdv_argument_errors(lib):
     def f(q=P, k=P + 0x1000000000, v=P + 0x2000000000, o=P + 0x3000000000, decay=P + 0x4000000000, kv_in=None, kv_out=None,
           Bt=1, H=2, N=256, Dk=256, Dv=128, block=0, dtype=1):
-        return lib.ltn_attn_fwd_dkdv(q, k, v, o, decay, kv_in, kv_out, Bt, H, N, Dk, Dv, block, dtype, None)
+        return lib.ltn_attn_fwd_dkdv(q, k, v, o, decay, kv_in, kv_out, Bt, H, N, Dk, Dv, block, dtype, None, 0, None)
     assert f(q=None) == E_NULL and f(o=None) == E_NULL and f(decay=None) == E_NULL
     assert f(N=-1) == E_SHAPE and f(Dk=0) == E_SHAPE
     assert f(Dk=128, Dv=128) == E_UNSUP            # equal widths: the plain entry points
@@ -240,12 +240,24 @@ def test_dkdv_argument_errors(lib):
 
     def b(q=P, k=P + 0x1000000000, v=P + 0x2000000000, g=P + 0x3000000000, dq=P + 0x5000000000, dk=P + 0x6000000000, dv=P + 0x7000000000,
           decay=P + 0x4000000000, Bt=1, H=2, N=256, Dk=256, Dv=128, block=0, dtype=1):
-        return lib.ltn_attn_bwd_dkdv(q, k, v, g, dq, dk, dv, decay, Bt, H, N, Dk, Dv, block, dtype, None)
+        return lib.ltn_attn_bwd_dkdv(q, k, v, g, dq, dk, dv, decay, Bt, H, N, Dk, Dv, block, dtype, None, 0, None)
     assert b(g=None) == E_NULL and b(dk=None) == E_NULL
     assert b(Dk=128, Dv=128) == E_UNSUP and b(N=-2) == E_SHAPE
     assert b(dq=P) == E_UNSUP and b(dk=P + 0x7000000000) == E_UNSUP
     assert b(dv=P + 0x7000000008) == E_ALIGN
     assert b(N=0) == OK
+
+    # few long chains: the unequal-width calls are cut into segments too and then need their workspace
+    import torch
+    assert ltn.ltn_attn_workspace_bytes_dkdv(4, 32, 8192, 256, 128, torch.bfloat16, 0) == 0
+    need = ltn.ltn_attn_workspace_bytes_dkdv(1, 8, 16384, 256, 128, torch.bfloat16, 0)
+    assert need == 8 * 16 * 256 * 128 * 4                  # 16 segments of 1024 tokens, two 64-column workgroups each
+    assert ltn.ltn_attn_workspace_bytes_dkdv(1, 8, 16384, 256, 128, torch.float32, 0) == 0
+    assert ltn.ltn_attn_workspace_bytes_dkdv(1, 8, 16384, 256, 128, torch.bfloat16, 1) >= need
+    assert ltn.ltn_attn_workspace_bytes_dkdv(1, 8, 16384, 128, 128, torch.bfloat16, 0) == 0   # no such shape
+    assert f(H=8, N=16384) == E_SHAPE                      # workspace too small
+    assert lib.ltn_attn_fwd_dkdv(P, P + (1 << 36), P + (2 << 36), P + (3 << 36), P + (4 << 36), None, None,
+                                 1, 8, 16384, 256, 128, 0, 1, None, need, None) == E_NULL
 
     def d(q=P, k=P + 0x1000000000, v=P + 0x2000000000, o=P + 0x3000000000, kv=P + 0x8000000000, decay=P + 0x4000000000,
           Bt=1, H=2, S=3, Dk=256, Dv=128, dtype=1):

@@ -9,7 +9,7 @@ import torch
 import paper_2307_14995_amd as ltn
 from paper_2307_14995_amd import synth
 from oracle import ltn_oracle as orc
-from _helpers import check, dev, gpu, mixed_decay
+from _helpers import TOL_ROW, check, check_rows, dev, force_plan, gpu, mixed_decay
 
 pytestmark = pytest.mark.gpu
 
@@ -124,26 +124,68 @@ def test_dkdv_empty_and_errors():
         ltn.ltn_attn_fwd_dkdv(a, a.clone(), a[..., :32].contiguous(), decay)
 
 
-def test_dkdv_full_size_sampled_chains():
-    # first-layer shape of the 7B-sized model, the launch configuration the report times:
-    # every chain is computed on the GPU, two of them are checked against the oracle
+@pytest.mark.parametrize("Dk,Dv", SHAPES)
+@pytest.mark.parametrize("N,segs", [(130, 2), (517, 3), (1000, 5)])
+def test_dkdv_segmented_forward_backward(Dk, Dv, N, segs):
+    """Chains cut into segments (forced): state-only sweep, scan over [Dk x Dv] states, per-segment
+    pass; with an initial state, the final state, and all three gradients."""
+    Bt, H = 1, 3
+    dtype = torch.bfloat16
+    q, k, v = synth.make_qkv_dkdv(Bt, H, N, Dk, Dv, dtype, 620 + N)
+    d_o = synth.make_do(Bt, H, N, Dv, dtype, 620 + N)
+    kv0 = torch.randn(Bt, H, Dk, Dv, generator=torch.Generator().manual_seed(N)) * 0.1
+    decay = mixed_decay(H)
+    ref, kv_ref = orc.fwd_recurrent_dkdv(q, k, v, decay, kv_in=kv0, return_state=True)
+    refs = orc.bwd_recurrent_dkdv(q, k, v, d_o, decay)
+    with force_plan(segs=segs):
+        assert ltn.ltn_attn_workspace_bytes_dkdv(Bt, H, N, Dk, Dv, dtype, 0) > 0
+        assert ltn.ltn_attn_workspace_bytes_dkdv(Bt, H, N, Dk, Dv, dtype, 1) > 0
+        o, kv = ltn.ltn_attn_fwd_dkdv(*gpu(q, k, v, decay), kv_in=kv0.to(dev()), return_state=True)
+        o2 = ltn.ltn_attn_fwd_dkdv(*gpu(q, k, v, decay), kv_in=kv0.to(dev()))       # final state not requested
+        grads = ltn.ltn_attn_bwd_dkdv(*gpu(q, k, v, d_o, decay))
+    check("o", o, ref, 1e-2)
+    check("kv", kv, kv_ref, 1e-2)
+    assert torch.equal(o2, o)
+    for name, got, r in zip(("dq", "dk", "dv"), grads, refs):
+        check(name, got, r, 1e-2)
+
+
+def test_dkdv_few_long_chains_are_cut_into_segments_by_default():
+    Bt, H, N, Dk, Dv = 1, 4, 4096 + 70, 256, 128         # 4 chains x 2 slices: cut 4 ways by the library's own rule
+    dtype = torch.bfloat16
+    assert ltn.ltn_attn_workspace_bytes_dkdv(Bt, H, N, Dk, Dv, dtype, 0) == 4 * Bt * H * Dk * Dv * 4
+    q, k, v = synth.make_qkv_dkdv(Bt, H, N, Dk, Dv, dtype, 640)
+    d_o = synth.make_do(Bt, H, N, Dv, dtype, 640)
+    decay = synth.decay_bench_rule(H)
+    o, kv = ltn.ltn_attn_fwd_dkdv(*gpu(q, k, v, decay), return_state=True)
+    ref, kv_ref = orc.fwd_recurrent_dkdv(q, k, v, decay, return_state=True)
+    check("o", o, ref, 1e-2)
+    check_rows("o rows", o, ref, TOL_ROW[dtype])
+    check("kv", kv, kv_ref, 1e-2)
+    for name, got, r in zip(("dq", "dk", "dv"), ltn.ltn_attn_bwd_dkdv(*gpu(q, k, v, d_o, decay)),
+                            orc.bwd_recurrent_dkdv(q, k, v, d_o, decay)):
+        check(name, got, r, 1e-2)
+        check_rows(name + " rows", got, r, TOL_ROW[dtype])
+
+
+def test_dkdv_full_size_every_chain():
+    # first-layer shape of the 7B-sized model, the launch configuration the report times: every
+    # chain against the oracle (batch entry by batch entry), slice by slice and token by token
     Bt, H, N, Dk, Dv = 4, 32, 8192, 256, 128
     dtype = torch.bfloat16
     q, k, v = synth.make_qkv_dkdv(Bt, H, N, Dk, Dv, dtype, 600)
     d_o = synth.make_do(Bt, H, N, Dv, dtype, 600)
     decay = synth.decay_bench_rule(H)
     qd, kd, vd, gd, dd = gpu(q, k, v, d_o, decay)
-    o = ltn.ltn_attn_fwd_dkdv(qd, kd, vd, dd)
-    dq, dk, dv = ltn.ltn_attn_bwd_dkdv(qd, kd, vd, gd, dd)
-    torch.cuda.synchronize()
-    for b, h in ((0, 3), (3, 31)):
-        sl = (slice(b, b + 1), slice(h, h + 1))
-        dec = decay[h:h + 1]
-        ref = orc.fwd_recurrent_dkdv(q[sl], k[sl], v[sl], dec)
-        check(f"o[{b},{h}]", o[sl], ref, TOL[dtype])
-        for name, got, r in zip(("dq", "dk", "dv"), (dq, dk, dv),
-                                orc.bwd_recurrent_dkdv(q[sl], k[sl], v[sl], d_o[sl], dec)):
-            check(f"{name}[{b},{h}]", got[sl], r, TOL[dtype])
+    o = ltn.ltn_attn_fwd_dkdv(qd, kd, vd, dd).cpu()
+    grads = tuple(x.cpu() for x in ltn.ltn_attn_bwd_dkdv(qd, kd, vd, gd, dd))
+    for b in range(Bt):
+        sl = slice(b, b + 1)
+        refs = (orc.fwd_recurrent_dkdv(q[sl], k[sl], v[sl], decay),) + tuple(
+            orc.bwd_recurrent_dkdv(q[sl], k[sl], v[sl], d_o[sl], decay))
+        for name, got, r in zip(("o", "dq", "dk", "dv"), (o,) + grads, refs):
+            check(f"{name}[{b}]", got[sl], r, TOL[dtype])
+            check_rows(f"{name}[{b}] rows", got[sl], r, TOL_ROW[dtype])
 
 
 # ------------------------------------------------------------------ swish and the expansion
