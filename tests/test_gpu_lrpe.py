@@ -150,6 +150,41 @@ def test_dkdv_segmented_forward_backward(Dk, Dv, N, segs):
         check(name, got, r, 1e-2)
 
 
+def _random_cases_dkdv(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        Dk, Dv = SHAPES[int(rng.integers(0, len(SHAPES)))]
+        Bt, H = int(rng.integers(1, 4)), int(rng.integers(1, 13))       # the chain count decides the slice width
+        N = int(rng.choice([rng.integers(1, 64), rng.integers(64, 400), rng.integers(400, 1200)]))
+        dtype = torch.bfloat16 if rng.integers(0, 3) else torch.float32
+        segs = int(rng.choice([1, 2, 3, 6])) if dtype == torch.bfloat16 else 0
+        cases.append((i, Bt, H, N, Dk, Dv, dtype, segs))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases_dkdv(12, 2027),
+                         ids=lambda c: "B%dH%dN%dDk%dDv%d%sseg%d" % (c[1:6] + (str(c[6]).split(".")[-1],) + c[7:]))
+def test_dkdv_seeded_shape_sweep(case):
+    """Unequal widths on seeded odd shapes, both dtypes, segment count forced (bf16)."""
+    i, Bt, H, N, Dk, Dv, dtype, segs = case
+    tol = TOL[dtype]
+    q, k, v = synth.make_qkv_dkdv(Bt, H, N, Dk, Dv, dtype, 660 + i)
+    d_o = synth.make_do(Bt, H, N, Dv, dtype, 660 + i)
+    kv0 = torch.randn(Bt, H, Dk, Dv, generator=torch.Generator().manual_seed(90 + i)) * 0.1
+    decay = torch.rand(H, generator=torch.Generator().manual_seed(1300 + i))
+    decay[0] = 1.0
+    ref, kv_ref = orc.fwd_recurrent_dkdv(q, k, v, decay, kv_in=kv0, return_state=True)
+    refs = orc.bwd_recurrent_dkdv(q, k, v, d_o, decay)
+    with force_plan(segs=segs):
+        o, kv = ltn.ltn_attn_fwd_dkdv(*gpu(q, k, v, decay), kv_in=kv0.to(dev()), return_state=True)
+        grads = ltn.ltn_attn_bwd_dkdv(*gpu(q, k, v, d_o, decay))
+    check("o", o, ref, tol)
+    check("kv", kv, kv_ref, tol)
+    for name, got, r in zip(("dq", "dk", "dv"), grads, refs):
+        check(name, got, r, tol)
+
+
 def test_dkdv_few_long_chains_are_cut_into_segments_by_default():
     Bt, H, N, Dk, Dv = 1, 4, 4096 + 70, 256, 128         # 4 chains x 2 slices: cut 4 ways by the library's own rule
     dtype = torch.bfloat16

@@ -504,6 +504,75 @@ def test_bf16_seeded_shape_sweep(case):
         check(n, x, r, 1e-2)
 
 
+def _random_cases_f32(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        D = int(rng.choice([64, 128]))
+        Bt, H = int(rng.integers(1, 4)), int(rng.integers(1, 10))
+        N = int(rng.choice([rng.integers(1, 64), rng.integers(64, 400), rng.integers(400, 900)]))
+        block = int(rng.choice([0, 16, 32] + ([64] if D == 64 else [])))
+        dv = int(rng.choice([0, D, D // 2, D // 4]))      # widths a kernel lacks are ignored by the library
+        cases.append((i, Bt, H, N, D, block, dv))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases_f32(12, 2025), ids=lambda c: "B%dH%dN%dD%dblk%ddv%d" % c[1:])
+def test_fp32_seeded_shape_sweep(case):
+    """fp32 tensors: forward (initial state in, final state out) and backward on seeded odd
+    shapes, block length and value-column split forced, against the oracle."""
+    i, Bt, H, N, D, block, dv = case
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.float32, 900 + i)
+    g = synth.make_do(Bt, H, N, D, torch.float32, 900 + i)
+    kv0 = torch.randn(Bt, H, D, D, generator=torch.Generator().manual_seed(50 + i)) * 0.1
+    decay = torch.rand(H, generator=torch.Generator().manual_seed(1100 + i))
+    decay[-1] = 0.0
+    ref, kv_ref = orc.fwd_recurrent(q, k, v, decay, kv_in=kv0, return_state=True)
+    refs = orc.bwd_recurrent(q, k, v, g, decay)
+    with force_plan(dv, 0):
+        o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), kv_in=kv0.to(dev()), return_state=True, block=block)
+        outs = ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay), block=block)
+    check("O", o, ref, 1e-4)
+    check("kv", kv, kv_ref, 1e-4)
+    check_rows("O rows", o, ref, TOL_ROW[torch.float32])
+    for n, x, r in zip(("dQ", "dK", "dV"), outs, refs):
+        check(n, x, r, 1e-4)
+        check_rows(n + " rows", x, r, TOL_ROW[torch.float32])
+
+
+def _random_cases_wide(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        D = int(rng.choice([96, 256]))
+        Bt, H = int(rng.integers(1, 3)), int(rng.integers(1, 7))
+        N = int(rng.choice([rng.integers(1, 64), rng.integers(64, 400), rng.integers(400, 1200)]))
+        segs = int(rng.choice([1, 1, 2, 3, 5]))
+        dv = int(rng.choice([0, 32, 64]))
+        cases.append((i, Bt, H, N, D, dv, segs))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases_wide(10, 2026), ids=lambda c: "B%dH%dN%dD%ddv%dseg%d" % c[1:])
+def test_bf16_wide_heads_seeded_shape_sweep(case):
+    """Heads of 96 and 256 features on seeded odd shapes, segment count forced."""
+    i, Bt, H, N, D, dv, segs = case
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 950 + i)
+    g = synth.make_do(Bt, H, N, D, torch.bfloat16, 950 + i)
+    kv0 = torch.randn(Bt, H, D, D, generator=torch.Generator().manual_seed(70 + i)) * 0.1
+    decay = torch.rand(H, generator=torch.Generator().manual_seed(1200 + i))
+    decay[0] = 1.0
+    ref, kv_ref = orc.fwd_recurrent(q, k, v, decay, kv_in=kv0, return_state=True)
+    refs = orc.bwd_recurrent(q, k, v, g, decay)
+    with force_plan(dv, segs):
+        o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), kv_in=kv0.to(dev()), return_state=True)
+        outs = ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay))
+    check("O", o, ref, 1e-2)
+    check("kv", kv, kv_ref, 1e-2)
+    for n, x, r in zip(("dQ", "dK", "dV"), outs, refs):
+        check(n, x, r, 1e-2)
+
+
 # --------------------------------------------------------------------------- the paper's tiling as a kernel
 
 
