@@ -33,6 +33,11 @@ static __device__ __attribute__((aligned(256))) const unsigned char kZeros[256] 
 __device__ __forceinline__ void dma16(unsigned lds, const char* g) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds), "v"(g) : "memory", "m0");
 }
+// The same load with a wave-uniform 64-bit base (scalar registers) and a 32-bit unsigned
+// per-lane byte offset: no per-lane 64-bit address arithmetic at the point of issue.
+__device__ __forceinline__ void dma16s(unsigned lds, const char* base, unsigned off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds), "v"(off), "s"(base) : "memory", "m0");
+}
 template <int N>
 __device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory"); }
 
@@ -87,10 +92,13 @@ struct TileDma {
     static_assert(Swz<COLS>::NI % 4 == 0, "every state wave issues the same number of loads");
     static_assert(REAL % 8 == 0 && REAL <= COLS, "whole 16-byte chunks");
     static constexpr int PER_WAVE = Swz<COLS>::NI / 4;
+    static constexpr bool FAST = REAL == COLS;   // complete blocks can take the scalar-base form
     long long src[PER_WAVE];
     int row[PER_WAVE];
+    unsigned low[PER_WAVE];   // the same position as a byte offset from the block's lowest-address row
     __device__ __forceinline__ void init(int u, int lane, long long row_stride) {
         using S = Swz<COLS>;
+        const long long pitch = row_stride < 0 ? -row_stride : row_stride;
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int slot = 64 * (u + 4 * i) + lane;
@@ -98,7 +106,16 @@ struct TileDma {
             const int c = (slot % S::CPR) ^ S::key(r);
             row[i] = (REAL < COLS && c * 8 >= REAL) ? kBlock : r;
             src[i] = (long long)r * row_stride + c * 16;
+            low[i] = (unsigned)((row_stride < 0 ? kBlock - 1 - r : r) * pitch + c * 16);
         }
+    }
+    // A complete block (all kBlock rows valid, all columns real): `lowest` is the wave-uniform
+    // global address of the block's lowest-address row (its row 0, or its last row on a
+    // reversed token axis), plus the slice's column offset.
+    __device__ __forceinline__ void issue_full(const char* lowest, unsigned lds, int u) const {
+        static_assert(FAST, "tiles with zero-filled columns go through issue()");
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i) dma16s(lds + 1024u * (unsigned)(u + 4 * i), lowest, low[i]);
     }
     // base: global address of the block's row 0 (plus the slice's column offset);
     // lds: LDS byte address of the tile; rows >= valid come from the zero buffer
@@ -107,6 +124,57 @@ struct TileDma {
         for (int i = 0; i < PER_WAVE; ++i) {
             const char* g = (row[i] < valid) ? base + src[i] : (const char*)kZeros;
             dma16(lds + 1024u * (unsigned)(u + 4 * i), g);
+        }
+    }
+};
+
+// The same fetch in scalar-base form for any subset of waves.  The per-lane part of a load's
+// address repeats every 16 rows (the swizzle key does), so a tile needs only NV = CPR / 4
+// per-lane offsets; the 16-row group and the block sit in the wave-uniform base address.  Load
+// j = m NV + v (m: 16-row group, v < NV) fills LDS slots 64j .. 64j+63 as above; of NW issuing
+// waves, wave W_ takes the loads with j % NW == W_ (NI / NW loads per tile and wave).
+template <int COLS>
+struct TileDmaU {
+    using S = Swz<COLS>;
+    static constexpr int NV = S::CPR / 4;
+    static constexpr int NI = S::NI;
+    static_assert(NV >= 1 && NI == 4 * NV, "four 16-row groups per tile");
+    unsigned off[NV];     // (row within its 16-row group, from the group's lowest-address row) * pitch + chunk * 16
+    __device__ __forceinline__ void init(int lane, long long pitch, int rev) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int slot = 64 * v + lane;
+            const int rr = slot / S::CPR;                       // 0..15
+            const int c = (slot % S::CPR) ^ S::key(rr);
+            off[v] = (unsigned)((rev ? 15 - rr : rr) * pitch + c * 16);
+        }
+    }
+    // row0: wave-uniform global address of the block's row 0 (plus the slice's column offset);
+    // rows follow at +pitch, or at -pitch on a reversed token axis.  All kBlock rows are read.
+    template <int NW, int W_>
+    __device__ __forceinline__ void issue_full(const char* row0, long long pitch, int rev, unsigned lds) const {
+        static_assert(NI % NW == 0, "every issuing wave takes the same number of loads");
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const char* grp = row0 + (rev ? -(long long)(16 * m + 15) * pitch : (long long)(16 * m) * pitch);
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+                if ((m * NV + v) % NW == W_) dma16s(lds + 1024u * (unsigned)(m * NV + v), grp, off[v]);
+        }
+    }
+    // The same loads for a short last block: rows >= valid come from the zero buffer.
+    template <int NW, int W_>
+    __device__ __forceinline__ void issue_partial(const char* row0, long long pitch, int rev, unsigned lds, int valid,
+                                                  int lane) const {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const char* grp = row0 + (rev ? -(long long)(16 * m + 15) * pitch : (long long)(16 * m) * pitch);
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+                if ((m * NV + v) % NW == W_) {
+                    const int r = 16 * m + (64 * v + lane) / S::CPR;
+                    dma16(lds + 1024u * (unsigned)(m * NV + v), r < valid ? grp + off[v] : (const char*)kZeros);
+                }
         }
     }
 };

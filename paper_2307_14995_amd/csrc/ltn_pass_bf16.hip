@@ -29,13 +29,18 @@
 //   * state waves 4..7: wave u owns state rows [u*D/4, (u+1)*D/4) x DV in fp32
 //     accumulators for the whole sequence, applies S <- lambda^len S + (decayed B)^T C
 //     and publishes a bf16 copy [dv][dk] to LDS (double buffered), which the output waves
-//     read as the A operand of S^T A^T.  These waves also drive the tile pipeline:
+//     read as the A operand of S^T A^T.
 //   * all three operand tiles go global -> LDS directly (global_load_lds_dwordx4: no
-//     registers, every wave-wide load covers 1 KB of consecutive addresses) into a ring of
-//     2-4 stages (as many as fit beside the two state copies), so one to three blocks of
-//     loads are always in flight per workgroup; one barrier per block.  Output waves read
-//     their A fragments from LDS and issue no global loads at all, so their stores never
-//     stand in front of a load they wait for.  LDS rows are unpadded; the 16-byte chunk
+//     registers, every wave-wide load covers 1 KB of consecutive addresses; wave-uniform base
+//     in scalar registers plus a 32-bit lane offset) into a ring of 2-4 stages (as many as fit
+//     beside the two state copies), so one to three blocks of loads are always in flight per
+//     workgroup; one barrier per block.  The loads are issued by output waves 0 and 1: the
+//     state waves' chain (update, publish) is the longest between two barriers, a burst of
+//     40-48 wave-wide loads holds its issuer for 600-1600 cycles, and those two waves have the
+//     fewest causal score tiles.  They wait for a block with an exact vmcnt that counts their
+//     own stores in between (VMEM operations of a wave retire in issue order), never for the
+//     stores themselves.  The gated pass, heads of 96 features and the register-fed layout
+//     keep the loads in the state waves.  LDS rows are unpadded; the 16-byte chunk
 //     index is XOR-swizzled with the row so that row reads, transpose reads
 //     (ds_read_b64_tr_b16, for operands needed "down the token axis") and the state-copy
 //     writes spread over the banks.  Rows past the end of a short last block are fetched
@@ -76,7 +81,22 @@ struct Cfg {
     static constexpr int P_SB = PST * PSTAGE;
     static constexpr int PASS_TOTAL = P_SB + 2 * SBYTES;
     static_assert(PASS_TOTAL <= 163840, "LDS per workgroup");
+    // Plain pass: the tile loads are issued by output waves 0 .. FW-1 -- the waves with the
+    // fewest causal score tiles, which reach the block's barrier long before the state waves do;
+    // the texture addresser takes 16 cycles per wave-wide 1 KB load, and whoever issues a
+    // block's 40-48 loads in a burst stands still for that long.
+    static constexpr int FW = 2;
 };
+
+// MODE of a workgroup: the plain pass, the pass with the gated epilogue, or the
+// state-only sweep of the sequence-parallel form (no outputs: only the segment's end state).
+enum { kPlain = 0, kGated = 1, kStateOnly = 2 };
+
+// Who issues the tile loads: output waves in the plain pass (unless they feed themselves the
+// A operand through registers) and in the state-only sweep, where they have nothing else to
+// do, over tensors whose rows fill the tiles; the state waves otherwise.
+template <int D, int DV, int MODE, int DR>
+constexpr bool kOutFetch = DR == D && ((MODE == kPlain && !Cfg<D, DV>::AREG) || MODE == kStateOnly);
 
 // Register prefetch loads of the AREG output waves are issued from inline assembly and
 // waited for with explicit vmcnt counts: left to the compiler, loads that rotate through
@@ -396,21 +416,94 @@ struct Chain {            // what every wave of the workgroup knows about its pr
 
 // =============================================================== pass body
 
-// MODE of a workgroup: the plain pass, the pass with the gated epilogue, or the
-// state-only sweep of the sequence-parallel form (no outputs: only the segment's end state).
-enum { kPlain = 0, kGated = 1, kStateOnly = 2 };
-
-template <int D, int DV, int DC, int W, int MODE>
-__device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, int lane) {
+template <int D, int DV, int DC, int W, int MODE, int DR>
+__device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, unsigned lds0, int lane) {
     using C = Cfg<D, DV>;
     constexpr bool GATED = MODE == kGated;
-    if constexpr (MODE == kStateOnly) {    // nothing to produce: keep the barriers company
-        __syncthreads();
-        for (int blk = 0; blk + 1 < ch.T; ++blk) __syncthreads();
-        return;
-    }
+    constexpr bool SO = MODE == kStateOnly;          // nothing to produce: tile loads and barriers only
     constexpr int KS = C::KS;
     constexpr long long ROW = DC * 2;      // the output's row (and U's, Y's)
+    const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
+
+    // Tile pipeline (issuing waves only): block b lives in ring stage b % PST; the loads of
+    // block b + PST - 1 go out right after the barrier that frees their stage.  This wave's
+    // VMEM operations retire in issue order, loads and stores alike, so "block b + 1 has
+    // landed" is a vmcnt of exactly the operations issued after its loads: the NT/2 stores of
+    // every block since and the loads of the PST - 2 blocks behind it.
+    constexpr bool ISSUER = kOutFetch<D, DV, MODE, DR> && W < C::FW;
+    constexpr bool NOA = SO || C::AREG;              // the A tile is not fetched into LDS
+    constexpr int L = ISSUER ? ((NOA ? 1 : 2) * TileDmaU<D>::NI + TileDmaU<DV>::NI) / C::FW : 0;   // loads per block, this wave
+    constexpr int S = SO ? 0 : C::NT / 2;                                                           // stores per block, this wave
+    static_assert((C::PST - 2) * L + (C::PST - 1) * S <= 63, "vmcnt field");
+    constexpr long long AROW = D * 2;
+    TileDmaU<D> dab;                                  // A and B tiles: same shape, same offsets
+    TileDmaU<DV> dcc;
+    const char* pa0 = nullptr;
+    const char* pb0 = nullptr;
+    const char* pc0 = nullptr;
+    if constexpr (ISSUER) {
+        dab.init(lane, AROW, ch.rev);
+        dcc.init(lane, ROW, ch.rev);
+        pa0 = ch.a + (ch.rev ? (ch.N - 1) * AROW : 0);
+        pb0 = ch.b + (ch.rev ? (ch.N - 1) * AROW : 0);
+        pc0 = ch.c + (ch.rev ? (ch.N - 1) * ROW : 0);
+    }
+    const long long astep = ch.rev ? -(long long)kBlock * AROW : (long long)kBlock * AROW;
+    auto fetch = [&](int b, int stage) {
+        if constexpr (ISSUER) {
+            b = b < ch.T ? b : ch.T - 1;   // past the end: re-read the last block into a free stage
+            const int valid = (b + 1 == ch.T) ? ch.last_valid : kBlock;
+            const unsigned lds = lds0 + (unsigned)(stage * C::PSTAGE);
+            const char* pa = pa0 + (long long)b * astep;
+            const char* pb = pb0 + (long long)b * astep;
+            const char* pc = pc0 + (long long)b * step;
+            if (valid == kBlock) {
+                if constexpr (!NOA) dab.template issue_full<C::FW, W>(pa, AROW, ch.rev, lds);
+                dab.template issue_full<C::FW, W>(pb, AROW, ch.rev, lds + C::BOFF);
+                dcc.template issue_full<C::FW, W>(pc, ROW, ch.rev, lds + C::COFF);
+            } else {
+                if constexpr (!NOA) dab.template issue_partial<C::FW, W>(pa, AROW, ch.rev, lds, valid, lane);
+                dab.template issue_partial<C::FW, W>(pb, AROW, ch.rev, lds + C::BOFF, valid, lane);
+                dcc.template issue_partial<C::FW, W>(pc, ROW, ch.rev, lds + C::COFF, valid, lane);
+            }
+        }
+    };
+    auto wait_next = [&](int blk) {        // block blk + 1 has landed (this wave's part)
+        if constexpr (ISSUER) {
+            if constexpr (C::PST == 2) {
+                wait_dma<S>();
+            } else if constexpr (C::PST == 3) {
+                if (blk == 0) wait_dma<L + S>(); else wait_dma<L + 2 * S>();
+            } else {
+                if (blk == 0) wait_dma<2 * L + S>();
+                else if (blk == 1) wait_dma<2 * L + 2 * S>();
+                else wait_dma<2 * L + 3 * S>();
+            }
+        }
+    };
+    if constexpr (ISSUER) {                // blocks 0 .. PST-2 in flight, block 0 landed
+#pragma unroll
+        for (int b = 0; b < C::PST - 1; ++b) fetch(b, b);
+        wait_dma<(C::PST - 2) * L>();
+    }
+
+    if constexpr (SO) {
+        __syncthreads();
+        int stage = 0;
+        for (int blk = 0; blk + 1 < ch.T; ++blk) {
+            if constexpr (ISSUER) {
+                int fs = stage + C::PST - 1;
+                if (fs >= C::PST) fs -= C::PST;
+                fetch(blk + C::PST - 1, fs);
+                wait_next(blk);
+            }
+            __syncthreads();
+            stage = (stage + 1 == C::PST) ? 0 : stage + 1;
+        }
+        if constexpr (ISSUER) wait_dma<0>();
+        return;
+    }
+
     const int g = lane >> 4, i16 = lane & 15;
     OutConsts<W> k;
     k.init(ch.lam, g, i16);
@@ -419,7 +512,6 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, in
 
     // this lane's token row (16W + i16) of block 0
     const long long r0 = ch.rev ? (ch.N - 1 - (16 * W + i16)) : (long long)(16 * W + i16);
-    const long long step = ch.rev ? -(long long)kBlock * ROW : (long long)kBlock * ROW;
     const long long lane_off = r0 * ROW + (8 * g) * 2;
     char* po = ch.out ? ch.out + lane_off : nullptr;
     const char* pu = GATED ? ch.gate + lane_off : nullptr;
@@ -430,18 +522,28 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, in
     for (int blk = 0; blk < ch.T; ++blk) {
         const bool more = blk + 1 < ch.T;
         const bool row_ok = (16 * W + i16) < ((blk + 1 == ch.T) ? ch.last_valid : kBlock);
+        if constexpr (ISSUER) {
+            int fs = stage + C::PST - 1;   // stage of block blk + PST - 1 (free since the last barrier)
+            if (fs >= C::PST) fs -= C::PST;
+            fetch(blk + C::PST - 1, fs);
+        }
         const char* st = smem + stage * C::PSTAGE;
         Frag Af[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) Af[ks].u = *(const u32x4*)(st + (16 * W) * C::F::RB + ro.row[ks]);
         const long long bo = (long long)blk * step;
+        // with more blocks to come every lane stores (the count above relies on it)
         output_pass<D, DV, W, DV, GATED>(st + C::BOFF, st + C::COFF,
                                          smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
                                          po ? po + bo : nullptr, more || row_ok,
                                          GATED ? pu + bo : nullptr, GATED ? py + bo : nullptr, ch.eps);
-        if (more) __syncthreads();
+        if (more) {
+            wait_next(blk);
+            __syncthreads();
+        }
         stage = (stage + 1 == C::PST) ? 0 : stage + 1;
     }
+    if constexpr (ISSUER) wait_dma<0>();   // nothing may land in LDS after this workgroup is gone
 }
 
 // Output wave of the AREG layout: as pass_output_wave, but the A fragments of its 16 rows
@@ -522,6 +624,7 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
     constexpr int MT = C::MT, NT = C::NT;
     constexpr bool SO = MODE == kStateOnly;          // no published state copies
     constexpr bool NOA = SO || C::AREG;              // the A tile is not this wave's business
+    constexpr bool OUTF = kOutFetch<D, DV, MODE, DR>;   // output waves run the tile pipeline
     constexpr long long ROW = DR * 2, CROW = DC * 2;
     const int g = lane >> 4, i16 = lane & 15;
     const int dk0 = u * (D / 4);
@@ -560,10 +663,22 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
     constexpr int kLoads = (NOA ? 1 : 2) * TileDma<D>::PER_WAVE + TileDma<DV>::PER_WAVE;   // per block, per wave
     static_assert((C::PST - 2) * kLoads <= 63, "vmcnt field");
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
+    // complete blocks: scalar base (the block's lowest-address row) + per-lane 32-bit offsets
+    const long long lowadj = ch.rev ? -(long long)(kBlock - 1) * ROW : 0;
+    const long long clowadj = ch.rev ? -(long long)(kBlock - 1) * CROW : 0;
     auto fetch = [&](int b, int stage) {
+        if constexpr (OUTF) return;
         b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block into a free stage
         const int valid = valid_of(b);
         const unsigned lds = lds0 + (unsigned)(stage * C::PSTAGE);
+        if (TileDma<D, DR>::FAST && valid == kBlock) {
+            if constexpr (TileDma<D, DR>::FAST) {
+                if constexpr (!NOA) db.issue_full(pa0 + (long long)b * step + lowadj, lds, u);
+                db.issue_full(pb0 + (long long)b * step + lowadj, lds + C::BOFF, u);
+                dc.issue_full(pc0 + (long long)b * cstep + clowadj, lds + C::COFF, u);
+            }
+            return;
+        }
         if constexpr (!NOA) db.issue(pa0 + (long long)b * step, lds, u, valid);
         db.issue(pb0 + (long long)b * step, lds + C::BOFF, u, valid);
         dc.issue(pc0 + (long long)b * cstep, lds + C::COFF, u, valid);
@@ -573,7 +688,7 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
 #pragma unroll
     for (int b = 0; b < C::PST - 1; ++b) fetch(b, b);
     if constexpr (!SO) publish_state<D, DV, DV>(st, smem + C::P_SB, k);
-    wait_dma<(C::PST - 2) * kLoads>();
+    if constexpr (!OUTF) wait_dma<(C::PST - 2) * kLoads>();
     __syncthreads();
 
     int stage = 0;                                   // stage of block blk
@@ -590,12 +705,12 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
         state_update<D, DV, DV>(st, tb + C::BOFF, tb + C::COFF, k);
         if (more) {
             if constexpr (!SO) publish_state<D, DV, DV>(st, smem + C::P_SB + ((blk + 1) & 1) * C::SBYTES, k);
-            wait_dma<(C::PST - 2) * kLoads>();       // block blk+1 has landed (this wave's part)
+            if constexpr (!OUTF) wait_dma<(C::PST - 2) * kLoads>();   // block blk+1 has landed (this wave's part)
             __syncthreads();
         }
         stage = (stage + 1 == C::PST) ? 0 : stage + 1;
     }
-    wait_dma<0>();                                   // nothing may land in LDS after this workgroup is gone
+    if constexpr (!OUTF) wait_dma<0>();              // nothing may land in LDS after this workgroup is gone
 
     if (ch.state_out) {
 #pragma unroll
@@ -673,8 +788,11 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
         static_assert(MODE != kGated && DR == D, "the register-fed layout has no gated epilogue");
         switch (wave) {
             case 0: case 1: case 2: case 3:
-                if constexpr (MODE == kStateOnly) {
-                    pass_output_wave<D, DV, DC, 0, MODE>(ch, smem, lane);      // only keeps the barriers company
+                if constexpr (MODE == kStateOnly) {    // tile loads (waves 0 .. FW-1) and barriers only
+                    if (wave == 0) pass_output_wave<D, DV, DC, 0, MODE, DR>(ch, smem, lds0, lane);
+                    else if (wave == 1) pass_output_wave<D, DV, DC, 1, MODE, DR>(ch, smem, lds0, lane);
+                    else if (wave == 2) pass_output_wave<D, DV, DC, 2, MODE, DR>(ch, smem, lds0, lane);
+                    else pass_output_wave<D, DV, DC, 3, MODE, DR>(ch, smem, lds0, lane);
                 } else {
                     if (wave == 0) areg_output_wave<D, DV, DC, 0>(ch, smem, lane);
                     else if (wave == 1) areg_output_wave<D, DV, DC, 1>(ch, smem, lane);
@@ -686,10 +804,10 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
         }
     } else {
         switch (wave) {
-            case 0: pass_output_wave<D, DV, DC, 0, MODE>(ch, smem, lane); break;
-            case 1: pass_output_wave<D, DV, DC, 1, MODE>(ch, smem, lane); break;
-            case 2: pass_output_wave<D, DV, DC, 2, MODE>(ch, smem, lane); break;
-            case 3: pass_output_wave<D, DV, DC, 3, MODE>(ch, smem, lane); break;
+            case 0: pass_output_wave<D, DV, DC, 0, MODE, DR>(ch, smem, lds0, lane); break;
+            case 1: pass_output_wave<D, DV, DC, 1, MODE, DR>(ch, smem, lds0, lane); break;
+            case 2: pass_output_wave<D, DV, DC, 2, MODE, DR>(ch, smem, lds0, lane); break;
+            case 3: pass_output_wave<D, DV, DC, 3, MODE, DR>(ch, smem, lds0, lane); break;
             default: pass_state_wave<D, DV, DC, MODE, DR>(ch, smem, lds0, lane, wave - 4); break;
         }
     }
