@@ -355,8 +355,9 @@ ltn_status ltn_attn_set_debug_plan(int dv, int segs);
  * when few chains meet a long sequence: then every chain is cut into segments that run
  * in parallel (the recurrence of Sec. 3.3 is linear in the state, so the segments' end
  * states can be computed from zero and combined by a scan), and the workspace holds one
- * fp32 D x D state per (pass, chain, segment).  Contents are scratch: undefined before
- * and after the call. */
+ * fp32 D x D state per (pass, chain, segment).  For ltn_attn_fwd_gated the figure covers
+ * both of its forms (fused, and plain forward followed by the gate kernel).  Contents are
+ * scratch: undefined before and after the call. */
 size_t ltn_attn_workspace_bytes(int Bt, int H, long long N, int D, int block,
                                 ltn_dtype dtype, int call);
 

@@ -94,11 +94,13 @@ ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype 
 // compute units idle and makes every workgroup re-read A and B; cutting each chain into
 // segments instead gives full-width workgroups to all compute units at the price of one
 // extra read of B and C (the state-only sweep) and two more launches.  Measured on MI355X
-// (8 and 32 chains, N = 4096 .. 16384, forward and backward): pays when a chain can be cut at
-// least 8 ways into segments of at least 1024 tokens without exceeding one round of compute
-// units, and never otherwise.  bf16 kernels only.  Heads of 256 features always need four
-// 64-column workgroups per chain and segment; there the form pays from 4 segments on (measured:
-// Bt = 1, N = 8192 .. 32768, 4 .. 32 heads).
+// (2 .. 64 chains, N = 2048 .. 65536, forward and backward, every segment count): pays when a
+// chain can be cut at least 8 ways into segments of at least 512 tokens without exceeding one
+// round of compute units, and from 5 ways on when the segments are at least 2048 tokens long
+// (36 .. 48 passes of long chains, e.g. the backward of 12 .. 16 chains); never otherwise.
+// bf16 kernels only.  Heads of 256 features always need four 64-column workgroups per chain
+// and segment, heads of 96 three of 32; there, and for the gated pass, the form pays from 4
+// segments of at least 1024 tokens on (measured: Bt = 1, N = 8192 .. 32768, 4 .. 32 heads).
 // ltn_attn_set_debug_plan (test only) forces a segment count.
 struct SegPlan { int segs; long long seg_len; };
 constexpr long long kMinSegsFullWidth = 4;   // measured: 2 segments lose to one workgroup per chain
@@ -109,9 +111,15 @@ SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtyp
     // D = 256: every (chain, segment) still needs four 64-column workgroups; D = 96: three of 32
     const long long per_seg = (D == 256) ? 4 : (D == 96 ? 3 : 1);
     long long want = 256 / (per_seg * chain_passes);
-    if (want > N / 1024) want = N / 1024;
     // a pass that must keep full-width slices has no column split to fall back on
-    if (want < ((full_width || per_seg > 1) ? kMinSegsFullWidth : 8)) want = 1;
+    const bool wide_only = full_width || per_seg > 1;
+    const long long min_len = wide_only ? 1024 : 512;
+    if (want > N / min_len) want = N / min_len;
+    if (wide_only) {
+        if (want < kMinSegsFullWidth) want = 1;
+    } else if (want < 8 && !(want >= 5 && N / want >= 2048)) {
+        want = 1;
+    }
     if (const int v = g_debug_segs.load(std::memory_order_relaxed)) want = v;
     if (want <= 1) return plan;
     long long len = (N + want - 1) / want;
@@ -231,9 +239,17 @@ size_t ltn_attn_workspace_bytes(int Bt, int H, long long N, int D, int block, lt
     if (Bt <= 0 || H <= 0 || N <= 0 || (D != 64 && D != 96 && D != 128 && D != 256) || call < 0 || call > 2) return 0;
     const long long chains = (long long)Bt * H;
     const int count = (call == 1) ? 3 : 1;
+    const size_t state = (size_t)D * D * sizeof(float);                                   // one fp32 state per segment
     const SegPlan plan = pick_segments(chains * count, N, D, dtype, call == 2);
-    if (plan.segs == 1) return 0;
-    return (size_t)count * (size_t)chains * (size_t)plan.segs * D * D * sizeof(float);   // one fp32 state per segment
+    size_t need = plan.segs == 1 ? 0 : (size_t)count * (size_t)chains * (size_t)plan.segs * state;
+    if (call == 2) {
+        // the gated forward may run as the plain forward followed by the gate kernel (when the
+        // attention output is stored anyway): room for whichever plan needs more
+        const SegPlan plain = pick_segments(chains, N, D, dtype, false);
+        const size_t alt = plain.segs == 1 ? 0 : (size_t)chains * (size_t)plain.segs * state;
+        if (alt > need) need = alt;
+    }
+    return need;
 }
 
 ltn_status ltn_attn_check_decay(const float* decay_host, int H) {

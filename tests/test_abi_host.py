@@ -313,7 +313,7 @@ def test_debug_plan_and_plan_query(lib):
     assert lib.ltn_attn_set_debug_plan(0, 5000) == E_SHAPE
     assert ltn.ltn_attn_query_plan(4, 32, 8192, 128, torch.bfloat16, 0) == (64, 1)    # headline forward: two slices
     assert ltn.ltn_attn_query_plan(4, 32, 8192, 128, torch.bfloat16, 1) == (128, 1)   # headline backward: full width
-    assert ltn.ltn_attn_query_plan(1, 2, 8192, 128, torch.bfloat16, 0) == (32, 8)       # 16 chain segments, four slices each
+    assert ltn.ltn_attn_query_plan(1, 2, 8192, 128, torch.bfloat16, 0) == (32, 16)      # 32 chain segments of 512 tokens, four slices each
     try:
         ltn.ltn_attn_set_debug_plan(32, 3)
         assert ltn.ltn_attn_query_plan(4, 32, 8192, 128, torch.bfloat16, 0) == (32, 3)
@@ -349,14 +349,25 @@ def test_probe_argument_errors(lib):
 def test_workspace_query(lib):
     import torch
     D = 128
-    # few long chains: one fp32 state per (pass, chain, segment); 8 segments of 1024 tokens here
-    assert ltn.ltn_attn_workspace_bytes(1, 2, 8192, D, 0, torch.bfloat16, 0) == 1 * 2 * 8 * D * D * 4
-    assert ltn.ltn_attn_workspace_bytes(1, 2, 8192, D, 0, torch.bfloat16, 1) == 3 * 2 * 8 * D * D * 4
+    # few long chains: one fp32 state per (pass, chain, segment); 16 segments of 512 tokens here
+    assert ltn.ltn_attn_workspace_bytes(1, 2, 8192, D, 0, torch.bfloat16, 0) == 1 * 2 * 16 * D * D * 4
+    assert ltn.ltn_attn_workspace_bytes(1, 2, 8192, D, 0, torch.bfloat16, 1) == 3 * 2 * 16 * D * D * 4
     assert ltn.ltn_attn_workspace_bytes(1, 2, 8192, D, 0, torch.float32, 0) == 0     # bf16 kernels only
-    assert ltn.ltn_attn_workspace_bytes(1, 32, 4096, D, 0, torch.bfloat16, 0) == 0   # segments would be too short
+    assert ltn.ltn_attn_workspace_bytes(1, 32, 4096, D, 0, torch.bfloat16, 0) == 32 * 8 * D * D * 4   # 8 segments of 512 tokens
+    assert ltn.ltn_attn_workspace_bytes(1, 32, 2048, D, 0, torch.bfloat16, 0) == 0   # segments would be too short
+    assert ltn.ltn_attn_workspace_bytes(1, 64, 16384, D, 0, torch.bfloat16, 0) == 0  # 4 segments at most: not worth it
+    # 5 .. 7 segments only when they are long: the backward of 16 chains (48 passes)
+    assert ltn.ltn_attn_workspace_bytes(1, 16, 16384, D, 0, torch.bfloat16, 1) == 3 * 16 * 5 * D * D * 4
+    assert ltn.ltn_attn_workspace_bytes(1, 16, 8192, D, 0, torch.bfloat16, 1) == 0
     assert ltn.ltn_attn_workspace_bytes(0, 2, 8192, D, 0, torch.bfloat16, 0) == 0
     # the gated forward keeps full-width slices, so it cuts chains sooner (from 4 segments on)
-    assert ltn.ltn_attn_workspace_bytes(1, 32, 4096, D, 0, torch.bfloat16, 2) == 32 * 4 * D * D * 4
+    # (4 segments; its other form, plain forward + gate kernel, takes the plain forward's 8: room for both)
+    assert ltn.ltn_attn_query_plan(1, 32, 4096, D, torch.bfloat16, 2) == (128, 4)
+    assert ltn.ltn_attn_workspace_bytes(1, 32, 4096, D, 0, torch.bfloat16, 2) == 32 * 8 * D * D * 4
+    for (Bt, H, N) in [(1, 2, 2048), (1, 4, 4096), (1, 8, 8192), (2, 8, 16384), (1, 32, 65536), (1, 48, 16384), (4, 32, 8192)]:
+        for d in (64, 96, 128, 256):
+            assert ltn.ltn_attn_workspace_bytes(Bt, H, N, d, 0, torch.bfloat16, 2) >= \
+                ltn.ltn_attn_workspace_bytes(Bt, H, N, d, 0, torch.bfloat16, 0)
     assert ltn.ltn_attn_workspace_bytes(4, 32, 8192, D, 0, torch.bfloat16, 2) == 0
     assert ltn.ltn_attn_workspace_bytes(1, 2, 8192, D, 0, torch.bfloat16, 3) == 0     # no such call
 

@@ -459,7 +459,7 @@ def test_segmented_call_needs_its_workspace():
     lib = ltn.load_library()
     import ctypes
     need = ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 0)
-    assert need == 8 * Bt * H * D * D * 4               # 8192 tokens: eight segments of 1024
+    assert need == 16 * Bt * H * D * D * 4              # 8192 tokens: sixteen segments of 512
     p = lambda t: ctypes.c_void_p(t.data_ptr())
     rc = lib.ltn_attn_fwd(p(q), p(k), p(v), p(o), p(dd), None, None, Bt, H, N, D, 0, 1, None, 0, None)
     assert rc == 2, ltn.ltn_status_str(rc)               # LTN_ERR_SHAPE: workspace too small
