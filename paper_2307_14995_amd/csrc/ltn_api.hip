@@ -99,8 +99,9 @@ ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype 
 // round of compute units, and from 5 ways on when the segments are at least 2048 tokens long
 // (36 .. 48 passes of long chains, e.g. the backward of 12 .. 16 chains); never otherwise.
 // bf16 kernels only.  Heads of 256 features always need four 64-column workgroups per chain
-// and segment, heads of 96 three of 32; there, and for the gated pass, the form pays from 4
-// segments of at least 1024 tokens on (measured: Bt = 1, N = 8192 .. 32768, 4 .. 32 heads).
+// and segment, heads of 96 three of 32; there the form pays from 3 segments of at least 512
+// tokens on (measured: 2 .. 32 chains, N = 2048 .. 32768, forward and backward), for the gated
+// pass from 4 segments of at least 1024 tokens on (32 and 64 chains, N = 8192, 16384).
 // ltn_attn_set_debug_plan (test only) forces a segment count.
 struct SegPlan { int segs; long long seg_len; };
 constexpr long long kMinSegsFullWidth = 4;   // measured: 2 segments lose to one workgroup per chain
@@ -112,11 +113,12 @@ SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtyp
     const long long per_seg = (D == 256) ? 4 : (D == 96 ? 3 : 1);
     long long want = 256 / (per_seg * chain_passes);
     // a pass that must keep full-width slices has no column split to fall back on
-    const bool wide_only = full_width || per_seg > 1;
-    const long long min_len = wide_only ? 1024 : 512;
+    const long long min_len = full_width ? 1024 : 512;
     if (want > N / min_len) want = N / min_len;
-    if (wide_only) {
+    if (full_width) {
         if (want < kMinSegsFullWidth) want = 1;
+    } else if (per_seg > 1) {
+        if (want < 3) want = 1;
     } else if (want < 8 && !(want >= 5 && N / want >= 2048)) {
         want = 1;
     }
@@ -556,7 +558,7 @@ static SegPlan pick_segments_dkdv(long long chain_passes, long long N, int DA, i
     if (dtype != LTN_BF16 || chain_passes <= 0 || N <= 64) return plan;
     const long long per_seg = DC / dkdv_hi(DA, DC);
     long long want = 256 / (per_seg * chain_passes);
-    if (want > N / 1024) want = N / 1024;
+    if (want > N / 512) want = N / 512;       // segments of at least 512 tokens (measured: 2 .. 32 chains, N = 2048 .. 16384)
     if (want < kMinSegsFullWidth) want = 1;
     if (const int v = g_debug_segs.load(std::memory_order_relaxed)) want = v;
     if (want <= 1) return plan;

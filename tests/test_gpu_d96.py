@@ -78,9 +78,9 @@ def test_d96_decode_continues_a_prefix(dtype):
 
 
 def test_d96_few_long_chains_are_cut_into_segments_by_default():
-    Bt, H, N = 1, 4, 4096 + 33                  # 4 chains x 3 slices: cut 4 ways by the library's own rule
-    assert ltn.ltn_attn_query_plan(Bt, H, N, D, torch.bfloat16, 0) == (32, 4)
-    assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 0) == 4 * Bt * H * D * D * 4
+    Bt, H, N = 1, 4, 4096 + 33                  # 4 chains x 3 slices: cut 8 ways by the library's own rule
+    assert ltn.ltn_attn_query_plan(Bt, H, N, D, torch.bfloat16, 0) == (32, 8)
+    assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 0) == 8 * Bt * H * D * D * 4
     q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 880)
     kv0 = torch.randn(Bt, H, D, D, generator=torch.Generator().manual_seed(881)) * 0.1
     decay = synth.decay_bench_rule(H)

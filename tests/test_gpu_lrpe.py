@@ -186,9 +186,9 @@ def test_dkdv_seeded_shape_sweep(case):
 
 
 def test_dkdv_few_long_chains_are_cut_into_segments_by_default():
-    Bt, H, N, Dk, Dv = 1, 4, 4096 + 70, 256, 128         # 4 chains x 2 slices: cut 4 ways by the library's own rule
+    Bt, H, N, Dk, Dv = 1, 4, 4096 + 70, 256, 128         # 4 chains x 2 slices: cut 8 ways by the library's own rule
     dtype = torch.bfloat16
-    assert ltn.ltn_attn_workspace_bytes_dkdv(Bt, H, N, Dk, Dv, dtype, 0) == 4 * Bt * H * Dk * Dv * 4
+    assert ltn.ltn_attn_workspace_bytes_dkdv(Bt, H, N, Dk, Dv, dtype, 0) == 8 * Bt * H * Dk * Dv * 4
     q, k, v = synth.make_qkv_dkdv(Bt, H, N, Dk, Dv, dtype, 640)
     d_o = synth.make_do(Bt, H, N, Dv, dtype, 640)
     decay = synth.decay_bench_rule(H)
