@@ -23,9 +23,9 @@
 //   * State waves 4..7: wave 4 + u owns state rows [u D/4, (u+1) D/4) x DV in accumulators for
 //     the whole sequence; once per block the new state goes to LDS transposed ([dv][dk], 16-byte
 //     writes) for the next block's A_i S_i.
-//   * The next block's tiles are fetched into registers (all eight waves share the loads) while
-//     the current block is computed and written to LDS between two barriers at the end of the
-//     block.
+//   * The next block's tiles are fetched into registers by the output waves (the state waves'
+//     work is the longer one between two barriers) while the current block is computed, and
+//     written to LDS between two barriers at the end of the block.
 // Only non-negative powers of lambda are formed.
 #include "ltn_kernels.h"
 
@@ -56,9 +56,12 @@ struct FCfg {
     static_assert(D == 64 || D == 128, "head dims of this kernel");
     static_assert(NT % VG == 0 && NTW >= 1, "every wave needs a value-column tile");
     static_assert(FLOATS * 4 <= 163840, "LDS per workgroup");
-    // prefetch registers: 16-byte pieces per thread and tile (the last round of a tile may be partial)
+    // prefetch registers of the output waves (they fetch the tiles; the state waves' work is the
+    // longer one between two barriers): 16-byte pieces per thread and tile (the last round of a
+    // tile may be partial)
+    static constexpr int FT = kMThreads / 2;       // threads of waves 0..3
     static constexpr int EA = B * (D / 4), EC = B * (DV / 4);
-    static constexpr int LA = (EA + kMThreads - 1) / kMThreads, LC = (EC + kMThreads - 1) / kMThreads;
+    static constexpr int LA = (EA + FT - 1) / FT, LC = (EC + FT - 1) / FT;
 };
 
 // The whole pass as one wave runs it; STRIP (the wave's token strip in the output part) is a
@@ -124,38 +127,40 @@ __device__ __forceinline__ void pass_f32_mfma_wave(const PassBatch& pb, const in
         }
     };
 
-    // tile prefetch through registers
-    v4f ra[C::LA], rb[C::LA], rc[C::LC];
+    // tile prefetch through registers (output waves: tid < FT)
+    v4f ra[STATE ? 1 : C::LA], rb[STATE ? 1 : C::LA], rc[STATE ? 1 : C::LC];
     auto fetch = [&](long long t0) {
+        if constexpr (STATE) return;
         const long long left = N - t0;
 #pragma unroll
-        for (int i = 0; i < C::LA; ++i) {
-            const int e = tid + i * kMThreads, r = e / (D / 4), c4 = e % (D / 4);
+        for (int i = 0; i < (STATE ? 0 : C::LA); ++i) {
+            const int e = tid + i * C::FT, r = e / (D / 4), c4 = e % (D / 4);
             const bool ok = e < C::EA && r < left;
             const size_t gr = (size_t)(rev ? (N - 1 - (t0 + r)) : (t0 + r));
             ra[i] = ok ? *(const v4f*)(Ap + gr * D + 4 * c4) : v4f{0.f, 0.f, 0.f, 0.f};
             rb[i] = ok ? *(const v4f*)(Bp + gr * D + 4 * c4) : v4f{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
-        for (int i = 0; i < C::LC; ++i) {
-            const int e = tid + i * kMThreads, r = e / (DV / 4), c4 = e % (DV / 4);
+        for (int i = 0; i < (STATE ? 0 : C::LC); ++i) {
+            const int e = tid + i * C::FT, r = e / (DV / 4), c4 = e % (DV / 4);
             const bool ok = e < C::EC && r < left;
             const size_t gr = (size_t)(rev ? (N - 1 - (t0 + r)) : (t0 + r));
             rc[i] = ok ? *(const v4f*)(Cp + gr * D + 4 * c4) : v4f{0.f, 0.f, 0.f, 0.f};
         }
     };
     auto commit = [&]() {
+        if constexpr (STATE) return;
 #pragma unroll
-        for (int i = 0; i < C::LA; ++i) {
-            const int e = tid + i * kMThreads, r = e / (D / 4), c4 = e % (D / 4);
+        for (int i = 0; i < (STATE ? 0 : C::LA); ++i) {
+            const int e = tid + i * C::FT, r = e / (D / 4), c4 = e % (D / 4);
             if (e < C::EA) {
                 *(v4f*)&As[r * PA + 4 * c4] = ra[i];
                 *(v4f*)&Bs[r * PA + 4 * c4] = rb[i];
             }
         }
 #pragma unroll
-        for (int i = 0; i < C::LC; ++i) {
-            const int e = tid + i * kMThreads, r = e / (DV / 4), c4 = e % (DV / 4);
+        for (int i = 0; i < (STATE ? 0 : C::LC); ++i) {
+            const int e = tid + i * C::FT, r = e / (DV / 4), c4 = e % (DV / 4);
             if (e < C::EC) *(v4f*)&Cs[r * PC + 4 * c4] = rc[i];
         }
     };
