@@ -671,7 +671,7 @@ def test_time_is_linear_in_sequence_length():
     # measured ratios 1.92 .. 2.09 from 8192 on; the bounds leave room for a shared box's noise
     assert 1.8 < times[32768] / times[16384] < 2.2, times
     assert 1.8 < times[65536] / times[32768] < 2.2, times
-    assert 1.8 < times[16384] / times[8192] < 2.2, times
+    assert 1.8 < times[16384] / times[8192] < 2.3, times      # measured 2.0 .. 2.12: at 8192 the tensors (268 MB) about fit the memory-side cache
     assert 1.6 < times[8192] / times[4096] < 2.2, times
     xs = [math.log(n) for n in times]
     ys = [math.log(t) for t in times.values()]
