@@ -346,7 +346,7 @@ ltn_status ltn_attn_query_plan(int Bt, int H, long long N, int D, ltn_dtype dtyp
  * chain (0 = the library's choice, 1 = never cut).  It exists so that the parity tests can
  * reach every kernel variant at small sizes; it also changes what
  * ltn_attn_workspace_bytes returns.  Not thread-safe against concurrent calls into the
- * library.  LTN_ERR_SHAPE for values outside {0, 16, 32, 64, 128, 256} / [0, 4096]. */
+ * library.  LTN_ERR_SHAPE for values outside {0, 16, 32, 64, 96, 128, 256} / [0, 4096]. */
 ltn_status ltn_attn_set_debug_plan(int dv, int segs);
 
 /* Scratch bytes a call needs for these arguments: call = 0 for ltn_attn_fwd, 1 for

@@ -47,7 +47,13 @@ size_t esize_of(ltn_dtype dtype) { return dtype == LTN_BF16 ? 2 : 4; }
 // full width (fewest re-reads).  Measured on MI355X for 8..256 chains, forward and
 // backward.  ltn_attn_set_debug_plan (test only) overrides the choice.
 int pick_dv(long long chain_passes, int D, ltn_dtype dtype, int blk) {
-    if (D == 96) return 32;                // three 32-column slices (the kernels exist for those only)
+    if (D == 96) {                         // three 32-column slices, or all 96 columns in one workgroup
+        if (dtype != LTN_BF16) return 32;
+        if (const int v = g_debug_dv.load(std::memory_order_relaxed)) {
+            if (v == 32 || v == 96) return v;
+        }
+        return chain_passes * 3 <= 256 ? 32 : 96;
+    }
     // D = 256: the state copies of more than 64 columns do not fit the LDS
     const int hi = (D == 256) ? 64 : D;
     int lo = (dtype == LTN_BF16) ? 32 : (D == 256 ? 64 : D / 2);
@@ -209,7 +215,7 @@ ltn_status scratch_on_current_device(void** out) {
 extern "C" {
 
 ltn_status ltn_attn_set_debug_plan(int dv, int segs) {
-    if (dv != 0 && dv != 16 && dv != 32 && dv != 64 && dv != 128 && dv != 256) return LTN_ERR_SHAPE;
+    if (dv != 0 && dv != 16 && dv != 32 && dv != 64 && dv != 96 && dv != 128 && dv != 256) return LTN_ERR_SHAPE;
     if (segs < 0 || segs > 4096) return LTN_ERR_SHAPE;
     g_debug_dv.store(dv, std::memory_order_relaxed);
     g_debug_segs.store(segs, std::memory_order_relaxed);

@@ -66,7 +66,9 @@ struct Cfg {
     static constexpr int MT = D / 64;          // 16-row state tiles owned per state wave
     static constexpr int NT = DV / 16;         // 16-column tiles of the value slice
     using F = Swz<D>;                          // full-width tiles and state copies [DV][D]
-    using V = Swz<DV>;                         // DV-wide C tile of the pass body
+    // the C tile in LDS: DV columns, or the next power of two with the rest zero-filled (96 -> 128)
+    static constexpr int CW = DV == 96 ? 128 : DV;
+    using V = Swz<CW>;
     static constexpr int SBYTES = DV * F::RB;  // one bf16 state copy
     // pass body: ring of PST stages {A tile, B tile, C tile}, then two state copies.
     // AREG (256 query/key features, the LRPE-d expansion of Eq. 1): two 32 KB tiles per
@@ -432,12 +434,12 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, un
     // every block since and the loads of the PST - 2 blocks behind it.
     constexpr bool ISSUER = kOutFetch<D, DV, MODE, DR> && W < C::FW;
     constexpr bool NOA = SO || C::AREG;              // the A tile is not fetched into LDS
-    constexpr int L = ISSUER ? ((NOA ? 1 : 2) * TileDmaU<D>::NI + TileDmaU<DV>::NI) / C::FW : 0;   // loads per block, this wave
+    constexpr int L = ISSUER ? ((NOA ? 1 : 2) * TileDmaU<D>::NI + TileDmaU<C::CW>::NI) / C::FW : 0;   // loads per block, this wave
     constexpr int S = SO ? 0 : C::NT / 2;                                                           // stores per block, this wave
     static_assert((C::PST - 2) * L + (C::PST - 1) * S <= 63, "vmcnt field");
     constexpr long long AROW = D * 2;
     TileDmaU<D> dab;                                  // A and B tiles: same shape, same offsets
-    TileDmaU<DV> dcc;
+    TileDmaU<C::CW> dcc;
     const char* pa0 = nullptr;
     const char* pb0 = nullptr;
     const char* pc0 = nullptr;
@@ -507,7 +509,7 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, un
     const int g = lane >> 4, i16 = lane & 15;
     OutConsts<W> k;
     k.init(ch.lam, g, i16);
-    ReadOffs<D, DV, DV> ro;
+    ReadOffs<D, DV, C::CW> ro;
     ro.init(g, i16, 0);
 
     // this lane's token row (16W + i16) of block 0
@@ -533,7 +535,7 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, un
         for (int ks = 0; ks < KS; ++ks) Af[ks].u = *(const u32x4*)(st + (16 * W) * C::F::RB + ro.row[ks]);
         const long long bo = (long long)blk * step;
         // with more blocks to come every lane stores (the count above relies on it)
-        output_pass<D, DV, W, DV, GATED>(st + C::BOFF, st + C::COFF,
+        output_pass<D, DV, W, C::CW, GATED>(st + C::BOFF, st + C::COFF,
                                          smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
                                          po ? po + bo : nullptr, more || row_ok,
                                          GATED ? pu + bo : nullptr, GATED ? py + bo : nullptr, ch.eps);
@@ -557,7 +559,7 @@ __device__ __forceinline__ void areg_output_wave(const Chain& ch, char* smem, in
     const int g = lane >> 4, i16 = lane & 15;
     OutConsts<W> k;
     k.init(ch.lam, g, i16);
-    ReadOffs<D, DV, DV> ro;
+    ReadOffs<D, DV, C::CW> ro;
     ro.init(g, i16, 0);
 
     const long long r0 = ch.rev ? (ch.N - 1 - (16 * W + i16)) : (long long)(16 * W + i16);
@@ -589,7 +591,7 @@ __device__ __forceinline__ void areg_output_wave(const Chain& ch, char* smem, in
         for (int ks = 0; ks < KS; ++ks) Af[ks].u = cur_set.f[ks];
         load_a(incoming, blk + 2);
         const char* st = smem + stage * C::PSTAGE;
-        output_pass<D, DV, W, DV>(st + C::BOFF, st + C::COFF, smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
+        output_pass<D, DV, W, C::CW>(st + C::BOFF, st + C::COFF, smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
                                   po + (long long)blk * step, more || row_ok);
         if (more) __syncthreads();
     };
@@ -628,7 +630,7 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
     constexpr long long ROW = DR * 2, CROW = DC * 2;
     const int g = lane >> 4, i16 = lane & 15;
     const int dk0 = u * (D / 4);
-    StateConsts<D, DV, DV> k;
+    StateConsts<D, DV, C::CW> k;
     k.set_block_len(ch.lam, kBlock, lane);
     k.init_offsets(g, i16, dk0, 0);
 
@@ -657,10 +659,10 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
     const char* pb0 = ch.b + (ch.rev ? (ch.N - 1) * ROW : 0);
     const char* pc0 = ch.c + (ch.rev ? (ch.N - 1) * CROW : 0);
     TileDma<D, DR> db;                               // A and B tiles: same shape, same offsets
-    TileDma<DV> dc;
+    TileDma<C::CW, DV> dc;
     db.init(u, lane, rs);
     dc.init(u, lane, crs);
-    constexpr int kLoads = (NOA ? 1 : 2) * TileDma<D>::PER_WAVE + TileDma<DV>::PER_WAVE;   // per block, per wave
+    constexpr int kLoads = (NOA ? 1 : 2) * TileDma<D>::PER_WAVE + TileDma<C::CW, DV>::PER_WAVE;   // per block, per wave
     static_assert((C::PST - 2) * kLoads <= 63, "vmcnt field");
     auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
     // complete blocks: scalar base (the block's lowest-address row) + per-lane 32-bit offsets
@@ -687,7 +689,7 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
     // prologue: blocks 0 .. PST-2 in flight, block 0 landed; initial state copy published
 #pragma unroll
     for (int b = 0; b < C::PST - 1; ++b) fetch(b, b);
-    if constexpr (!SO) publish_state<D, DV, DV>(st, smem + C::P_SB, k);
+    if constexpr (!SO) publish_state<D, DV, C::CW>(st, smem + C::P_SB, k);
     if constexpr (!OUTF) wait_dma<(C::PST - 2) * kLoads>();
     __syncthreads();
 
@@ -702,9 +704,9 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
             if (ch.last_valid != kBlock) k.set_block_len(ch.lam, ch.last_valid, lane);
         }
         const char* tb = smem + stage * C::PSTAGE;
-        state_update<D, DV, DV>(st, tb + C::BOFF, tb + C::COFF, k);
+        state_update<D, DV, C::CW>(st, tb + C::BOFF, tb + C::COFF, k);
         if (more) {
-            if constexpr (!SO) publish_state<D, DV, DV>(st, smem + C::P_SB + ((blk + 1) & 1) * C::SBYTES, k);
+            if constexpr (!SO) publish_state<D, DV, C::CW>(st, smem + C::P_SB + ((blk + 1) & 1) * C::SBYTES, k);
             if constexpr (!OUTF) wait_dma<(C::PST - 2) * kLoads>();   // block blk+1 has landed (this wave's part)
             __syncthreads();
         }
@@ -855,9 +857,10 @@ hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stre
 #undef LTN_BF16_DC
         return hipErrorInvalidValue;
     }
-    if (D == 96) {                         // computed as 128 with zero-filled tile columns, 32-column slices
-        if (pb.p[0].gate || dv != 32) return hipErrorInvalidValue;
-        if (pb.state_only) return launch_t<128, 32, kStateOnly, 96, 96>(pb, stream);
+    if (D == 96) {                         // computed as 128 with zero-filled tile columns: 32-column slices or all 96
+        if (pb.p[0].gate || (dv != 32 && dv != 96)) return hipErrorInvalidValue;
+        if (pb.state_only) return dv == 32 ? launch_t<128, 32, kStateOnly, 96, 96>(pb, stream) : hipErrorInvalidValue;
+        if (dv == 96) return launch_t<128, 96, kPlain, 96, 96>(pb, stream);
         return launch_t<128, 32, kPlain, 96, 96>(pb, stream);
     }
     if (pb.p[0].gate) {                    // gated epilogue: one pass, complete output rows

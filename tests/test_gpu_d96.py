@@ -8,7 +8,7 @@ import torch
 import paper_2307_14995_amd as ltn
 from paper_2307_14995_amd import synth
 from oracle import ltn_oracle as orc
-from _helpers import check, dev, gpu, mixed_decay
+from _helpers import check, dev, force_plan, gpu, mixed_decay
 
 pytestmark = pytest.mark.gpu
 
@@ -56,6 +56,37 @@ def test_d96_backward(dtype, Bt, H, N):
     for name, got, ref in zip(("dq", "dk", "dv"), ltn.ltn_attn_bwd(qd, kd, vd, gd, dd),
                               orc.bwd_recurrent(q, k, v, d_o, decay)):
         check(name, got, ref, TOL[dtype])
+
+
+@pytest.mark.parametrize("dv", [32, 96])
+@pytest.mark.parametrize("N", [1, 63, 65, 200, 517])
+def test_d96_both_slice_widths(dv, N):
+    """Three 32-column workgroups per chain, or one with all 96 columns (forced): forward with an
+    initial state and the final state, and all three gradients."""
+    Bt, H = 2, 3
+    dtype = torch.bfloat16
+    q, k, v = synth.make_qkv(Bt, H, N, D, dtype, 870 + N)
+    d_o = synth.make_do(Bt, H, N, D, dtype, 870 + N)
+    kv0 = torch.randn(Bt, H, D, D, generator=torch.Generator().manual_seed(N)) * 0.1
+    decay = mixed_decay(H)
+    ref, ref_kv = orc.fwd_recurrent(q, k, v, decay, kv_in=kv0, return_state=True)
+    refs = orc.bwd_recurrent(q, k, v, d_o, decay)
+    with force_plan(dv=dv):
+        assert ltn.ltn_attn_query_plan(Bt, H, N, D, dtype, 0)[0] == dv
+        o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), kv_in=kv0.to(dev()), return_state=True)
+        grads = ltn.ltn_attn_bwd(*gpu(q, k, v, d_o, decay))
+    check("o", o, ref, TOL[dtype])
+    check("kv_out", kv, ref_kv, TOL[dtype])
+    for name, got, r in zip(("dq", "dk", "dv"), grads, refs):
+        check(name, got, r, TOL[dtype])
+
+
+def test_d96_many_chains_take_all_columns_in_one_workgroup():
+    # 4 x 24 chains: the backward's 288 passes are more than one round of compute units even at full
+    # width, the forward's 96 chains x 3 slices are not
+    assert ltn.ltn_attn_query_plan(4, 24, 130, D, torch.bfloat16, 0) == (96, 1)
+    assert ltn.ltn_attn_query_plan(4, 24, 130, D, torch.bfloat16, 1) == (96, 1)
+    assert ltn.ltn_attn_query_plan(2, 24, 130, D, torch.bfloat16, 0) == (32, 1)
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])

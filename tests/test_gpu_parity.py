@@ -502,7 +502,7 @@ def _random_cases_wide(n, seed):
         Bt, H = int(rng.integers(1, 3)), int(rng.integers(1, 7))
         N = int(rng.choice([rng.integers(1, 64), rng.integers(64, 400), rng.integers(400, 1200)]))
         segs = int(rng.choice([1, 1, 2, 3, 5]))
-        dv = int(rng.choice([0, 32, 64]))
+        dv = int(rng.choice([0, 32, 64] if D == 256 else [0, 32, 96, 96]))
         cases.append((i, Bt, H, N, D, dv, segs))
     return cases
 
