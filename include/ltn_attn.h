@@ -38,8 +38,8 @@
  *     lambda = 1 are exact and strong decays cannot overflow (the failure mode
  *     Sec. 3.3 describes for the factorised form of Algorithm 1).
  *   - Supported shapes: D in {64, 96, 128, 256} for ltn_attn_fwd, ltn_attn_bwd, the decode
- *     steps, the gate kernels and the gated forward (which for 96 and 256 features needs
- *     its `o` argument); D in {64, 128} for the tiled comparison kernels; N >= 0
+ *     steps, the gate kernels and the gated forward (which for 256 features, and for 96 in
+ *     fp32, needs its `o` argument); D in {64, 128} for the tiled comparison kernels; N >= 0
  *     arbitrary (a short last block
  *     is handled on chip; the paper's listings assume block | N).
  *     `block` is the intra-block tile length: 0 lets the library choose
@@ -138,9 +138,9 @@ ltn_status ltn_attn_fwd_static(const void* q, const void* k, const void* v, void
  *   y     out: device, [Bt,H,N,D] dtype
  * (With few chains and `o` requested, the library may instead run the plain forward and
  * apply the epilogue to the stored o in a second kernel; y then derives from o rounded
- * to `dtype`, so the two forms of the call agree to rounding, not bit for bit.  For D = 96
- * and D = 256 that is the only form: a complete output row of these widths does not fit
- * one workgroup's on-chip state, so `o` must be given -- LTN_ERR_UNSUPPORTED otherwise.)
+ * to `dtype`, so the two forms of the call agree to rounding, not bit for bit.  For D = 256,
+ * and for D = 96 in fp32, that is the only form: no kernel there holds a complete output row
+ * in one workgroup, so `o` must be given -- LTN_ERR_UNSUPPORTED otherwise.)
  *   eps   >= 0, added to the mean square under the root (0 is the printed formula:
  *         an all-zero output row then yields NaN, as the formula does)
  * Other arguments, layout and errors as for ltn_attn_fwd.

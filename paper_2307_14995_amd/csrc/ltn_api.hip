@@ -116,7 +116,7 @@ SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtyp
     SegPlan plan = {1, 0};
     if (dtype != LTN_BF16 || chain_passes <= 0 || N <= 64) return plan;
     // D = 256: every (chain, segment) still needs four 64-column workgroups; D = 96: three of 32
-    const long long per_seg = (D == 256) ? 4 : (D == 96 ? 3 : 1);
+    const long long per_seg = (D == 256) ? 4 : ((D == 96 && !full_width) ? 3 : 1);
     long long want = 256 / (per_seg * chain_passes);
     // a pass that must keep full-width slices has no column split to fall back on
     const long long min_len = full_width ? 1024 : 512;
@@ -294,10 +294,10 @@ static ltn_status fwd_common(const void* q, const void* k, const void* v, const 
     const ltn_status cs = check_common(Bt, H, N, D, block, dtype, &blk);
     if (cs != LTN_OK) return cs;
     if (gated && !(eps >= 0.0f)) return LTN_ERR_SHAPE;
-    // 96 and 256 features: no kernel holds a complete output row of these widths in one workgroup,
-    // so the epilogue is applied to the stored attention output by the gate kernel; a caller
-    // that does not want o stored has no fused form to fall back on
-    const bool unfused_only = gated && (D == 256 || D == 96);
+    // 256 features (and 96 in fp32): no kernel holds a complete output row of these widths in one
+    // workgroup, so the epilogue is applied to the stored attention output by the gate kernel; a
+    // caller that does not want o stored has no fused form to fall back on
+    const bool unfused_only = gated && (D == 256 || (D == 96 && dtype != LTN_BF16));
     if (unfused_only && !o && !empty) return LTN_ERR_UNSUPPORTED;
     const size_t need_ws = ltn_attn_workspace_bytes(Bt, H, N, D, block, dtype, gated ? 2 : 0);
     if (workspace_bytes < need_ws) return LTN_ERR_SHAPE;

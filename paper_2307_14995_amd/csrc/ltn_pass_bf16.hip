@@ -178,14 +178,14 @@ struct ReadOffs {
 //   token mixer's epilogue (Sec. 3.1.2 Eq. 3 with the SimpleRMSNorm of Sec. 3.1.3 per head),
 //   y = o / sqrt(mean(o^2) + eps) (.) u, is applied before anything is stored; gate/yout are
 //   this lane's addresses in U and Y (same position as out), out may be null.
-template <int D, int DV, int W, int CCOLS, bool GATED = false>
+template <int D, int DV, int W, int CCOLS, bool GATED = false, int DROW = D>
 __device__ __forceinline__ void output_pass(const char* btile, const char* ctile, const char* scopy,
                                             const Frag (&Af)[D / 32], const OutConsts<W>& k,
                                             const ReadOffs<D, DV, CCOLS>& ro, char* out, bool store,
                                             const char* gate = nullptr, char* yout = nullptr, float eps = 0.f) {
     using C = Cfg<D, DV>;
     constexpr int KS = C::KS, NT = C::NT, RB = C::F::RB, CRB = Swz<CCOLS>::RB;
-    static_assert(!GATED || DV == D, "the gated epilogue needs complete output rows");
+    static_assert(!GATED || DV == DROW, "the gated epilogue needs complete output rows (DROW features)");
 
     // gate values of this lane's token: issued first, used last
     u32x4 uq[GATED ? NT / 2 : 1];
@@ -284,7 +284,7 @@ __device__ __forceinline__ void output_pass(const char* btile, const char* ctile
             auto t = __builtin_amdgcn_permlane16_swap(__float_as_uint(ss), __float_as_uint(ss), false, false);
             ss = __uint_as_float(t[0]) + __uint_as_float(t[1]);
         }
-        const float rstd = 1.0f / sqrtf(ss * (1.0f / D) + eps);
+        const float rstd = 1.0f / sqrtf(ss * (1.0f / DROW) + eps);
 #pragma unroll
         for (int p = 0; p < NT / 2; ++p) {
             float x[8];
@@ -535,7 +535,7 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, un
         for (int ks = 0; ks < KS; ++ks) Af[ks].u = *(const u32x4*)(st + (16 * W) * C::F::RB + ro.row[ks]);
         const long long bo = (long long)blk * step;
         // with more blocks to come every lane stores (the count above relies on it)
-        output_pass<D, DV, W, C::CW, GATED>(st + C::BOFF, st + C::COFF,
+        output_pass<D, DV, W, C::CW, GATED, DC>(st + C::BOFF, st + C::COFF,
                                          smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
                                          po ? po + bo : nullptr, more || row_ok,
                                          GATED ? pu + bo : nullptr, GATED ? py + bo : nullptr, ch.eps);
@@ -829,7 +829,8 @@ void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
 template <int D, int DV, int MODE = kPlain, int DC = D, int DR = D>
 hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
     static_assert(DV <= DC && DC % DV == 0, "value-column slices tile the C operand");
-    static_assert(DC == D || MODE != kGated, "unequal widths: no gated epilogue");
+    static_assert(DC == D || MODE != kGated || (D == 128 && DC == 96 && DR == 96 && DV == 96),
+                  "unequal widths: no gated epilogue (heads of 96 features computed as 128 have one)");
     const int nsplit = DC / DV;
     const long long wgs = (long long)pb.chains * pb.segs * pb.count * nsplit;
     if (wgs <= 0 || wgs > 0x7fffffffLL || pb.segs < 1) return hipErrorInvalidValue;
@@ -858,7 +859,11 @@ hipError_t launch_pass_bf16(const PassBatch& pb, int D, int dv, hipStream_t stre
         return hipErrorInvalidValue;
     }
     if (D == 96) {                         // computed as 128 with zero-filled tile columns: 32-column slices or all 96
-        if (pb.p[0].gate || (dv != 32 && dv != 96)) return hipErrorInvalidValue;
+        if (dv != 32 && dv != 96) return hipErrorInvalidValue;
+        if (pb.p[0].gate) {                // gated epilogue: one pass, all 96 columns of a row in one workgroup
+            if (pb.count != 1 || dv != 96 || !pb.p[0].gated_out || pb.state_only) return hipErrorInvalidValue;
+            return launch_t<128, 96, kGated, 96, 96>(pb, stream);
+        }
         if (pb.state_only) return dv == 32 ? launch_t<128, 32, kStateOnly, 96, 96>(pb, stream) : hipErrorInvalidValue;
         if (dv == 96) return launch_t<128, 96, kPlain, 96, 96>(pb, stream);
         return launch_t<128, 32, kPlain, 96, 96>(pb, stream);

@@ -126,6 +126,6 @@ def test_d96_unsupported_variants():
     decay = synth.decay_bench_rule(H).to(dev())
     a = torch.zeros(1, H, 64, D, dtype=torch.bfloat16, device=dev())
     with pytest.raises(ltn.LtnError):
-        ltn.ltn_attn_fwd_gated(a, a.clone(), a.clone(), a.clone(), decay, store_o=False)   # only with O stored
+        ltn.ltn_attn_fwd_gated(a.float(), a.float(), a.float(), a.float(), decay, store_o=False)   # fp32: only with O stored
     with pytest.raises(ltn.LtnError):
         ltn.ltn_attn_fwd_tiled(a, a.clone(), a.clone(), decay)

@@ -205,8 +205,8 @@ def test_forward_gated_full_size_every_chain():
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 @pytest.mark.parametrize("D", [96, 256])
 def test_gated_other_head_dims(dtype, D):
-    """96 and 256 features: the gate kernels on rows, and the gated forward in its one form
-    there (plain forward, then the epilogue on the stored attention output)."""
+    """96 and 256 features: the gate kernels on rows, and the gated forward in the form every
+    width and dtype has (plain forward, then the epilogue on the stored attention output)."""
     tol = TOL[dtype]
     rows = 1031
     g = torch.Generator().manual_seed(940 + D)
@@ -230,8 +230,40 @@ def test_gated_other_head_dims(dtype, D):
     check("O", o, o_ref, tol)
     check("Y | stored O", yy, orc.gate_fwd(o.cpu(), ug, 1e-6), tol)
     check("Y", yy, orc.gate_fwd(o_ref, ug, 1e-6), 2 * tol)      # end to end: one stored rounding deep
-    with pytest.raises(ltn.LtnError):
-        ltn.ltn_attn_fwd_gated(*gpu(q, k, v, ug, decay), eps=1e-6, store_o=False)
+    if D == 96 and dtype == torch.bfloat16:      # a workgroup holds all 96 columns of a row: the fused form exists
+        _, y2 = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, ug, decay), eps=1e-6, store_o=False)
+        check("Y (fused)", y2, orc.gate_fwd(o_ref, ug, 1e-6), tol)
+    else:
+        with pytest.raises(ltn.LtnError):
+            ltn.ltn_attn_fwd_gated(*gpu(q, k, v, ug, decay), eps=1e-6, store_o=False)
+
+
+@pytest.mark.parametrize("N,segs", [(1, 0), (63, 0), (65, 0), (333, 0), (517, 3), (1000, 5)])
+def test_bf16_forward_gated_96_features(N, segs):
+    """The fused epilogue on heads of 96 features (all 96 value columns in one workgroup), ragged
+    lengths, with an initial state, the final state and O stored or not; also on forced segments."""
+    Bt, H, D = 2, 3, 96
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 470 + N)
+    u = synth.make_gate(Bt, H, N, D, torch.bfloat16, 470 + N)
+    kv0 = torch.randn(Bt, H, D, D, generator=torch.Generator().manual_seed(N)) * 0.1
+    decay = mixed_decay(H)
+    o_ref, y_ref = orc.fwd_gated(q, k, v, u, decay, eps=1e-6, kv_in=kv0)
+    _, kv_ref = orc.fwd_recurrent(q, k, v, decay, kv_in=kv0, return_state=True)
+    with force_plan(segs=segs):
+        _, y, kv = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6, kv_in=kv0.to(dev()),
+                                          return_state=True, store_o=False)
+    check("Y", y, y_ref, 1e-2)
+    check("kv", kv, kv_ref, 1e-2)
+    if segs == 0:
+        # many chains: the library keeps the fused form with O stored too (192 chains and more)
+        Bt2, H2 = 8, 24
+        q, k, v = synth.make_qkv(Bt2, H2, N, D, torch.bfloat16, 480 + N)
+        u = synth.make_gate(Bt2, H2, N, D, torch.bfloat16, 480 + N)
+        decay = synth.decay_bench_rule(H2)
+        o_ref, y_ref = orc.fwd_gated(q, k, v, u, decay, eps=1e-6)
+        o, y = ltn.ltn_attn_fwd_gated(*gpu(q, k, v, u, decay), eps=1e-6)
+        check("O (192 chains)", o, o_ref, 1e-2)
+        check("Y (192 chains)", y, y_ref, 1e-2)
 
 
 def test_forward_gated_argument_errors():

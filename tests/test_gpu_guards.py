@@ -98,6 +98,28 @@ def test_guards_decode(dtype, D, S):
 
 
 @pytest.mark.parametrize("N", [1, 65, 517])
+def test_guards_96_features_all_columns_and_gated(N):
+    Bt, H, D = 1, 3, 96
+    q, k, v = gpu(*synth.make_qkv(Bt, H, N, D, torch.bfloat16, 1380 + N))
+    g, = gpu(synth.make_do(Bt, H, N, D, torch.bfloat16, 1380 + N))
+    u, = gpu(synth.make_gate(Bt, H, N, D, torch.bfloat16, 1380 + N))
+    dd, = gpu(mixed_decay(H))
+    for segs in (0, 3):
+        with force_plan(96, segs):
+            o, y, y2 = (Guarded((Bt, H, N, D), torch.bfloat16) for _ in range(3))
+            kv = Guarded((Bt, H, D, D), torch.float32)
+            ltn.ltn_attn_fwd(q, k, v, dd, out=o.t, kv_out=kv.t)
+            gr = [Guarded((Bt, H, N, D), torch.bfloat16) for _ in range(3)]
+            ltn.ltn_attn_bwd(q, k, v, g, dd, out=tuple(x.t for x in gr))
+            ltn.ltn_attn_fwd_gated(q, k, v, u, dd, eps=1e-6, store_o=False, y_out=y.t)
+            o2 = Guarded((Bt, H, N, D), torch.bfloat16)
+            ltn.ltn_attn_fwd_gated(q, k, v, u, dd, eps=1e-6, out=o2.t, y_out=y2.t)
+            torch.cuda.synchronize()
+        for x in [o, y, y2, o2, kv] + gr:
+            assert x.intact() and x.written()
+
+
+@pytest.mark.parametrize("N", [1, 65, 517])
 def test_guards_gated_tiled_and_unequal_widths(N):
     Bt, H, D = 1, 3, 128
     q, k, v = gpu(*synth.make_qkv(Bt, H, N, D, torch.bfloat16, 1360 + N))
