@@ -405,6 +405,27 @@ def test_bf16_segmented_by_default_for_few_long_chains():
         check(n, x, r, 1e-2)
 
 
+def test_one_very_long_chain():
+    """A single chain of 262144 tokens: the deepest cut the library's rule makes (256 segments, one
+    per compute unit), forward with the final state and backward, every token row against the oracle."""
+    Bt, H, N, D = 1, 1, 262144, 64
+    assert ltn.ltn_attn_query_plan(Bt, H, N, D, torch.bfloat16, 0)[1] == 256
+    assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 1) == 3 * 84 * D * D * 4
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 97)
+    g = synth.make_do(Bt, H, N, D, torch.bfloat16, 97)
+    decay = torch.tensor([float(np.exp(-1.0 / 512.0))])
+    o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), return_state=True)
+    grads = ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay))
+    ref, kv_ref = orc.fwd_recurrent(q, k, v, decay, return_state=True)
+    refs = orc.bwd_recurrent(q, k, v, g, decay)
+    check("O", o, ref, 1e-2)
+    check_rows("O rows", o, ref, TOL_ROW[torch.bfloat16])
+    check("kv", kv, kv_ref, 1e-2)
+    for n, x, r in zip(("dQ", "dK", "dV"), grads, refs):
+        check(n, x, r, 1e-2)
+        check_rows(n + " rows", x, r, TOL_ROW[torch.bfloat16])
+
+
 def test_segmented_call_needs_its_workspace():
     Bt, H, N, D = 1, 2, 8192, 128
     q, k, v = gpu(*synth.make_qkv(Bt, H, N, D, torch.bfloat16, 93))
