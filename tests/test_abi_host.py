@@ -152,6 +152,21 @@ def test_decode_steps_argument_errors(lib):
     assert call(S=0, q=None, k=None, v=None, o=None) == OK # nothing to read: pointers may be NULL
 
 
+def test_public_header_is_plain_c_and_cxx(tmp_path):
+    """The boundary is a C ABI: the header must compile on its own as C99 and as C++ (no torch or
+    HIP types in the signatures)."""
+    import os
+    import shutil
+    import subprocess
+    hdr = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "ltn_attn.h")
+    for cc, args in (("gcc", ["-xc", "-std=c99"]), ("g++", ["-xc++", "-std=c++17"])):
+        if shutil.which(cc) is None:
+            pytest.skip(cc + " not available")
+        r = subprocess.run([cc] + args + ["-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", hdr],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+
+
 def test_fwd_gated_argument_errors(lib):
     f = lib.ltn_attn_fwd_gated
     cf = ctypes.c_float
