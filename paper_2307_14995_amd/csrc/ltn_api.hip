@@ -107,7 +107,8 @@ ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype 
 // bf16 kernels only.  Heads of 256 features always need four 64-column workgroups per chain
 // and segment, heads of 96 three of 32; there the form pays from 3 segments of at least 512
 // tokens on (measured: 2 .. 32 chains, N = 2048 .. 32768, forward and backward), for the gated
-// pass from 4 segments of at least 1024 tokens on (32 and 64 chains, N = 8192, 16384).
+// pass from 4 segments of at least 512 tokens on, and from 2 when they are at least 2048 tokens
+// long (measured: 4 .. 100 chains, N = 2048 .. 16384, 64 / 96 / 128 features).
 // ltn_attn_set_debug_plan (test only) forces a segment count.
 struct SegPlan { int segs; long long seg_len; };
 constexpr long long kMinSegsFullWidth = 4;   // measured: 2 segments lose to one workgroup per chain
@@ -119,10 +120,14 @@ SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtyp
     const long long per_seg = (D == 256) ? 4 : ((D == 96 && !full_width) ? 3 : 1);
     long long want = 256 / (per_seg * chain_passes);
     // a pass that must keep full-width slices has no column split to fall back on
-    const long long min_len = full_width ? 1024 : 512;
-    if (want > N / min_len) want = N / min_len;
+    if (want > N / 512) want = N / 512;       // segments of at least 512 tokens
     if (full_width) {
-        if (want < kMinSegsFullWidth) want = 1;
+        // from 4 ways on; 2 or 3 ways when the segments stay at least 2048 tokens long (not for 96
+        // features, whose state-only sweep runs three workgroups per segment; for 128 features
+        // only when that leaves an eighth of the compute units free: at 128 chains the second
+        // read of K and V costs more than the idle half of the chip)
+        const bool few_ok = D != 96 && want >= 2 && N / want >= 2048 && (D == 64 || chain_passes * want <= 224);
+        if (want < kMinSegsFullWidth && !few_ok) want = 1;
     } else if (per_seg > 1) {
         if (want < 3) want = 1;
     } else if (want < 8 && !(want >= 5 && N / want >= 2048)) {

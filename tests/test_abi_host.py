@@ -375,9 +375,9 @@ def test_workspace_query(lib):
     assert ltn.ltn_attn_workspace_bytes(1, 16, 16384, D, 0, torch.bfloat16, 1) == 3 * 16 * 5 * D * D * 4
     assert ltn.ltn_attn_workspace_bytes(1, 16, 8192, D, 0, torch.bfloat16, 1) == 0
     assert ltn.ltn_attn_workspace_bytes(0, 2, 8192, D, 0, torch.bfloat16, 0) == 0
-    # the gated forward keeps full-width slices, so it cuts chains sooner (from 4 segments on)
-    # (4 segments; its other form, plain forward + gate kernel, takes the plain forward's 8: room for both)
-    assert ltn.ltn_attn_query_plan(1, 32, 4096, D, torch.bfloat16, 2) == (128, 4)
+    # the gated forward keeps full-width slices, so it cuts chains sooner (from 4 segments on, or 2 long ones)
+    # (8 segments of 512 tokens, as its other form, plain forward + gate kernel, takes: room for either)
+    assert ltn.ltn_attn_query_plan(1, 32, 4096, D, torch.bfloat16, 2) == (128, 8)
     assert ltn.ltn_attn_workspace_bytes(1, 32, 4096, D, 0, torch.bfloat16, 2) == 32 * 8 * D * D * 4
     for (Bt, H, N) in [(1, 2, 2048), (1, 4, 4096), (1, 8, 8192), (2, 8, 16384), (1, 32, 65536), (1, 48, 16384), (4, 32, 8192)]:
         for d in (64, 96, 128, 256):

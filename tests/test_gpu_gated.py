@@ -135,9 +135,9 @@ def test_bf16_forward_gated_segmented(segs, N):
 
 
 def test_bf16_forward_gated_few_long_chains_by_default():
-    Bt, H, N, D = 1, 4, 4096 + 50, 128       # 4 chains: the fused form is cut 4 ways by the library's own rule,
-    # the plain forward (+ gate kernel, the form taken when O is stored) 8 ways; the query covers both
-    assert ltn.ltn_attn_query_plan(Bt, H, N, D, torch.bfloat16, 2) == (128, 4)
+    Bt, H, N, D = 1, 4, 4096 + 50, 128       # 4 chains: cut 8 ways by the library's own rule, the fused form and
+    # the plain forward (+ gate kernel, the form taken when O is stored) alike; the query covers both
+    assert ltn.ltn_attn_query_plan(Bt, H, N, D, torch.bfloat16, 2) == (128, 8)
     assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 2) == 8 * Bt * H * D * D * 4
     assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 0) == 8 * Bt * H * D * D * 4
     q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 49)
