@@ -39,8 +39,9 @@
 //     40-48 wave-wide loads holds its issuer for 600-1600 cycles, and those two waves have the
 //     fewest causal score tiles.  They wait for a block with an exact vmcnt that counts their
 //     own stores in between (VMEM operations of a wave retire in issue order), never for the
-//     stores themselves.  The gated pass, heads of 96 features and the register-fed layout
-//     keep the loads in the state waves.  LDS rows are unpadded; the 16-byte chunk
+//     stores themselves.  In the register-fed layout (256 features) all four output waves
+//     share the loads; the gated pass and heads of 96 features keep them in the state waves.
+//     LDS rows are unpadded; the 16-byte chunk
 //     index is XOR-swizzled with the row so that row reads, transpose reads
 //     (ds_read_b64_tr_b16, for operands needed "down the token axis") and the state-copy
 //     writes spread over the banks.  Rows past the end of a short last block are fetched
@@ -88,17 +89,19 @@ struct Cfg {
     // the texture addresser takes 16 cycles per wave-wide 1 KB load, and whoever issues a
     // block's 40-48 loads in a burst stands still for that long.
     static constexpr int FW = 2;
+    // AREG layout: all four output waves share the B and C tile loads (each also fetches its own
+    // A fragments); the state waves' update and publish are the longer chain there.
+    static constexpr int AFW = 4;
 };
 
 // MODE of a workgroup: the plain pass, the pass with the gated epilogue, or the
 // state-only sweep of the sequence-parallel form (no outputs: only the segment's end state).
 enum { kPlain = 0, kGated = 1, kStateOnly = 2 };
 
-// Who issues the tile loads: output waves in the plain pass (unless they feed themselves the
-// A operand through registers) and in the state-only sweep, where they have nothing else to
-// do, over tensors whose rows fill the tiles; the state waves otherwise.
+// Who issues the tile loads: output waves in the plain pass and in the state-only sweep, where
+// they have nothing else to do, over tensors whose rows fill the tiles; the state waves otherwise.
 template <int D, int DV, int MODE, int DR>
-constexpr bool kOutFetch = DR == D && ((MODE == kPlain && !Cfg<D, DV>::AREG) || MODE == kStateOnly);
+constexpr bool kOutFetch = DR == D && (MODE == kPlain || MODE == kStateOnly);
 
 // Register prefetch loads of the AREG output waves are issued from inline assembly and
 // waited for with explicit vmcnt counts: left to the compiler, loads that rotate through
@@ -549,9 +552,10 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, un
 }
 
 // Output wave of the AREG layout: as pass_output_wave, but the A fragments of its 16 rows
-// come straight from global memory into three rotating register sets, two blocks ahead.
+// come straight from global memory into three rotating register sets, two blocks ahead, and
+// every output wave issues a quarter of the B and C tile loads.
 template <int D, int DV, int DC, int W>
-__device__ __forceinline__ void areg_output_wave(const Chain& ch, char* smem, int lane) {
+__device__ __forceinline__ void areg_output_wave(const Chain& ch, char* smem, unsigned lds0, int lane) {
     using C = Cfg<D, DV>;
     constexpr int KS = C::KS, NT = C::NT;
     static_assert(KS == 8, "register sets of eight fragments");
@@ -577,10 +581,37 @@ __device__ __forceinline__ void areg_output_wave(const Chain& ch, char* smem, in
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) gload16(s.f[ks], ok ? p + ks * 64 : (const char*)kZeros);
     };
+    // Tile pipeline: per block this wave issues, in this order, its L loads of the B and C tiles
+    // of block blk + PST - 1, the KS loads of set(blk + 2) and the NT/2 stores of block blk; all
+    // of them retire in issue order.
+    constexpr int L = (TileDmaU<D>::NI + TileDmaU<C::CW>::NI) / C::AFW;
+    static_assert(W < C::AFW && TileDmaU<D>::NI % C::AFW == 0 && TileDmaU<C::CW>::NI % C::AFW == 0, "even shares");
+    TileDmaU<D> dbb;
+    TileDmaU<C::CW> dcc;
+    dbb.init(lane, AROW, ch.rev);
+    dcc.init(lane, ROW, ch.rev);
+    const char* pb0 = ch.b + (ch.rev ? (ch.N - 1) * AROW : 0);
+    const char* pc0 = ch.c + (ch.rev ? (ch.N - 1) * ROW : 0);
+    auto fetch = [&](int b, int stage) {
+        b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block into a free stage
+        const int valid = valid_of(b);
+        const unsigned lds = lds0 + (unsigned)(stage * C::PSTAGE);
+        const char* pb = pb0 + (long long)b * astep;
+        const char* pc = pc0 + (long long)b * step;
+        if (valid == kBlock) {
+            dbb.template issue_full<C::AFW, W>(pb, AROW, ch.rev, lds + C::BOFF);
+            dcc.template issue_full<C::AFW, W>(pc, ROW, ch.rev, lds + C::COFF);
+        } else {
+            dbb.template issue_partial<C::AFW, W>(pb, AROW, ch.rev, lds + C::BOFF, valid, lane);
+            dcc.template issue_partial<C::AFW, W>(pc, ROW, ch.rev, lds + C::COFF, valid, lane);
+        }
+    };
     // Set(blk) was issued two blocks ago; since then this wave issued the NT/2 stores of
-    // each of two blocks and the KS loads of set(blk+1).
-    constexpr int kAfter = NT + KS;
-    static_assert(kAfter <= 63, "vmcnt field");
+    // each of two blocks, the KS loads of set(blk+1) and one block's tile loads.
+    constexpr int kAfter = NT + KS + L;
+    // The tiles of block blk + 1 went out PST - 1 blocks ago, before that block's set and stores.
+    constexpr int kTilesAfter = (C::PST - 1) * (KS + NT / 2) + (C::PST - 2) * L;
+    static_assert(kAfter <= 63 && kTilesAfter <= 63, "vmcnt field");
 
     auto do_block = [&](int blk, int stage, Set& cur_set, Set& incoming) {
         const bool more = blk + 1 < ch.T;
@@ -589,16 +620,25 @@ __device__ __forceinline__ void areg_output_wave(const Chain& ch, char* smem, in
         Frag Af[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) Af[ks].u = cur_set.f[ks];
+        int fs = stage + C::PST - 1;       // stage of block blk + PST - 1 (free since the last barrier)
+        if (fs >= C::PST) fs -= C::PST;
+        fetch(blk + C::PST - 1, fs);
         load_a(incoming, blk + 2);
         const char* st = smem + stage * C::PSTAGE;
+        // with more blocks to come every lane stores (the counts above rely on it)
         output_pass<D, DV, W, C::CW>(st + C::BOFF, st + C::COFF, smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
                                   po + (long long)blk * step, more || row_ok);
-        if (more) __syncthreads();
+        if (more) {
+            wait_dma<kTilesAfter>();       // block blk + 1 has landed (this wave's part)
+            __syncthreads();
+        }
     };
 
     Set s0, s1, s2;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) s0.f[ks] = s1.f[ks] = s2.f[ks] = u32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int b = 0; b < C::PST - 1; ++b) fetch(b, b);      // tiles of blocks 0 .. PST-2
     load_a(s0, 0);
     load_a(s1, 1);
     wait_vm8<0>(s0.f);                     // blocks 0 and 1 are retired here, so the
@@ -612,7 +652,8 @@ __device__ __forceinline__ void areg_output_wave(const Chain& ch, char* smem, in
         if (blk + 1 < ch.T) { do_block(blk + 1, stage, s1, s0); next(); }
         if (blk + 2 < ch.T) { do_block(blk + 2, stage, s2, s1); next(); }
     }
-    // the last two prefetches were never consumed: retire them before the registers die
+    // the last two prefetches were never consumed: retire them before the registers die (and
+    // with them every tile load: nothing may land in LDS after this workgroup is gone)
     wait_vm8<0>(s0.f);
     wait_vm8<0>(s1.f);
     wait_vm8<0>(s2.f);
@@ -796,10 +837,10 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
                     else if (wave == 2) pass_output_wave<D, DV, DC, 2, MODE, DR>(ch, smem, lds0, lane);
                     else pass_output_wave<D, DV, DC, 3, MODE, DR>(ch, smem, lds0, lane);
                 } else {
-                    if (wave == 0) areg_output_wave<D, DV, DC, 0>(ch, smem, lane);
-                    else if (wave == 1) areg_output_wave<D, DV, DC, 1>(ch, smem, lane);
-                    else if (wave == 2) areg_output_wave<D, DV, DC, 2>(ch, smem, lane);
-                    else areg_output_wave<D, DV, DC, 3>(ch, smem, lane);
+                    if (wave == 0) areg_output_wave<D, DV, DC, 0>(ch, smem, lds0, lane);
+                    else if (wave == 1) areg_output_wave<D, DV, DC, 1>(ch, smem, lds0, lane);
+                    else if (wave == 2) areg_output_wave<D, DV, DC, 2>(ch, smem, lds0, lane);
+                    else areg_output_wave<D, DV, DC, 3>(ch, smem, lds0, lane);
                 }
                 break;
             default: pass_state_wave<D, DV, DC, MODE, DR>(ch, smem, lds0, lane, wave - 4); break;
