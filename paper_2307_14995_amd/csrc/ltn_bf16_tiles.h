@@ -2,6 +2,8 @@
 // MFMA operand fragments, direct global -> LDS tile loads, the swizzled LDS tile layout and
 // the regrouped 16-byte output stores.  Internal; included by the kernel sources only.
 #pragma once
+#include <type_traits>
+#include <utility>
 #include "ltn_kernels.h"
 
 namespace ltn {
@@ -38,6 +40,15 @@ __device__ __forceinline__ void dma16(unsigned lds, const char* g) {
 __device__ __forceinline__ void dma16s(unsigned lds, const char* base, unsigned off) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds), "v"(off), "s"(base) : "memory", "m0");
 }
+// The same with only the lanes of `mask` taking part (wave-uniform; all 64 lanes are active at
+// the call): the other lanes' LDS slots are left as they are.  EXEC is put back inside the
+// statement.
+__device__ __forceinline__ void dma16s_masked(unsigned lds, const char* base, unsigned off, unsigned long long mask) {
+    unsigned long long saved;
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, %4\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, %0"
+                 : "=&s"(saved) : "s"(lds), "v"(off), "s"(base), "s"(mask) : "memory", "m0");
+}
 template <int N>
 __device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory"); }
 
@@ -58,6 +69,13 @@ __device__ __forceinline__ bf16x4 to_bf16(const f32x4& x) {
 
 constexpr int kBlock = 64;
 
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(const F& f, std::integer_sequence<int, Is...>) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(const F& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
+
 // Unpadded row-major LDS tile of COLS bf16 columns whose 16-byte chunks are XOR-swizzled
 // with the row: chunk c of row r lives at chunk position c ^ key(r).  The key is built so
 // that (i) 8 consecutive rows put a given 32-byte chunk pair on 8 different bank groups
@@ -74,9 +92,9 @@ struct Swz {
     static constexpr int BYTES = kBlock * RB;  // a 64-row tile
     static constexpr int NI = BYTES / 1024;    // wave-wide direct loads per tile
     static_assert(COLS == 256 || COLS == 128 || COLS == 64 || COLS == 32, "tile widths");
-    __device__ static __forceinline__ int key(int r) {
-        const int q = r / RPB;             // index of the row's 256-byte group member
-        return ((q % (KC / 2)) << 1) | ((q / (KC / 2)) & 1);
+    __host__ __device__ static constexpr int key(int r) {
+        // q: index of the row's 256-byte group member
+        return (((r / RPB) % (KC / 2)) << 1) | (((r / RPB) / (KC / 2)) & 1);
     }
     __device__ static __forceinline__ int off(int r, int c) { return r * RB + ((c ^ key(r)) << 4); }
 };
@@ -133,12 +151,35 @@ struct TileDma {
 // per-lane offsets; the 16-row group and the block sit in the wave-uniform base address.  Load
 // j = m NV + v (m: 16-row group, v < NV) fills LDS slots 64j .. 64j+63 as above; of NW issuing
 // waves, wave W_ takes the loads with j % NW == W_ (NI / NW loads per tile and wave).
-template <int COLS>
+// REAL < COLS: the tensor's rows hold only REAL features.  The lanes of the tile's remaining
+// chunks take no part in a load, so those chunks keep what they hold: zeros written once by
+// the workgroup before its first load.
+template <int COLS, int REAL = COLS>
 struct TileDmaU {
     using S = Swz<COLS>;
     static constexpr int NV = S::CPR / 4;
     static constexpr int NI = S::NI;
     static_assert(NV >= 1 && NI == 4 * NV, "four 16-row groups per tile");
+    static_assert(REAL % 8 == 0 && REAL <= COLS, "whole 16-byte chunks");
+    // lanes of load v (of any 16-row group) whose chunk holds real features
+    __host__ __device__ static constexpr unsigned long long real_lanes(int v) {
+        unsigned long long m = 0;
+        for (int lane = 0; lane < 64; ++lane) {
+            const int slot = 64 * v + lane;
+            const int c = (slot % S::CPR) ^ S::key(slot / S::CPR);
+            if (c * 8 < REAL) m |= 1ull << lane;
+        }
+        return m;
+    }
+    template <int V>
+    __device__ __forceinline__ void load(unsigned lds, const char* grp) const {
+        if constexpr (REAL == COLS) {
+            dma16s(lds, grp, off[V]);
+        } else {
+            constexpr unsigned long long m = real_lanes(V);
+            dma16s_masked(lds, grp, off[V], m);
+        }
+    }
     unsigned off[NV];     // (row within its 16-row group, from the group's lowest-address row) * pitch + chunk * 16
     __device__ __forceinline__ void init(int lane, long long pitch, int rev) {
 #pragma unroll
@@ -157,9 +198,10 @@ struct TileDmaU {
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             const char* grp = row0 + (rev ? -(long long)(16 * m + 15) * pitch : (long long)(16 * m) * pitch);
-#pragma unroll
-            for (int v = 0; v < NV; ++v)
-                if ((m * NV + v) % NW == W_) dma16s(lds + 1024u * (unsigned)(m * NV + v), grp, off[v]);
+            static_for<NV>([&](auto vc) {
+                constexpr int v = decltype(vc)::value;
+                if ((m * NV + v) % NW == W_) load<v>(lds + 1024u * (unsigned)(m * NV + v), grp);
+            });
         }
     }
     // The same loads for a short last block: rows >= valid come from the zero buffer.
@@ -169,12 +211,15 @@ struct TileDmaU {
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
             const char* grp = row0 + (rev ? -(long long)(16 * m + 15) * pitch : (long long)(16 * m) * pitch);
-#pragma unroll
-            for (int v = 0; v < NV; ++v)
+            static_for<NV>([&](auto vc) {
+                constexpr int v = decltype(vc)::value;
                 if ((m * NV + v) % NW == W_) {
+                    constexpr unsigned long long rl = real_lanes(v);
                     const int r = 16 * m + (64 * v + lane) / S::CPR;
-                    dma16(lds + 1024u * (unsigned)(m * NV + v), r < valid ? grp + off[v] : (const char*)kZeros);
+                    const bool real = REAL == COLS || ((rl >> lane) & 1);
+                    dma16(lds + 1024u * (unsigned)(m * NV + v), (r < valid && real) ? grp + off[v] : (const char*)kZeros);
                 }
+            });
         }
     }
 };

@@ -40,12 +40,13 @@
 //     fewest causal score tiles.  They wait for a block with an exact vmcnt that counts their
 //     own stores in between (VMEM operations of a wave retire in issue order), never for the
 //     stores themselves.  In the register-fed layout (256 features) all four output waves
-//     share the loads; the gated pass and heads of 96 features keep them in the state waves.
-//     LDS rows are unpadded; the 16-byte chunk
+//     share the loads; the gated pass keeps them in the state waves (its output waves also
+//     load the gate through the compiler's own wait counts).  LDS rows are unpadded; the 16-byte chunk
 //     index is XOR-swizzled with the row so that row reads, transpose reads
 //     (ds_read_b64_tr_b16, for operands needed "down the token axis") and the state-copy
 //     writes spread over the banks.  Rows past the end of a short last block are fetched
-//     from a small buffer of zeros.
+//     from a small buffer of zeros; tile columns past the end of a tensor's rows (heads of 96
+//     features in 128-wide tiles) are cleared once and masked out of every load.
 //   * wave role and strip are compile-time constants of the code each wave runs, so
 //     causal tile skipping costs no branches inside a block.
 // Only non-negative powers of lambda are formed.
@@ -99,9 +100,9 @@ struct Cfg {
 enum { kPlain = 0, kGated = 1, kStateOnly = 2 };
 
 // Who issues the tile loads: output waves in the plain pass and in the state-only sweep, where
-// they have nothing else to do, over tensors whose rows fill the tiles; the state waves otherwise.
+// they have nothing else to do; the state waves in the gated pass.
 template <int D, int DV, int MODE, int DR>
-constexpr bool kOutFetch = DR == D && (MODE == kPlain || MODE == kStateOnly);
+constexpr bool kOutFetch = MODE == kPlain || MODE == kStateOnly;
 
 // Register prefetch loads of the AREG output waves are issued from inline assembly and
 // waited for with explicit vmcnt counts: left to the compiler, loads that rotate through
@@ -440,9 +441,9 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, un
     constexpr int L = ISSUER ? ((NOA ? 1 : 2) * TileDmaU<D>::NI + TileDmaU<C::CW>::NI) / C::FW : 0;   // loads per block, this wave
     constexpr int S = SO ? 0 : C::NT / 2;                                                           // stores per block, this wave
     static_assert((C::PST - 2) * L + (C::PST - 1) * S <= 63, "vmcnt field");
-    constexpr long long AROW = D * 2;
-    TileDmaU<D> dab;                                  // A and B tiles: same shape, same offsets
-    TileDmaU<C::CW> dcc;
+    constexpr long long AROW = DR * 2;
+    TileDmaU<D, DR> dab;                              // A and B tiles: same shape, same offsets
+    TileDmaU<C::CW, DV> dcc;
     const char* pa0 = nullptr;
     const char* pb0 = nullptr;
     const char* pc0 = nullptr;
@@ -827,6 +828,27 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
     ch.rev = P.rev;
     ch.lam = pb.decay[chain % pb.H];
 
+    if constexpr (kOutFetch<D, DV, MODE, DR> && (DR != D || Cfg<D, DV>::CW != DV)) {
+        // Tiles wider than the tensors' rows: their loads leave the surplus chunks alone, which
+        // hold zeros from here on (cleared once, in every ring stage, before the first load).
+        using C = Cfg<D, DV>;
+        static_assert(!C::AREG, "stages with an A tile");
+        constexpr int ZA = (D - DR) / 8, ZC = (C::CW - DV) / 8;      // surplus chunks per row
+        constexpr int kPerStage = kBlock * (2 * ZA + ZC);
+        for (int i = wave * 64 + lane; i < C::PST * kPerStage; i += kThreads) {
+            const int stage = i / kPerStage, j = i % kPerStage;
+            int off;
+            if (j < 2 * kBlock * ZA) {
+                const int t = j / (kBlock * ZA), q = j % (kBlock * ZA);   // tile A or B, row and chunk
+                off = (t ? C::BOFF : 0) + C::F::off(q / ZA, DR / 8 + q % ZA);
+            } else {
+                const int q = j - 2 * kBlock * ZA;
+                off = C::COFF + C::V::off(q / (ZC ? ZC : 1), DV / 8 + q % (ZC ? ZC : 1));
+            }
+            *(u32x4*)(smem + stage * C::PSTAGE + off) = u32x4{0, 0, 0, 0};
+        }
+        __syncthreads();
+    }
     if constexpr (Cfg<D, DV>::AREG) {
         static_assert(MODE != kGated && DR == D, "the register-fed layout has no gated epilogue");
         switch (wave) {
