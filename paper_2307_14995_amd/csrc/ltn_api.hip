@@ -106,19 +106,36 @@ ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype 
 // (36 .. 48 passes of long chains, e.g. the backward of 12 .. 16 chains); never otherwise.
 // bf16 kernels only.  Heads of 256 features always need four 64-column workgroups per chain
 // and segment, heads of 96 three of 32; there the form pays from 3 segments of at least 512
-// tokens on (measured: 2 .. 32 chains, N = 2048 .. 32768, forward and backward), for the gated
+// tokens on (measured: 2 .. 32 chains, N = 2048 .. 32768, forward and backward; heads of 96
+// features have a second cut for their 96-column workgroups, in place), for the gated
 // pass from 4 segments of at least 512 tokens on, and from 2 when they are at least 2048 tokens
 // long (measured: 4 .. 100 chains, N = 2048 .. 16384, 64 / 96 / 128 features).
 // ltn_attn_set_debug_plan (test only) forces a segment count.
 struct SegPlan { int segs; long long seg_len; };
 constexpr long long kMinSegsFullWidth = 4;   // measured: 2 segments lose to one workgroup per chain
 
-SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtype, bool full_width = false) {
+SegPlan cut_chain(long long N, long long want) {
+    SegPlan plan = {1, 0};
+    if (want <= 1) return plan;
+    long long len = (N + want - 1) / want;
+    len = (len + 63) / 64 * 64;
+    const long long segs = (N + len - 1) / len;
+    if (segs <= 1 || segs > 0x7fff) return plan;
+    plan.segs = (int)segs;
+    plan.seg_len = len;
+    return plan;
+}
+
+// paired_chains: the number of chains when the passes are the three of a backward (whose
+// (dV, dK) workgroups sit side by side on one XCD at full width), else 0.
+SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtype, bool full_width = false,
+                      long long paired_chains = 0) {
     SegPlan plan = {1, 0};
     if (dtype != LTN_BF16 || chain_passes <= 0 || N <= 64) return plan;
     // D = 256: every (chain, segment) still needs four 64-column workgroups; D = 96: three of 32
     const long long per_seg = (D == 256) ? 4 : ((D == 96 && !full_width) ? 3 : 1);
     long long want = 256 / (per_seg * chain_passes);
+    bool whole_rows = per_seg == 1;        // one workgroup per chain, pass and segment
     // a pass that must keep full-width slices has no column split to fall back on
     if (want > N / 512) want = N / 512;       // segments of at least 512 tokens
     if (full_width) {
@@ -130,18 +147,47 @@ SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtyp
         if (want < kMinSegsFullWidth && !few_ok) want = 1;
     } else if (per_seg > 1) {
         if (want < 3) want = 1;
+        if (D == 96) {
+            // Workgroup ids deal (chain, segment) pairs to the 8 XCDs of 32 compute units and keep
+            // a pair's three slices on one XCD: an XCD's share must not exceed its units (11
+            // pairs per XCD -- 252 workgroups -- ran 30 % slower than 10).
+            while (want > 1 && (chain_passes * want + 7) / 8 * 3 > 32) --want;
+            // Heads of 96 features also have one 96-column workgroup per chain and segment
+            // (pick_dv takes it when three 32-column slices each would need more than one round).
+            // From 12 chain passes on, cutting for that width pays from 8 segments on -- of at
+            // least 768 tokens, or 512 where the rule above finds nothing to cut -- and from 5
+            // segments of at least 1024 tokens (measured: 4 .. 32 chains, N = 4096 .. 32768,
+            // forward and backward, every segment count).
+            if (chain_passes >= 12) {
+                long long all = 256 / chain_passes;
+                if (all > N / 512) all = N / 512;
+                if (all >= 5) {
+                    const long long len = N / all;
+                    if ((all >= 8 && (len >= 768 || want == 1)) || len >= 1024) {
+                        want = all;
+                        whole_rows = true;
+                    }
+                }
+            }
+        }
     } else if (want < 8 && !(want >= 5 && N / want >= 2048)) {
         want = 1;
     }
+    if (paired_chains > 0 && want >= 6 && whole_rows) {
+        // The backward's workgroup ids pair a chain's (dV, dK) passes on one XCD only when
+        // chains x segments is a multiple of 8: up to a quarter fewer segments for that
+        // (measured, 4 / 5 / 6 / 12 chains: 21 -> 20, 17 -> 16, 14 -> 12, 7 -> 6 segments run
+        // 9-15 % faster).
+        for (long long w = want; w >= 2 && 4 * w >= 3 * want; --w) {
+            const SegPlan p = cut_chain(N, w);
+            if (p.segs > 1 && (paired_chains * p.segs) % 8 == 0) {
+                want = w;
+                break;
+            }
+        }
+    }
     if (const int v = g_debug_segs.load(std::memory_order_relaxed)) want = v;
-    if (want <= 1) return plan;
-    long long len = (N + want - 1) / want;
-    len = (len + 63) / 64 * 64;
-    const long long segs = (N + len - 1) / len;
-    if (segs <= 1 || segs > 0x7fff) return plan;
-    plan.segs = (int)segs;
-    plan.seg_len = len;
-    return plan;
+    return cut_chain(N, want);
 }
 
 // full_width: the pass carries the gated epilogue, which needs complete output rows in one
@@ -149,7 +195,8 @@ SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtyp
 ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void* workspace, hipStream_t stream,
                       bool full_width = false) {
     const long long chain_passes = (long long)pb.chains * pb.count;
-    const SegPlan plan = pick_segments(chain_passes, pb.N, D, dtype, full_width);
+    const SegPlan plan = pick_segments(chain_passes, pb.N, D, dtype, full_width,
+                                       (pb.pairs_first && pb.count == 3) ? pb.chains : 0);
     pb.segs = 1;
     if (plan.segs == 1) {
         const int dv = full_width ? D : pick_dv(chain_passes, D, dtype, blk);
@@ -234,7 +281,7 @@ ltn_status ltn_attn_query_plan(int Bt, int H, long long N, int D, ltn_dtype dtyp
     if (dtype != LTN_F32 && dtype != LTN_BF16) return LTN_ERR_UNSUPPORTED;
     if (D != 64 && D != 96 && D != 128 && D != 256) return LTN_ERR_UNSUPPORTED;
     const long long chain_passes = (long long)Bt * H * (call == 1 ? 3 : 1);
-    const SegPlan plan = pick_segments(chain_passes, N, D, dtype, call == 2);
+    const SegPlan plan = pick_segments(chain_passes, N, D, dtype, call == 2, call == 1 ? (long long)Bt * H : 0);
     *segs_out = plan.segs;
     *dv_out = (call == 2) ? D : pick_dv(chain_passes * plan.segs, D, dtype, ltn_attn_pick_block(D, dtype));
     return LTN_OK;
@@ -253,7 +300,7 @@ size_t ltn_attn_workspace_bytes(int Bt, int H, long long N, int D, int block, lt
     const long long chains = (long long)Bt * H;
     const int count = (call == 1) ? 3 : 1;
     const size_t state = (size_t)D * D * sizeof(float);                                   // one fp32 state per segment
-    const SegPlan plan = pick_segments(chains * count, N, D, dtype, call == 2);
+    const SegPlan plan = pick_segments(chains * count, N, D, dtype, call == 2, call == 1 ? chains : 0);
     size_t need = plan.segs == 1 ? 0 : (size_t)count * (size_t)chains * (size_t)plan.segs * state;
     if (call == 2) {
         // the gated forward may run as the plain forward followed by the gate kernel (when the

@@ -329,6 +329,17 @@ def test_debug_plan_and_plan_query(lib):
     assert ltn.ltn_attn_query_plan(4, 32, 8192, 128, torch.bfloat16, 0) == (64, 1)    # headline forward: two slices
     assert ltn.ltn_attn_query_plan(4, 32, 8192, 128, torch.bfloat16, 1) == (128, 1)   # headline backward: full width
     assert ltn.ltn_attn_query_plan(1, 2, 8192, 128, torch.bfloat16, 0) == (32, 16)      # 32 chain segments of 512 tokens, four slices each
+    # backward of 4 chains: 21 ways would fill the chip, 20 keeps chains x segments a multiple of 8
+    assert ltn.ltn_attn_query_plan(1, 4, 32768, 128, torch.bfloat16, 1) == (128, 20)
+    assert ltn.ltn_attn_query_plan(1, 12, 16384, 128, torch.bfloat16, 1) == (128, 6)
+    assert ltn.ltn_attn_query_plan(1, 4, 32768, 128, torch.bfloat16, 0) == (128, 64)
+    # heads of 96 features: three-slice segments stay within an XCD's 32 units (80 chain segments,
+    # not 84); from 12 chain passes on the cut is made for one 96-column workgroup per segment
+    assert ltn.ltn_attn_query_plan(1, 4, 32768, 96, torch.bfloat16, 0) == (32, 20)
+    assert ltn.ltn_attn_query_plan(1, 32, 8192, 96, torch.bfloat16, 0) == (96, 8)
+    assert ltn.ltn_attn_query_plan(1, 32, 2048, 96, torch.bfloat16, 0) == (32, 1)
+    assert ltn.ltn_attn_query_plan(1, 16, 8192, 96, torch.bfloat16, 1) == (96, 5)
+    assert ltn.ltn_attn_query_plan(1, 16, 4096, 96, torch.bfloat16, 1) == (32, 1)
     try:
         ltn.ltn_attn_set_debug_plan(32, 3)
         assert ltn.ltn_attn_query_plan(4, 32, 8192, 128, torch.bfloat16, 0) == (32, 3)

@@ -121,6 +121,30 @@ def test_d96_few_long_chains_are_cut_into_segments_by_default():
     check("kv", kv, ref_kv, 1e-2)
 
 
+def test_d96_segments_of_whole_row_workgroups_by_default():
+    """From 12 chain passes on the library cuts for its 96-column workgroups (one per chain, pass
+    and segment): forward of 32 chains, backward of 8 (24 passes: 10 segments, 80 = a multiple of 8
+    chain segments), with a ragged tail and a state handed in."""
+    Bt, H, N = 1, 32, 4096 + 33
+    assert ltn.ltn_attn_query_plan(Bt, H, N, D, torch.bfloat16, 0) == (96, 8)
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 884)
+    kv0 = torch.randn(Bt, H, D, D, generator=torch.Generator().manual_seed(885)) * 0.1
+    decay = mixed_decay(H)
+    o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), kv_in=kv0.to(dev()), return_state=True)
+    ref, ref_kv = orc.fwd_recurrent(q, k, v, decay, kv_in=kv0, return_state=True)
+    check("o", o, ref, 1e-2)
+    check("kv", kv, ref_kv, 1e-2)
+    Bt, H, N = 1, 8, 8192 + 70
+    assert ltn.ltn_attn_query_plan(Bt, H, N, D, torch.bfloat16, 1) == (96, 10)
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 886)
+    g = synth.make_do(Bt, H, N, D, torch.bfloat16, 886)
+    decay = mixed_decay(H)
+    grads = ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay))
+    refs = orc.bwd_recurrent(q, k, v, g, decay)
+    for n, x, r in zip(("dq", "dk", "dv"), grads, refs):
+        check(n, x, r, 1e-2)
+
+
 def test_d96_unsupported_variants():
     H = 2
     decay = synth.decay_bench_rule(H).to(dev())

@@ -410,7 +410,8 @@ def test_one_very_long_chain():
     per compute unit), forward with the final state and backward, every token row against the oracle."""
     Bt, H, N, D = 1, 1, 262144, 64
     assert ltn.ltn_attn_query_plan(Bt, H, N, D, torch.bfloat16, 0)[1] == 256
-    assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 1) == 3 * 84 * D * D * 4
+    # backward: 85 ways at most for three passes, cut to 72 so that chains x segments is a multiple of 8
+    assert ltn.ltn_attn_workspace_bytes(Bt, H, N, D, 0, torch.bfloat16, 1) == 3 * 72 * D * D * 4
     q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 97)
     g = synth.make_do(Bt, H, N, D, torch.bfloat16, 97)
     decay = torch.tensor([float(np.exp(-1.0 / 512.0))])
