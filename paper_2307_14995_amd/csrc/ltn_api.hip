@@ -52,7 +52,8 @@ int pick_dv(long long chain_passes, int D, ltn_dtype dtype, int blk) {
         if (const int v = g_debug_dv.load(std::memory_order_relaxed)) {
             if (v == 32 || v == 96) return v;
         }
-        return chain_passes * 3 <= 256 ? 32 : 96;
+        // three slices per chain pass stay on one XCD: 10 chain passes per XCD of 32 units at most
+        return (chain_passes + 7) / 8 * 3 <= 32 ? 32 : 96;
     }
     // D = 256: the state copies of more than 64 columns do not fit the LDS
     const int hi = (D == 256) ? 64 : D;

@@ -340,6 +340,8 @@ def test_debug_plan_and_plan_query(lib):
     assert ltn.ltn_attn_query_plan(1, 32, 2048, 96, torch.bfloat16, 0) == (32, 1)
     assert ltn.ltn_attn_query_plan(1, 16, 8192, 96, torch.bfloat16, 1) == (96, 5)
     assert ltn.ltn_attn_query_plan(1, 16, 4096, 96, torch.bfloat16, 1) == (32, 1)
+    assert ltn.ltn_attn_query_plan(1, 80, 4096, 96, torch.bfloat16, 0) == (32, 1)     # 10 chains x 3 slices per XCD
+    assert ltn.ltn_attn_query_plan(1, 82, 4096, 96, torch.bfloat16, 0) == (96, 1)     # 11 would not fit its 32 units
     try:
         ltn.ltn_attn_set_debug_plan(32, 3)
         assert ltn.ltn_attn_query_plan(4, 32, 8192, 128, torch.bfloat16, 0) == (32, 3)
