@@ -138,4 +138,29 @@ __device__ __forceinline__ void map_workgroup(int wg, int per_chain, int chains,
     }
 }
 
+// The same dealing for a number of chains that is no multiple of 8: the launch is padded to
+// 8 * ceil(chains / 8) chain slots and the workgroups of the empty ones leave at once.  That
+// puts ceil(chains / 8) * per_chain workgroups on the first XCDs, so it is used only while
+// those fit an XCD's 32 compute units (xcd_ids_fit); otherwise ids stay chain-major.
+inline bool xcd_ids_fit(long long chains, int per_chain) {
+    return per_chain > 1 && ((chains & 7) == 0 || (chains + 7) / 8 * per_chain <= 32);
+}
+inline long long launch_chain_slots(long long chains, int per_chain) {
+    return xcd_ids_fit(chains, per_chain) ? (chains + 7) / 8 * 8 : chains;
+}
+// xcd_ids: xcd_ids_fit(chains, per_chain), computed by the host.  False: the workgroup is a
+// padding one and has nothing to do.
+__device__ __forceinline__ bool map_workgroup_padded(int wg, int per_chain, int chains, int xcd_ids,
+                                                     int& chain, int& within) {
+    if (xcd_ids) {
+        const int xcd = wg & 7, slot = wg >> 3;
+        chain = (slot / per_chain) * 8 + xcd;
+        within = slot % per_chain;
+    } else {
+        chain = wg / per_chain;
+        within = wg % per_chain;
+    }
+    return chain < chains;
+}
+
 }  // namespace ltn

@@ -770,14 +770,14 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
 }
 
 template <int D, int DV, int DC, int MODE, int DR>
-__device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int wg, char* smem, unsigned lds0,
-                                          int wave, int lane) {
+__device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int xcd_ids, int wg, char* smem,
+                                          unsigned lds0, int wave, int lane) {
     constexpr bool GATED = MODE == kGated;
     // (chain, segment) pairs are dealt to workgroups like chains; with one segment per
     // chain the pair index is the chain index
     int vchain, within;
-    map_workgroup(wg, pb.count * nsplit, pb.chains * pb.segs, vchain, within);
-    if (pb.pairs_first && pb.count == 3 && nsplit == 1 && ((pb.chains * pb.segs) & 7) == 0) {
+    bool mine = map_workgroup_padded(wg, pb.count * nsplit, pb.chains * pb.segs, xcd_ids, vchain, within);
+    if (pb.pairs_first && pb.count == 3 && nsplit == 1 && xcd_ids) {
         // Backward at full width: passes 0 and 1 of a chain walk the token axis together and
         // share two operands, pass 2 walks the other way.  Ids: all (pass 0, pass 1) pairs
         // first, a chain's pair side by side on one XCD, then every pass 2.  With more
@@ -785,7 +785,7 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
         // rounds are filled with pass-2 workgroups, which share nothing with anyone
         // (measured on MI355X, 96..256 chains: 0..3 % faster than chain-major ids when backward
         // launches follow each other, no different when they alternate with forward launches).
-        const int nch = pb.chains * pb.segs;
+        const int nch = (pb.chains * pb.segs + 7) / 8 * 8;       // chain slots of the launch
         const int xcd = wg & 7, slot = wg >> 3;
         if (wg < 2 * nch) {
             within = slot & 1;
@@ -794,7 +794,9 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
             within = 2;
             vchain = (slot - (nch >> 2)) * 8 + xcd;
         }
+        mine = vchain < pb.chains * pb.segs;
     }
+    if (!mine) return;                     // a padding workgroup: the whole workgroup leaves before any barrier
     const int chain = vchain / pb.segs;
     const int seg = vchain - chain * pb.segs;
     if (MODE == kStateOnly && seg + 1 == pb.segs && !pb.need_last) return;   // nobody consumes this end state
@@ -882,11 +884,11 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int w
 
 template <int D, int DV, int MODE, int DC = D, int DR = D>
 __global__ __launch_bounds__(kThreads)
-void pass_bf16_kernel(const PassBatch pb, const int nsplit) {
+void pass_bf16_kernel(const PassBatch pb, const int nsplit, const int xcd_ids) {
     __shared__ __attribute__((aligned(1024))) char smem[Cfg<D, DV>::PASS_TOTAL];
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: role dispatch is a uniform branch
-    pass_body<D, DV, DC, MODE, DR>(pb, nsplit, blockIdx.x, smem, lds_address(smem), wave, tid & 63);
+    pass_body<D, DV, DC, MODE, DR>(pb, nsplit, xcd_ids, blockIdx.x, smem, lds_address(smem), wave, tid & 63);
 }
 
 template <int D, int DV, int MODE = kPlain, int DC = D, int DR = D>
@@ -895,9 +897,12 @@ hipError_t launch_t(const PassBatch& pb, hipStream_t stream) {
     static_assert(DC == D || MODE != kGated || (D == 128 && DC == 96 && DR == 96 && DV == 96),
                   "unequal widths: no gated epilogue (heads of 96 features computed as 128 have one)");
     const int nsplit = DC / DV;
-    const long long wgs = (long long)pb.chains * pb.segs * pb.count * nsplit;
+    const long long nch = (long long)pb.chains * pb.segs;
+    const int per_chain = pb.count * nsplit;
+    const long long wgs = launch_chain_slots(nch, per_chain) * per_chain;
     if (wgs <= 0 || wgs > 0x7fffffffLL || pb.segs < 1) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((pass_bf16_kernel<D, DV, MODE, DC, DR>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit);
+    hipLaunchKernelGGL((pass_bf16_kernel<D, DV, MODE, DC, DR>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, pb, nsplit,
+                       (int)xcd_ids_fit(nch, per_chain));
     return hipGetLastError();
 }
 
