@@ -44,9 +44,14 @@ size_t esize_of(ltn_dtype dtype) { return dtype == LTN_BF16 ? 2 : 4; }
 // that chain's score tiles and re-reads its first two operands through L2, and a compute
 // unit holds one workgroup: the split is the deepest one whose workgroups still fit one
 // round of the 256 compute units; when even full-width slices need more than one round,
-// full width (fewest re-reads).  Measured on MI355X for 8..256 chains, forward and
-// backward.  ltn_attn_set_debug_plan (test only) overrides the choice.
-int pick_dv(long long chain_passes, int D, ltn_dtype dtype, int blk) {
+// full width (fewest re-reads).  Among the splits that fit one round, bf16 takes the deepest
+// whose workgroups of one chain can be given ids on one XCD (count passes x slices per chain,
+// ltn::xcd_ids_fit): slices that meet in one L2 beat a deeper split that does not (20 chains,
+// backward: 32-column slices 0.101 ms, 64-column 0.066 ms; 42 chains: 64-column 0.120 ms,
+// full width 0.110 ms).  Measured on MI355X for 8..256 chains, forward and backward.
+// ltn_attn_set_debug_plan (test only) overrides the choice.
+// chain_passes = chains (x segments) x count; count = passes per chain in the launch.
+int pick_dv(long long chain_passes, int D, ltn_dtype dtype, int blk, int count = 1) {
     if (D == 96) {                         // three 32-column slices, or all 96 columns in one workgroup
         if (dtype != LTN_BF16) return 32;
         if (const int v = g_debug_dv.load(std::memory_order_relaxed)) {
@@ -63,8 +68,13 @@ int pick_dv(long long chain_passes, int D, ltn_dtype dtype, int blk) {
     if (const int v = g_debug_dv.load(std::memory_order_relaxed)) {
         if ((v == D || v == D / 2 || v == D / 4 || v == D / 8) && v >= lo && v <= hi) return v;
     }
-    for (int dv = lo; dv <= hi; dv *= 2)
-        if (chain_passes * (D / dv) <= 256) return dv;
+    int fits = 0;
+    for (int dv = lo; dv <= hi; dv *= 2) {
+        if (chain_passes * (D / dv) > 256) continue;
+        if (dtype != LTN_BF16 || count * (D / dv) == 1 || ltn::xcd_ids_fit(chain_passes / count, count * (D / dv))) return dv;
+        if (!fits) fits = dv;
+    }
+    if (fits) return fits;
     // More than one round even at full width.  The fp32 matrix-core kernel is bound by its MFMA
     // and LDS latencies, and two of its half-width workgroups fit one compute unit (76 KB of LDS
     // each), so half width runs 5-7 % faster there (measured: 1B and 7B shapes, backward); the
@@ -200,7 +210,7 @@ ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void*
                                        (pb.pairs_first && pb.count == 3) ? pb.chains : 0);
     pb.segs = 1;
     if (plan.segs == 1) {
-        const int dv = full_width ? D : pick_dv(chain_passes, D, dtype, blk);
+        const int dv = full_width ? D : pick_dv(chain_passes, D, dtype, blk, pb.count);
         const hipError_t e = (dtype == LTN_BF16) ? ltn::launch_pass_bf16(pb, D, dv, stream)
                                                  : ltn::launch_pass_f32(pb, D, dv, blk, stream);
         return e == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
@@ -234,7 +244,7 @@ ltn_status run_passes(ltn::PassBatch& pb, int D, int blk, ltn_dtype dtype, void*
         main.p[i].state_in = states + i * per_pass;
         main.p[i].state_out = nullptr;
     }
-    const int dv = full_width ? D : pick_dv(chain_passes * plan.segs, D, dtype, blk);
+    const int dv = full_width ? D : pick_dv(chain_passes * plan.segs, D, dtype, blk, pb.count);
     return ltn::launch_pass_bf16(main, D, dv, stream) == hipSuccess ? LTN_OK : LTN_ERR_LAUNCH;
 }
 
@@ -284,7 +294,7 @@ ltn_status ltn_attn_query_plan(int Bt, int H, long long N, int D, ltn_dtype dtyp
     const long long chain_passes = (long long)Bt * H * (call == 1 ? 3 : 1);
     const SegPlan plan = pick_segments(chain_passes, N, D, dtype, call == 2, call == 1 ? (long long)Bt * H : 0);
     *segs_out = plan.segs;
-    *dv_out = (call == 2) ? D : pick_dv(chain_passes * plan.segs, D, dtype, ltn_attn_pick_block(D, dtype));
+    *dv_out = (call == 2) ? D : pick_dv(chain_passes * plan.segs, D, dtype, ltn_attn_pick_block(D, dtype), call == 1 ? 3 : 1);
     return LTN_OK;
 }
 

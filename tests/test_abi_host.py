@@ -340,6 +340,11 @@ def test_debug_plan_and_plan_query(lib):
     assert ltn.ltn_attn_query_plan(1, 32, 2048, 96, torch.bfloat16, 0) == (32, 1)
     assert ltn.ltn_attn_query_plan(1, 16, 8192, 96, torch.bfloat16, 1) == (96, 5)
     assert ltn.ltn_attn_query_plan(1, 16, 4096, 96, torch.bfloat16, 1) == (32, 1)
+    # slices of a chain share an XCD's L2 only when an XCD's share of workgroups fits its 32 units:
+    # 20 chains backward, 3 passes x 4 slices x 3 chains per XCD = 36 -> two slices per pass instead
+    assert ltn.ltn_attn_query_plan(1, 20, 4096, 128, torch.bfloat16, 1) == (64, 1)
+    assert ltn.ltn_attn_query_plan(1, 16, 4096, 128, torch.bfloat16, 1) == (32, 1)
+    assert ltn.ltn_attn_query_plan(1, 42, 4096, 128, torch.bfloat16, 1) == (128, 1)
     assert ltn.ltn_attn_query_plan(1, 80, 4096, 96, torch.bfloat16, 0) == (32, 1)     # 10 chains x 3 slices per XCD
     assert ltn.ltn_attn_query_plan(1, 82, 4096, 96, torch.bfloat16, 0) == (96, 1)     # 11 would not fit its 32 units
     try:
