@@ -40,8 +40,8 @@
 //     fewest causal score tiles.  They wait for a block with an exact vmcnt that counts their
 //     own stores in between (VMEM operations of a wave retire in issue order), never for the
 //     stores themselves.  In the register-fed layout (256 features) all four output waves
-//     share the loads; the gated pass keeps them in the state waves (its output waves also
-//     load the gate through the compiler's own wait counts).  LDS rows are unpadded; the 16-byte chunk
+//     share the loads; in the gated pass the gate values are loaded from assembly too, ahead
+//     of the block's tile loads, and counted with them.  LDS rows are unpadded; the 16-byte chunk
 //     index is XOR-swizzled with the row so that row reads, transpose reads
 //     (ds_read_b64_tr_b16, for operands needed "down the token axis") and the state-copy
 //     writes spread over the banks.  Rows past the end of a short last block are fetched
@@ -99,10 +99,6 @@ struct Cfg {
 // state-only sweep of the sequence-parallel form (no outputs: only the segment's end state).
 enum { kPlain = 0, kGated = 1, kStateOnly = 2 };
 
-// Who issues the tile loads: output waves in the plain pass and in the state-only sweep, where
-// they have nothing else to do; the state waves in the gated pass.
-template <int D, int DV, int MODE, int DR>
-constexpr bool kOutFetch = MODE == kPlain || MODE == kStateOnly;
 
 // Register prefetch loads of the AREG output waves are issued from inline assembly and
 // waited for with explicit vmcnt counts: left to the compiler, loads that rotate through
@@ -182,21 +178,16 @@ struct ReadOffs {
 //   token mixer's epilogue (Sec. 3.1.2 Eq. 3 with the SimpleRMSNorm of Sec. 3.1.3 per head),
 //   y = o / sqrt(mean(o^2) + eps) (.) u, is applied before anything is stored; gate/yout are
 //   this lane's addresses in U and Y (same position as out), out may be null.
-template <int D, int DV, int W, int CCOLS, bool GATED = false, int DROW = D>
+//   uq (GATED): the gate values of this lane's token, loads issued by the caller from assembly
+//   before the block's tile loads; GWAIT = the VMEM operations the wave issued after them.
+template <int D, int DV, int W, int CCOLS, bool GATED = false, int DROW = D, int GWAIT = 0>
 __device__ __forceinline__ void output_pass(const char* btile, const char* ctile, const char* scopy,
                                             const Frag (&Af)[D / 32], const OutConsts<W>& k,
                                             const ReadOffs<D, DV, CCOLS>& ro, char* out, bool store,
-                                            const char* gate = nullptr, char* yout = nullptr, float eps = 0.f) {
+                                            u32x4* uq = nullptr, char* yout = nullptr, float eps = 0.f) {
     using C = Cfg<D, DV>;
     constexpr int KS = C::KS, NT = C::NT, RB = C::F::RB, CRB = Swz<CCOLS>::RB;
     static_assert(!GATED || DV == DROW, "the gated epilogue needs complete output rows (DROW features)");
-
-    // gate values of this lane's token: issued first, used last
-    u32x4 uq[GATED ? NT / 2 : 1];
-    if constexpr (GATED) {
-#pragma unroll
-        for (int p = 0; p < NT / 2; ++p) uq[p] = store ? *(const u32x4*)(gate + 64 * p) : u32x4{0, 0, 0, 0};
-    }
 
     // -- transposed scores P^T[key tile kt <= W][own 16 rows]
     f32x4 sacc[W + 1];
@@ -289,6 +280,9 @@ __device__ __forceinline__ void output_pass(const char* btile, const char* ctile
             ss = __uint_as_float(t[0]) + __uint_as_float(t[1]);
         }
         const float rstd = 1.0f / sqrtf(ss * (1.0f / DROW) + eps);
+        wait_dma<GWAIT>();                 // the gate values have arrived
+#pragma unroll
+        for (int p = 0; p < NT / 2; ++p) asm volatile("" : "+v"(uq[p]));
 #pragma unroll
         for (int p = 0; p < NT / 2; ++p) {
             float x[8];
@@ -422,6 +416,23 @@ struct Chain {            // what every wave of the workgroup knows about its pr
 
 // =============================================================== pass body
 
+// "Block blk + 1 has landed" for a wave that issues, per block and in this order, G gate loads,
+// L tile loads (for block blk + PST - 1) and S stores, after PST - 1 blocks' tile loads up front:
+// the operations it issued after that block's loads.
+template <int PST, int L, int S, int G>
+__device__ __forceinline__ void wait_block(int blk) {
+    static_assert(PST >= 2 && PST <= 4, "ring depths");
+    if constexpr (PST == 2) {
+        wait_dma<S>();
+    } else if constexpr (PST == 3) {
+        if (blk == 0) wait_dma<L + S + G>(); else wait_dma<L + 2 * S + G>();
+    } else {
+        if (blk == 0) wait_dma<2 * L + S + G>();
+        else if (blk == 1) wait_dma<2 * L + 2 * S + 2 * G>();
+        else wait_dma<2 * L + 3 * S + 2 * G>();
+    }
+}
+
 template <int D, int DV, int DC, int W, int MODE, int DR>
 __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, unsigned lds0, int lane) {
     using C = Cfg<D, DV>;
@@ -436,11 +447,12 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, un
     // VMEM operations retire in issue order, loads and stores alike, so "block b + 1 has
     // landed" is a vmcnt of exactly the operations issued after its loads: the NT/2 stores of
     // every block since and the loads of the PST - 2 blocks behind it.
-    constexpr bool ISSUER = kOutFetch<D, DV, MODE, DR> && W < C::FW;
+    constexpr bool ISSUER = W < C::FW;
     constexpr bool NOA = SO || C::AREG;              // the A tile is not fetched into LDS
     constexpr int L = ISSUER ? ((NOA ? 1 : 2) * TileDmaU<D>::NI + TileDmaU<C::CW>::NI) / C::FW : 0;   // loads per block, this wave
-    constexpr int S = SO ? 0 : C::NT / 2;                                                           // stores per block, this wave
-    static_assert((C::PST - 2) * L + (C::PST - 1) * S <= 63, "vmcnt field");
+    constexpr int S = SO ? 0 : C::NT / 2;            // stores per block and output tensor, this wave
+    constexpr int G = GATED ? C::NT / 2 : 0;         // gate loads per block, issued before the block's tile loads
+    static_assert((C::PST - 2) * (L + G) + (C::PST - 1) * (GATED ? 2 : 1) * S <= 63, "vmcnt field");
     constexpr long long AROW = DR * 2;
     TileDmaU<D, DR> dab;                              // A and B tiles: same shape, same offsets
     TileDmaU<C::CW, DV> dcc;
@@ -474,17 +486,11 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, un
             }
         }
     };
+    const bool two_outputs = GATED && ch.out;          // the gated pass stores Y and, if asked, O
     auto wait_next = [&](int blk) {        // block blk + 1 has landed (this wave's part)
         if constexpr (ISSUER) {
-            if constexpr (C::PST == 2) {
-                wait_dma<S>();
-            } else if constexpr (C::PST == 3) {
-                if (blk == 0) wait_dma<L + S>(); else wait_dma<L + 2 * S>();
-            } else {
-                if (blk == 0) wait_dma<2 * L + S>();
-                else if (blk == 1) wait_dma<2 * L + 2 * S>();
-                else wait_dma<2 * L + 3 * S>();
-            }
+            if (two_outputs) wait_block<C::PST, L, 2 * S, G>(blk);
+            else wait_block<C::PST, L, S, G>(blk);
         }
     };
     if constexpr (ISSUER) {                // blocks 0 .. PST-2 in flight, block 0 landed
@@ -522,12 +528,20 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, un
     char* po = ch.out ? ch.out + lane_off : nullptr;
     const char* pu = GATED ? ch.gate + lane_off : nullptr;
     char* py = GATED ? ch.y + lane_off : nullptr;
+    u32x4 uq[GATED ? G : 1];
+#pragma unroll
+    for (int p = 0; p < (GATED ? G : 1); ++p) uq[p] = u32x4{0, 0, 0, 0};
 
     __syncthreads();                       // block 0 tiles and the initial state copy are in LDS
     int stage = 0;
     for (int blk = 0; blk < ch.T; ++blk) {
         const bool more = blk + 1 < ch.T;
         const bool row_ok = (16 * W + i16) < ((blk + 1 == ch.T) ? ch.last_valid : kBlock);
+        const long long bo = (long long)blk * step;
+        if constexpr (GATED) {             // gate values of this lane's token: issued first, used last
+#pragma unroll
+            for (int p = 0; p < G; ++p) gload16(uq[p], (more || row_ok) ? pu + bo + 64 * p : (const char*)kZeros);
+        }
         if constexpr (ISSUER) {
             int fs = stage + C::PST - 1;   // stage of block blk + PST - 1 (free since the last barrier)
             if (fs >= C::PST) fs -= C::PST;
@@ -537,12 +551,11 @@ __device__ __forceinline__ void pass_output_wave(const Chain& ch, char* smem, un
         Frag Af[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) Af[ks].u = *(const u32x4*)(st + (16 * W) * C::F::RB + ro.row[ks]);
-        const long long bo = (long long)blk * step;
         // with more blocks to come every lane stores (the count above relies on it)
-        output_pass<D, DV, W, C::CW, GATED, DC>(st + C::BOFF, st + C::COFF,
-                                         smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
-                                         po ? po + bo : nullptr, more || row_ok,
-                                         GATED ? pu + bo : nullptr, GATED ? py + bo : nullptr, ch.eps);
+        output_pass<D, DV, W, C::CW, GATED, DC, L>(st + C::BOFF, st + C::COFF,
+                                            smem + C::P_SB + (blk & 1) * C::SBYTES, Af, k, ro,
+                                            po ? po + bo : nullptr, more || row_ok,
+                                            uq, GATED ? py + bo : nullptr, ch.eps);
         if (more) {
             wait_next(blk);
             __syncthreads();
@@ -663,13 +676,10 @@ __device__ __forceinline__ void areg_output_wave(const Chain& ch, char* smem, un
 // DR: features per token that A and B really have in memory (D, or 96 computed as 128 with
 // the tiles' last columns zero-filled and the state's last rows unused).
 template <int D, int DV, int DC, int MODE, int DR>
-__device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, unsigned lds0, int lane, int u) {
+__device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, int lane, int u) {
     using C = Cfg<D, DV>;
     constexpr int MT = C::MT, NT = C::NT;
     constexpr bool SO = MODE == kStateOnly;          // no published state copies
-    constexpr bool NOA = SO || C::AREG;              // the A tile is not this wave's business
-    constexpr bool OUTF = kOutFetch<D, DV, MODE, DR>;   // output waves run the tile pipeline
-    constexpr long long ROW = DR * 2, CROW = DC * 2;
     const int g = lane >> 4, i16 = lane & 15;
     const int dk0 = u * (D / 4);
     StateConsts<D, DV, C::CW> k;
@@ -693,54 +703,14 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
             }
         }
 
-    // tile pipeline: block b lives in ring stage b % PST
-    const long long rs = ch.rev ? -ROW : ROW;        // byte stride between consecutive block rows
-    const long long crs = ch.rev ? -CROW : CROW;
-    const long long step = kBlock * rs, cstep = kBlock * crs;
-    const char* pa0 = ch.a + (ch.rev ? (ch.N - 1) * ROW : 0);
-    const char* pb0 = ch.b + (ch.rev ? (ch.N - 1) * ROW : 0);
-    const char* pc0 = ch.c + (ch.rev ? (ch.N - 1) * CROW : 0);
-    TileDma<D, DR> db;                               // A and B tiles: same shape, same offsets
-    TileDma<C::CW, DV> dc;
-    db.init(u, lane, rs);
-    dc.init(u, lane, crs);
-    constexpr int kLoads = (NOA ? 1 : 2) * TileDma<D>::PER_WAVE + TileDma<C::CW, DV>::PER_WAVE;   // per block, per wave
-    static_assert((C::PST - 2) * kLoads <= 63, "vmcnt field");
-    auto valid_of = [&](int b) { return (b + 1 == ch.T) ? ch.last_valid : kBlock; };
-    // complete blocks: scalar base (the block's lowest-address row) + per-lane 32-bit offsets
-    const long long lowadj = ch.rev ? -(long long)(kBlock - 1) * ROW : 0;
-    const long long clowadj = ch.rev ? -(long long)(kBlock - 1) * CROW : 0;
-    auto fetch = [&](int b, int stage) {
-        if constexpr (OUTF) return;
-        b = b < ch.T ? b : ch.T - 1;       // past the end: re-read the last block into a free stage
-        const int valid = valid_of(b);
-        const unsigned lds = lds0 + (unsigned)(stage * C::PSTAGE);
-        if (TileDma<D, DR>::FAST && valid == kBlock) {
-            if constexpr (TileDma<D, DR>::FAST) {
-                if constexpr (!NOA) db.issue_full(pa0 + (long long)b * step + lowadj, lds, u);
-                db.issue_full(pb0 + (long long)b * step + lowadj, lds + C::BOFF, u);
-                dc.issue_full(pc0 + (long long)b * cstep + clowadj, lds + C::COFF, u);
-            }
-            return;
-        }
-        if constexpr (!NOA) db.issue(pa0 + (long long)b * step, lds, u, valid);
-        db.issue(pb0 + (long long)b * step, lds + C::BOFF, u, valid);
-        dc.issue(pc0 + (long long)b * cstep, lds + C::COFF, u, valid);
-    };
-
-    // prologue: blocks 0 .. PST-2 in flight, block 0 landed; initial state copy published
-#pragma unroll
-    for (int b = 0; b < C::PST - 1; ++b) fetch(b, b);
+    // prologue: the initial state copy published (the output waves run the tile pipeline:
+    // block b lives in ring stage b % PST)
     if constexpr (!SO) publish_state<D, DV, C::CW>(st, smem + C::P_SB, k);
-    if constexpr (!OUTF) wait_dma<(C::PST - 2) * kLoads>();
     __syncthreads();
 
     int stage = 0;                                   // stage of block blk
     for (int blk = 0; blk < ch.T; ++blk) {
         const bool more = blk + 1 < ch.T;
-        int fs = stage + C::PST - 1;                 // stage of block blk + PST - 1 (free since the last barrier)
-        if (fs >= C::PST) fs -= C::PST;
-        fetch(blk + C::PST - 1, fs);
         if (!more) {
             if (!ch.state_out) break;                // the last update only feeds the returned state
             if (ch.last_valid != kBlock) k.set_block_len(ch.lam, ch.last_valid, lane);
@@ -749,12 +719,10 @@ __device__ __forceinline__ void pass_state_wave(const Chain& ch, char* smem, uns
         state_update<D, DV, C::CW>(st, tb + C::BOFF, tb + C::COFF, k);
         if (more) {
             if constexpr (!SO) publish_state<D, DV, C::CW>(st, smem + C::P_SB + ((blk + 1) & 1) * C::SBYTES, k);
-            if constexpr (!OUTF) wait_dma<(C::PST - 2) * kLoads>();   // block blk+1 has landed (this wave's part)
             __syncthreads();
         }
         stage = (stage + 1 == C::PST) ? 0 : stage + 1;
     }
-    if constexpr (!OUTF) wait_dma<0>();              // nothing may land in LDS after this workgroup is gone
 
     if (ch.state_out) {
 #pragma unroll
@@ -830,7 +798,7 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int x
     ch.rev = P.rev;
     ch.lam = pb.decay[chain % pb.H];
 
-    if constexpr (kOutFetch<D, DV, MODE, DR> && (DR != D || Cfg<D, DV>::CW != DV)) {
+    if constexpr (DR != D || Cfg<D, DV>::CW != DV) {
         // Tiles wider than the tensors' rows: their loads leave the surplus chunks alone, which
         // hold zeros from here on (cleared once, in every ring stage, before the first load).
         using C = Cfg<D, DV>;
@@ -867,7 +835,7 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int x
                     else areg_output_wave<D, DV, DC, 3>(ch, smem, lds0, lane);
                 }
                 break;
-            default: pass_state_wave<D, DV, DC, MODE, DR>(ch, smem, lds0, lane, wave - 4); break;
+            default: pass_state_wave<D, DV, DC, MODE, DR>(ch, smem, lane, wave - 4); break;
         }
     } else {
         switch (wave) {
@@ -875,7 +843,7 @@ __device__ __forceinline__ void pass_body(const PassBatch& pb, int nsplit, int x
             case 1: pass_output_wave<D, DV, DC, 1, MODE, DR>(ch, smem, lds0, lane); break;
             case 2: pass_output_wave<D, DV, DC, 2, MODE, DR>(ch, smem, lds0, lane); break;
             case 3: pass_output_wave<D, DV, DC, 3, MODE, DR>(ch, smem, lds0, lane); break;
-            default: pass_state_wave<D, DV, DC, MODE, DR>(ch, smem, lds0, lane, wave - 4); break;
+            default: pass_state_wave<D, DV, DC, MODE, DR>(ch, smem, lane, wave - 4); break;
         }
     }
 }
