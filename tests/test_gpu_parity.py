@@ -14,7 +14,7 @@ import torch
 import paper_2307_14995_amd as ltn
 from paper_2307_14995_amd import synth
 from oracle import ltn_oracle as orc
-from _helpers import TOL, TOL_ROW, check, check_rows, decays, dev, force_dv, force_plan, force_segs, gpu
+from _helpers import TOL, TOL_ROW, check, check_rows, decays, dev, force_dv, force_plan, force_segs, gpu, mixed_decay
 
 pytestmark = pytest.mark.gpu
 
@@ -158,6 +158,29 @@ def test_bf16_backward_ragged(D, N):
                 outs = ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay))
             for n, x, r in zip(("dQ", "dK", "dV"), outs, refs):
                 check(f"{n}[{name},dv={dv}]", x, r, 1e-2)
+
+
+@pytest.mark.parametrize("chains,D", [(9, 128), (20, 128), (42, 128), (13, 64), (82, 96), (9, 256), (260, 64)])
+def test_bf16_chain_counts_off_the_multiples_of_eight(chains, D):
+    """Chain counts that are no multiple of 8: the launch is padded to whole groups of 8 chain
+    slots while an XCD's share of workgroups fits its compute units (9 .. 42 chains here), else
+    ids stay chain-major (82 chains of three slices, 260 chains); the empty slots' workgroups must
+    touch nothing, every chain must be computed once, at every slice width."""
+    Bt, H, N = 1, chains, 200
+    q, k, v = synth.make_qkv(Bt, H, N, D, torch.bfloat16, 3100 + chains)
+    g = synth.make_do(Bt, H, N, D, torch.bfloat16, 3100 + chains)
+    decay = mixed_decay(H)
+    ref, ref_kv = orc.fwd_recurrent(q, k, v, decay, return_state=True)
+    refs = orc.bwd_recurrent(q, k, v, g, decay)
+    widths = {64: (0, 32, 64), 96: (0, 32, 96), 128: (0, 32, 64, 128), 256: (0, 32, 64)}[D]
+    for dv in widths:
+        with force_plan(dv, 1 if dv else 0):
+            o, kv = ltn.ltn_attn_fwd(*gpu(q, k, v, decay), return_state=True)
+            grads = ltn.ltn_attn_bwd(*gpu(q, k, v, g, decay))
+        check(f"o[dv={dv}]", o, ref, 1e-2)
+        check(f"kv[dv={dv}]", kv, ref_kv, 1e-2)
+        for n, x, r in zip(("dQ", "dK", "dV"), grads, refs):
+            check(f"{n}[dv={dv}]", x, r, 1e-2)
 
 
 def test_bf16_backward_probe_reads_back_scores():
