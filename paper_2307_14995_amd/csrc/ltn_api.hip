@@ -57,8 +57,8 @@ int pick_dv(long long chain_passes, int D, ltn_dtype dtype, int blk, int count =
         if (const int v = g_debug_dv.load(std::memory_order_relaxed)) {
             if (v == 32 || v == 96) return v;
         }
-        // three slices per chain pass stay on one XCD: 10 chain passes per XCD of 32 units at most
-        return (chain_passes + 7) / 8 * 3 <= 32 ? 32 : 96;
+        // three slices per pass while a chain's workgroups can share an XCD within one round
+        return (chain_passes * 3 <= 256 && ltn::xcd_ids_fit(chain_passes / count, count * 3)) ? 32 : 96;
     }
     // D = 256: the state copies of more than 64 columns do not fit the LDS
     const int hi = (D == 256) ? 64 : D;
@@ -163,6 +163,7 @@ SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtyp
             // a pair's three slices on one XCD: an XCD's share must not exceed its units (11
             // pairs per XCD -- 252 workgroups -- ran 30 % slower than 10).
             while (want > 1 && (chain_passes * want + 7) / 8 * 3 > 32) --want;
+            if (want < 3) want = 1;
             // Heads of 96 features also have one 96-column workgroup per chain and segment
             // (pick_dv takes it when three 32-column slices each would need more than one round).
             // From 12 chain passes on, cutting for that width pays from 8 segments on -- of at
