@@ -99,7 +99,9 @@ struct Swz {
     __device__ static __forceinline__ int off(int r, int c) { return r * RB + ((c ^ key(r)) << 4); }
 };
 
-// Direct global -> LDS fetch of one 64-row tile of COLS columns by four waves (u = 0..3).
+// Direct global -> LDS fetch of one 64-row tile of COLS columns by four waves (u = 0..3),
+// every lane with a full 64-bit address (the quadratic comparison kernels; the pass kernel uses
+// TileDmaU below).
 // Wave u issues the wave-wide loads j = u, u+4, ...; load j fills LDS slots 64j .. 64j+63
 // (slot s = row s / CPR, chunk position s % CPR).  `src[i]` is this lane's byte offset
 // from the block's first row for its i-th load; `row[i]` the tile row it fetches.
@@ -110,13 +112,10 @@ struct TileDma {
     static_assert(Swz<COLS>::NI % 4 == 0, "every state wave issues the same number of loads");
     static_assert(REAL % 8 == 0 && REAL <= COLS, "whole 16-byte chunks");
     static constexpr int PER_WAVE = Swz<COLS>::NI / 4;
-    static constexpr bool FAST = REAL == COLS;   // complete blocks can take the scalar-base form
     long long src[PER_WAVE];
     int row[PER_WAVE];
-    unsigned low[PER_WAVE];   // the same position as a byte offset from the block's lowest-address row
     __device__ __forceinline__ void init(int u, int lane, long long row_stride) {
         using S = Swz<COLS>;
-        const long long pitch = row_stride < 0 ? -row_stride : row_stride;
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int slot = 64 * (u + 4 * i) + lane;
@@ -124,16 +123,7 @@ struct TileDma {
             const int c = (slot % S::CPR) ^ S::key(r);
             row[i] = (REAL < COLS && c * 8 >= REAL) ? kBlock : r;
             src[i] = (long long)r * row_stride + c * 16;
-            low[i] = (unsigned)((row_stride < 0 ? kBlock - 1 - r : r) * pitch + c * 16);
         }
-    }
-    // A complete block (all kBlock rows valid, all columns real): `lowest` is the wave-uniform
-    // global address of the block's lowest-address row (its row 0, or its last row on a
-    // reversed token axis), plus the slice's column offset.
-    __device__ __forceinline__ void issue_full(const char* lowest, unsigned lds, int u) const {
-        static_assert(FAST, "tiles with zero-filled columns go through issue()");
-#pragma unroll
-        for (int i = 0; i < PER_WAVE; ++i) dma16s(lds + 1024u * (unsigned)(u + 4 * i), lowest, low[i]);
     }
     // base: global address of the block's row 0 (plus the slice's column offset);
     // lds: LDS byte address of the tile; rows >= valid come from the zero buffer
