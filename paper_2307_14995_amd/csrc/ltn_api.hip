@@ -113,8 +113,10 @@ ltn_status check_common(int Bt, int H, long long N, int D, int block, ltn_dtype 
 // extra read of B and C (the state-only sweep) and two more launches.  Measured on MI355X
 // (2 .. 64 chains, N = 2048 .. 65536, forward and backward, every segment count): pays when a
 // chain can be cut at least 8 ways into segments of at least 512 tokens without exceeding one
-// round of compute units, and from 5 ways on when the segments are at least 2048 tokens long
-// (36 .. 48 passes of long chains, e.g. the backward of 12 .. 16 chains); never otherwise.
+// round of compute units, from 5 ways on when the segments are at least 1024 tokens long
+// (33 .. 51 passes of long chains: the forward of 36 .. 48 chains at N = 8192 runs 17-29 % faster
+// cut 5 .. 7 ways, the backward of 12 .. 16 chains 11-16 %), and 4 ways in the backward of about
+// 20 chains with segments of at least 2048 tokens (13-19 %); never otherwise.
 // bf16 kernels only.  Heads of 256 features always need four 64-column workgroups per chain
 // and segment, heads of 96 three of 32; there the form pays from 3 segments of at least 512
 // tokens on (measured: 2 .. 32 chains, N = 2048 .. 32768, forward and backward; heads of 96
@@ -182,8 +184,12 @@ SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtyp
                 }
             }
         }
-    } else if (want < 8 && !(want >= 5 && N / want >= 2048)) {
-        want = 1;
+    } else if (want < 8) {
+        // 5 .. 7 ways: segments of at least 1024 tokens; 4 ways: the backward alone, segments of at
+        // least 2048 tokens, when its (dV, dK) pairs can sit side by side (chains x 4 a multiple of 8)
+        const bool few = want >= 5 && N / want >= 1024;
+        const bool four = want == 4 && paired_chains > 0 && (paired_chains * 4) % 8 == 0 && N / want >= 2048;
+        if (!few && !four) want = 1;
     }
     if (paired_chains > 0 && want >= 6 && whole_rows) {
         // The backward's workgroup ids pair a chain's (dV, dK) passes on one XCD only when

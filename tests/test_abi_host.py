@@ -391,7 +391,15 @@ def test_workspace_query(lib):
     assert ltn.ltn_attn_workspace_bytes(1, 64, 16384, D, 0, torch.bfloat16, 0) == 0  # 4 segments at most: not worth it
     # 5 .. 7 segments only when they are long: the backward of 16 chains (48 passes)
     assert ltn.ltn_attn_workspace_bytes(1, 16, 16384, D, 0, torch.bfloat16, 1) == 3 * 16 * 5 * D * D * 4
-    assert ltn.ltn_attn_workspace_bytes(1, 16, 8192, D, 0, torch.bfloat16, 1) == 0
+    assert ltn.ltn_attn_workspace_bytes(1, 16, 8192, D, 0, torch.bfloat16, 1) == 3 * 16 * 5 * D * D * 4   # 1638 tokens each
+    assert ltn.ltn_attn_workspace_bytes(1, 16, 4096, D, 0, torch.bfloat16, 1) == 0     # 819 tokens each: too short
+    assert ltn.ltn_attn_query_plan(1, 40, 8192, D, torch.bfloat16, 0) == (128, 6)      # forward of 40 chains: 6 ways
+    assert ltn.ltn_attn_query_plan(1, 40, 4096, D, torch.bfloat16, 0) == (32, 1)
+    # 4 ways: the backward alone, chains x 4 a multiple of 8, segments of at least 2048 tokens
+    assert ltn.ltn_attn_query_plan(1, 20, 8192, D, torch.bfloat16, 1) == (128, 4)
+    assert ltn.ltn_attn_query_plan(1, 21, 8192, D, torch.bfloat16, 1) == (64, 1)
+    assert ltn.ltn_attn_query_plan(1, 20, 4096, D, torch.bfloat16, 1) == (64, 1)
+    assert ltn.ltn_attn_query_plan(1, 60, 8192, D, torch.bfloat16, 0) == (32, 1)
     assert ltn.ltn_attn_workspace_bytes(0, 2, 8192, D, 0, torch.bfloat16, 0) == 0
     # the gated forward keeps full-width slices, so it cuts chains sooner (from 4 segments on, or 2 long ones)
     # (8 segments of 512 tokens, as its other form, plain forward + gate kernel, takes: room for either)
