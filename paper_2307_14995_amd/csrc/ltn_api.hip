@@ -187,8 +187,10 @@ SegPlan pick_segments(long long chain_passes, long long N, int D, ltn_dtype dtyp
     } else if (want < 8) {
         // 5 .. 7 ways: segments of at least 1024 tokens; 4 ways: the backward alone, segments of at
         // least 2048 tokens, when its (dV, dK) pairs can sit side by side (chains x 4 a multiple of 8)
-        const bool few = want >= 5 && N / want >= 1024;
-        const bool four = want == 4 && paired_chains > 0 && (paired_chains * 4) % 8 == 0 && N / want >= 2048;
+        // (heads of 64 features, whose blocks cost half as much: 512 and 1024 tokens)
+        const long long few_len = D == 64 ? 512 : 1024;
+        const bool few = want >= 5 && N / want >= few_len;
+        const bool four = want == 4 && paired_chains > 0 && (paired_chains * 4) % 8 == 0 && N / want >= 2 * few_len;
         if (!few && !four) want = 1;
     }
     if (paired_chains > 0 && want >= 6 && whole_rows) {
